@@ -1,0 +1,200 @@
+"""ctypes binding of the C oracle (kvl_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this.  It never touches the HIP library and the HIP library never touches it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+from typing import Iterator, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kvl_oracle.c")
+_LIB = os.path.join(_HERE, "libkvl_oracle.so")
+
+OK, E_ARG, E_TABLE, E_BLOCK, E_DUP = 0, -1, -2, -3, -4
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile kvl_oracle.c with gcc into libkvl_oracle.so beside it."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-fPIC",
+                               "-shared", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _bind(path: str):
+    lib = C.CDLL(path)
+    u32p, i32pp, u8pp = C.POINTER(C.c_uint32), C.POINTER(C.POINTER(C.c_int32)), C.POINTER(C.c_void_p)
+    lib.kvo_total_hit_tokens.restype = C.c_uint64
+    lib.kvo_total_hit_tokens.argtypes = [C.c_uint32, u32p]
+    lib.kvo_payload_bytes.restype = C.c_uint64
+    lib.kvo_payload_bytes.argtypes = [C.c_uint32, u32p, C.c_uint32, u32p]
+    lib.kvo_check.restype = C.c_int
+    lib.kvo_check.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, u32p, u32p, u32p, i32pp, C.c_int]
+    lib.kvo_pack.restype = C.c_int
+    lib.kvo_pack.argtypes = [C.c_uint32, C.c_uint32, u32p, C.c_uint32, u32p, i32pp,
+                             u8pp, C.c_void_p, C.c_uint32, C.c_uint32]
+    lib.kvo_unpack.restype = C.c_int
+    lib.kvo_unpack.argtypes = [C.c_uint32, C.c_uint32, u32p, C.c_uint32, u32p, i32pp,
+                               C.c_void_p, u8pp, C.c_uint32, C.c_uint32]
+    return lib
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = _bind(build())
+    return _lib
+
+
+class use_library:
+    """Context manager for tests that plant a mistake in a copy of the C source:
+    route every call through another build of the oracle, then restore."""
+
+    def __init__(self, path: str):
+        self.path = path
+
+    def __enter__(self):
+        global _lib
+        self.saved = _load()
+        _lib = _bind(self.path)
+        return self
+
+    def __exit__(self, *exc):
+        global _lib
+        _lib = self.saved
+        return False
+
+
+def _u32(a) -> Tuple[np.ndarray, "C._Pointer"]:
+    arr = np.ascontiguousarray(np.asarray(a, dtype=np.uint32))
+    return arr, arr.ctypes.data_as(C.POINTER(C.c_uint32))
+
+
+def _tables(tables: Sequence[np.ndarray]):
+    keep = [np.ascontiguousarray(np.asarray(t, dtype=np.int32)) for t in tables]
+    arr = (C.POINTER(C.c_int32) * max(1, len(keep)))()
+    for i, t in enumerate(keep):
+        arr[i] = t.ctypes.data_as(C.POINTER(C.c_int32)) if t.size else None
+    return keep, arr
+
+
+def _planes(planes: Sequence[np.ndarray], writable: bool):
+    for p in planes:
+        if p.dtype != np.uint8 or not p.flags["C_CONTIGUOUS"]:
+            raise TypeError("pool planes must be contiguous uint8 arrays")
+        if writable and not p.flags["WRITEABLE"]:
+            raise TypeError("pool plane is read-only")
+    arr = (C.c_void_p * max(1, len(planes)))()
+    for i, p in enumerate(planes):
+        arr[i] = p.ctypes.data
+    return arr
+
+
+def total_hit_tokens(hit) -> int:
+    h, hp = _u32(hit)
+    return int(_load().kvo_total_hit_tokens(h.size, hp))
+
+
+def payload_bytes(hit, row_bytes) -> int:
+    """Bytes of one layer's transfer buffer (all planes)."""
+    h, hp = _u32(hit)
+    rb, rbp = _u32(row_bytes)
+    return int(_load().kvo_payload_bytes(h.size, hp, rb.size, rbp))
+
+
+def check(block_tokens: int, pool_blocks: int, hit, app, tables, scatter: bool) -> int:
+    h, hp = _u32(hit)
+    a, ap = _u32(app)
+    keep, tp = _tables(tables)
+    ln, lp = _u32([t.size for t in keep])
+    return int(_load().kvo_check(block_tokens, pool_blocks, h.size, hp, ap, lp, tp, int(scatter)))
+
+
+def _ranges(n_req: int, threads: int) -> List[Tuple[int, int]]:
+    threads = max(1, min(threads, n_req))
+    cuts = np.linspace(0, n_req, threads + 1).astype(int)
+    return [(int(cuts[i]), int(cuts[i + 1])) for i in range(threads) if cuts[i] < cuts[i + 1]]
+
+
+def pack(block_tokens: int, row_bytes, hit, tables, pool_planes: Sequence[np.ndarray],
+         xfer: Optional[np.ndarray] = None, threads: int = 1) -> np.ndarray:
+    """Gather the hit rows of every request into a dense transfer buffer."""
+    lib = _load()
+    h, hp = _u32(hit)
+    rb, rbp = _u32(row_bytes)
+    keep, tp = _tables(tables)
+    pp = _planes(pool_planes, writable=False)
+    n = payload_bytes(h, rb)
+    if xfer is None:
+        xfer = np.empty(n, dtype=np.uint8)
+    if xfer.dtype != np.uint8 or xfer.size < n or not xfer.flags["C_CONTIGUOUS"]:
+        raise ValueError("transfer buffer too small or not contiguous uint8")
+
+    def run(rng):
+        rc = lib.kvo_pack(block_tokens, rb.size, rbp, h.size, hp, tp, pp,
+                          xfer.ctypes.data, rng[0], rng[1])
+        if rc != OK:
+            raise RuntimeError(f"kvo_pack failed: {rc}")
+
+    ranges = _ranges(h.size, threads) if h.size else []
+    if len(ranges) <= 1:
+        run((0, h.size))
+    else:
+        with ThreadPoolExecutor(len(ranges)) as ex:
+            list(ex.map(run, ranges))
+    return xfer
+
+
+def unpack(block_tokens: int, row_bytes, hit, tables, xfer: np.ndarray,
+           pool_planes: Sequence[np.ndarray], threads: int = 1) -> None:
+    """Scatter a dense transfer buffer into the hit rows of a paged pool, in place."""
+    lib = _load()
+    h, hp = _u32(hit)
+    rb, rbp = _u32(row_bytes)
+    keep, tp = _tables(tables)
+    pp = _planes(pool_planes, writable=True)
+    n = payload_bytes(h, rb)
+    if xfer.dtype != np.uint8 or xfer.size < n or not xfer.flags["C_CONTIGUOUS"]:
+        raise ValueError("transfer buffer too small or not contiguous uint8")
+
+    def run(rng):
+        rc = lib.kvo_unpack(block_tokens, rb.size, rbp, h.size, hp, tp,
+                            xfer.ctypes.data, pp, rng[0], rng[1])
+        if rc != OK:
+            raise RuntimeError(f"kvo_unpack failed: {rc}")
+
+    ranges = _ranges(h.size, threads) if h.size else []
+    if len(ranges) <= 1:
+        run((0, h.size))
+    else:
+        with ThreadPoolExecutor(len(ranges)) as ex:
+            list(ex.map(run, ranges))
+
+
+def stream_layers(block_tokens: int, row_bytes, hit, tables, host_layers: Sequence[np.ndarray],
+                  n_layers: int, dev_slots: Sequence[Sequence[np.ndarray]]
+                  ) -> Iterator[Tuple[int, int, Sequence[np.ndarray]]]:
+    """Layer-wise load (Section 4.1: the hit cache of layer l is brought into
+    the prefill engine's memory before layer l is computed, layer after layer).
+
+    Layer l's transfer buffer is ``host_layers[l mod H]``; it is unpacked into
+    destination slot ``l mod S``.  Yields ``(l, slot, planes)``: the slot's
+    contents as the compute of layer l must see them.
+    """
+    H, S = len(host_layers), len(dev_slots)
+    for l in range(n_layers):
+        s = l % S
+        unpack(block_tokens, row_bytes, hit, tables, host_layers[l % H], dev_slots[s])
+        yield l, s, dev_slots[s]

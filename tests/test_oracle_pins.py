@@ -1,0 +1,363 @@
+"""Pins for the CPU oracle: checks against things other than itself.
+
+The paper prints no worked example for the cache-load path, so the oracle is
+pinned by what the definition (Appendix A.5 layout, Section 4.1 "hit tokens of
+this layer") and plain mathematics fix: an independent per-byte brute force,
+library routines it must reduce to (memcpy, numpy.take), algebraic identities,
+and a closed-form fill.  A last test plants mistakes in copies of the C source
+and demands that the pins notice each of them.
+"""
+import itertools
+import os
+import re
+import subprocess
+import sys
+import tempfile
+
+import numpy as np
+import pytest
+
+import kvl_workloads as W
+import oracle
+from oracle import kvl_oracle as KO
+
+
+# --------------------------------------------------------------------------
+# independent brute force (pure Python, different structure from the C loops)
+# --------------------------------------------------------------------------
+
+def brute_pack(bs, row_bytes, hit, tables, pools):
+    """Walk the *output* byte by byte and ask where it comes from."""
+    T = sum(int(h) for h in hit)
+    out = bytearray()
+    for p, row in enumerate(row_bytes):
+        for g in range(T):                 # g-th hit token of the batch
+            r, t = 0, g
+            while t >= int(hit[r]):        # which request, which token of it
+                t -= int(hit[r])
+                r += 1
+            blk, within = divmod(t, bs)
+            start = (int(tables[r][blk]) * bs + within) * row
+            out += bytes(pools[p][start:start + row])
+    return np.frombuffer(bytes(out), dtype=np.uint8)
+
+
+def brute_hit_mask(bs, row, hit, tables, pool_blocks):
+    """Boolean per pool byte: does a hit token live here?"""
+    m = np.zeros(pool_blocks * bs * row, dtype=bool)
+    for r, h in enumerate(hit):
+        for t in range(int(h)):
+            ph = int(tables[r][t // bs]) * bs + (t % bs)
+            m[ph * row:(ph + 1) * row] = True
+    return m
+
+
+def brute_unpack(bs, row_bytes, hit, tables, xfer, pools):
+    T = sum(int(h) for h in hit)
+    pos = 0
+    for p, row in enumerate(row_bytes):
+        for r, h in enumerate(hit):
+            for t in range(int(h)):
+                ph = int(tables[r][t // bs]) * bs + (t % bs)
+                pools[p][ph * row:(ph + 1) * row] = xfer[pos:pos + row]
+                pos += row
+    assert pos == T * sum(row_bytes)
+
+
+def _o_pack(w, pools, side="src", **kw):
+    s = w.src if side == "src" else w.dst
+    return oracle.pack(w.layout.block_tokens, w.layout.row_bytes, w.hit, s.tables, pools, **kw)
+
+
+def _o_unpack(w, xfer, pools, side="dst", **kw):
+    s = w.src if side == "src" else w.dst
+    oracle.unpack(w.layout.block_tokens, w.layout.row_bytes, w.hit, s.tables, xfer, pools, **kw)
+
+
+TINY = [
+    dict(seed=1, n_requests=3, block_tokens=1, row_bytes=(16,), pool_blocks=40, max_tokens=9),
+    dict(seed=2, n_requests=4, block_tokens=2, row_bytes=(48,), pool_blocks=64, max_tokens=17),
+    dict(seed=3, n_requests=5, block_tokens=16, row_bytes=(656,), pool_blocks=32, max_tokens=70),
+    dict(seed=4, n_requests=3, block_tokens=16, row_bytes=(32, 16), pool_blocks=24, max_tokens=60),
+    dict(seed=5, n_requests=6, block_tokens=4, row_bytes=(16, 48), pool_blocks=64, max_tokens=30, kind="runs"),
+    dict(seed=6, n_requests=2, block_tokens=3, row_bytes=(5,), pool_blocks=20, max_tokens=20),  # odd row size
+    dict(seed=7, n_requests=4, block_tokens=8, row_bytes=(16,), pool_blocks=30, max_tokens=40, kind="contiguous"),
+]
+
+
+# --------------------------------------------------------------------------
+# the pin battery (also used by the planted-mistake test)
+# --------------------------------------------------------------------------
+
+def pin_brute_force():
+    for kw in TINY:
+        w = W.tiny(**kw)
+        pools = W.fill_pool(w, 0, "src")
+        got = _o_pack(w, pools)
+        want = brute_pack(w.layout.block_tokens, w.layout.row_bytes, w.hit, w.src.tables, pools)
+        assert got.tobytes() == want.tobytes(), kw
+        # unpack of an arbitrary byte string into a sentinel pool
+        x = W.random_payload(w, 0, got.size)
+        dst = W.sentinel_pool(w, "dst")
+        ref = [d.copy() for d in dst]
+        _o_unpack(w, x, dst)
+        brute_unpack(w.layout.block_tokens, w.layout.row_bytes, w.hit, w.dst.tables, x, ref)
+        for a, b in zip(dst, ref):
+            assert a.tobytes() == b.tobytes(), kw
+
+
+def pin_exhaustive_permutations():
+    bs, row = 2, 16
+    rng = np.random.Generator(np.random.PCG64(99))
+    pool = rng.integers(0, 256, size=5 * bs * row, dtype=np.uint8)
+    for n in range(1, 6):
+        for perm in itertools.permutations(range(5), n):
+            hit = [n * bs - 1]  # ragged: last block holds one row
+            tables = [np.array(perm, dtype=np.int32)]
+            got = oracle.pack(bs, (row,), hit, tables, [pool])
+            want = brute_pack(bs, (row,), hit, tables, [pool])
+            assert got.tobytes() == want.tobytes(), perm
+
+
+def pin_round_trip():
+    for kw in TINY + [dict(seed=11, n_requests=8, block_tokens=16, row_bytes=(1152,), pool_blocks=200, max_tokens=300)]:
+        w = W.tiny(**kw)
+        src = W.fill_pool(w, 0, "src")
+        x = _o_pack(w, src, "src")
+        # same table on the way back: hit rows restored, everything else sentinel
+        back = W.sentinel_pool(w, "src", 0xA5)
+        _o_unpack(w, x, back, "src")
+        for p, row in enumerate(w.layout.row_bytes):
+            m = brute_hit_mask(w.layout.block_tokens, row, w.hit, w.src.tables, w.src.pool_blocks)
+            assert np.array_equal(back[p][m], src[p][m])
+            assert np.all(back[p][~m] == 0xA5)
+        # other table: pack(unpack(x)) == x for an arbitrary byte string
+        y = W.random_payload(w, 1, x.size)
+        dst = W.sentinel_pool(w, "dst")
+        _o_unpack(w, y, dst, "dst")
+        assert _o_pack(w, dst, "dst").tobytes() == y.tobytes()
+
+
+def pin_byte_conservation():
+    for kw in TINY:
+        w = W.tiny(**kw)
+        T = int(np.sum(w.hit.astype(np.int64)))
+        n = T * sum(w.layout.row_bytes)
+        assert oracle.payload_bytes(w.hit, w.layout.row_bytes) == n
+        assert oracle.total_hit_tokens(w.hit) == T
+        guard = 64
+        buf = np.full(n + guard, 0x5C, dtype=np.uint8)
+        src = [np.where(p == 0x5C, np.uint8(0x5D), p) for p in W.fill_pool(w, 0, "src")]  # never 0x5C
+        _o_pack(w, src, xfer=buf)
+        assert np.all(buf[n:] == 0x5C)            # guard untouched
+        assert np.all(buf[:n] != 0x5C)            # every payload byte written
+        dst = W.sentinel_pool(w, "dst", 0x5C)
+        _o_unpack(w, buf, dst)
+        changed = sum(int(np.count_nonzero(d != 0x5C)) for d in dst)
+        assert changed == n                       # exactly payload bytes written
+
+
+def pin_memcpy_and_take():
+    rng = np.random.Generator(np.random.PCG64(5))
+    bs, row, nblk = 16, 48, 12
+    pool = rng.integers(0, 256, size=nblk * bs * row, dtype=np.uint8)
+    # identity table, whole blocks: pack is a memcpy of the prefix
+    hit = [7 * bs]
+    x = oracle.pack(bs, (row,), hit, [np.arange(nblk, dtype=np.int32)], [pool])
+    assert x.tobytes() == pool[:7 * bs * row].tobytes()
+    # block size 1: pack is a row gather
+    tb = [rng.permutation(nblk * bs)[:50].astype(np.int32), rng.permutation(nblk * bs)[:31].astype(np.int32)]
+    x = oracle.pack(1, (row,), [50, 31], tb, [pool])
+    want = np.take(pool.reshape(-1, row), np.concatenate(tb), axis=0)
+    assert x.tobytes() == want.tobytes()
+    # and unpack with block size 1 is a row scatter
+    dst = np.zeros_like(pool)
+    oracle.unpack(1, (row,), [50, 31], tb, x, [dst])
+    ref = np.zeros_like(pool).reshape(-1, row)
+    ref[np.concatenate(tb)] = want
+    assert dst.tobytes() == ref.tobytes()
+    # two planes are two independent one-plane problems laid out one after the other
+    pool2 = rng.integers(0, 256, size=nblk * bs * 16, dtype=np.uint8)
+    hit2 = [37, 5]
+    tabs = [np.array([3, 9, 1], np.int32), np.array([0], np.int32)]
+    both = oracle.pack(bs, (row, 16), hit2, tabs, [pool, pool2])
+    a = oracle.pack(bs, (row,), hit2, tabs, [pool])
+    b = oracle.pack(bs, (16,), hit2, tabs, [pool2])
+    assert both.tobytes() == a.tobytes() + b.tobytes()
+
+
+def pin_permutation_algebra():
+    rng = np.random.Generator(np.random.PCG64(17))
+    bs, row, n = 4, 32, 24
+    src = rng.integers(0, 256, size=n * bs * row, dtype=np.uint8)
+    pi = rng.permutation(n).astype(np.int32)
+    sigma = rng.permutation(n).astype(np.int32)
+    hit = [n * bs]
+    x = oracle.pack(bs, (row,), hit, [pi], [src])
+    dst = np.zeros_like(src)
+    oracle.unpack(bs, (row,), hit, [sigma], x, [dst])
+    S = src.reshape(n, bs * row)
+    D = dst.reshape(n, bs * row)
+    for i in range(n):
+        assert np.array_equal(D[sigma[i]], S[pi[i]])
+    # composing with the inverse hop is the identity
+    y = oracle.pack(bs, (row,), hit, [sigma], [dst])
+    back = np.zeros_like(src)
+    oracle.unpack(bs, (row,), hit, [pi], y, [back])
+    assert back.tobytes() == src.tobytes()
+
+
+def pin_closed_form_fill():
+    # every pool byte is a function of (block, row in block, byte); the packed
+    # buffer must then be that function of the table entries
+    w = W.tiny(seed=21, n_requests=5, block_tokens=16, row_bytes=(80,), pool_blocks=64, max_tokens=100)
+    bs, row = 16, 80
+    nb = w.src.pool_blocks
+
+    def f(b, t, j):
+        v = (b.astype(np.uint64) * np.uint64(2654435761) + t.astype(np.uint64) * np.uint64(40503)
+             + j.astype(np.uint64) * np.uint64(97))
+        return ((v >> np.uint64(7)) & np.uint64(0xFF)).astype(np.uint8)
+
+    B, Tt, J = np.meshgrid(np.arange(nb), np.arange(bs), np.arange(row), indexing="ij")
+    pool = f(B, Tt, J).reshape(-1)
+    x = _o_pack(w, [pool])
+    pos = 0
+    for r, h in enumerate(w.hit):
+        t = np.arange(int(h))
+        b = w.src.tables[r][t // bs]
+        tt, jj = np.meshgrid(t % bs, np.arange(row), indexing="ij")
+        bb = np.repeat(b[:, None], row, axis=1)
+        want = f(bb, tt, jj).reshape(-1)
+        assert x[pos:pos + want.size].tobytes() == want.tobytes()
+        pos += want.size
+    assert pos == x.size
+
+
+def pin_threads_agree():
+    w = W.tiny(seed=31, n_requests=9, block_tokens=16, row_bytes=(64, 32), pool_blocks=128, max_tokens=150)
+    src = W.fill_pool(w, 0, "src")
+    a = _o_pack(w, src)
+    b = _o_pack(w, src, threads=4)
+    assert a.tobytes() == b.tobytes()
+    d1, d4 = W.sentinel_pool(w), W.sentinel_pool(w)
+    _o_unpack(w, a, d1)
+    _o_unpack(w, a, d4, threads=4)
+    for u, v in zip(d1, d4):
+        assert u.tobytes() == v.tobytes()
+
+
+PINS = [pin_brute_force, pin_exhaustive_permutations, pin_round_trip, pin_byte_conservation,
+        pin_memcpy_and_take, pin_permutation_algebra, pin_closed_form_fill, pin_threads_agree]
+
+
+@pytest.mark.parametrize("pin", PINS, ids=lambda f: f.__name__)
+def test_pin(pin):
+    pin()
+
+
+# --------------------------------------------------------------------------
+# preconditions
+# --------------------------------------------------------------------------
+
+def test_check_preconditions():
+    bs, pool = 4, 10
+    ok = [np.array([1, 2, 3], np.int32), np.array([5], np.int32)]
+    assert oracle.check(bs, pool, [9, 2], [1, 2], ok, scatter=True) == oracle.OK
+    # table too short for hit + appended tokens (9 + 4 tokens need 4 blocks)
+    assert oracle.check(bs, pool, [9, 2], [4, 2], ok, scatter=False) == oracle.E_TABLE
+    bad = [np.array([1, 2, 10], np.int32), np.array([5], np.int32)]
+    assert oracle.check(bs, pool, [9, 2], [1, 2], bad, scatter=False) == oracle.E_BLOCK
+    neg = [np.array([1, -1, 3], np.int32), np.array([5], np.int32)]
+    assert oracle.check(bs, pool, [9, 2], [1, 2], neg, scatter=False) == oracle.E_BLOCK
+    dup = [np.array([1, 2, 3], np.int32), np.array([2], np.int32)]
+    assert oracle.check(bs, pool, [9, 2], [1, 2], dup, scatter=False) == oracle.OK   # gather may alias
+    assert oracle.check(bs, pool, [9, 2], [1, 2], dup, scatter=True) == oracle.E_DUP
+    # a block that only holds appended rows receives nothing, so it cannot alias
+    tail = [np.array([1, 2, 3], np.int32), np.array([5, 3], np.int32)]
+    assert oracle.check(bs, pool, [8, 2], [4, 6], tail, scatter=True) == oracle.OK
+
+
+def test_empty_batch_and_zero_hits():
+    x = oracle.pack(4, (16,), [], [], [np.zeros(64, np.uint8)])
+    assert x.size == 0
+    pool = np.arange(4 * 4 * 16, dtype=np.uint8)
+    x = oracle.pack(4, (16,), [0, 3, 0], [np.array([0], np.int32), np.array([2], np.int32),
+                                          np.zeros(0, np.int32)], [pool])
+    assert x.tobytes() == pool[2 * 4 * 16: 2 * 4 * 16 + 3 * 16].tobytes()
+
+
+# --------------------------------------------------------------------------
+# layer-wise streaming: same observables for any number of resident slots
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("S", [1, 2, 5])
+def test_stream_layers_observables(S):
+    L, H = 5, 2
+    w = W.tiny(seed=41, n_requests=4, block_tokens=8, row_bytes=(32,), pool_blocks=48, max_tokens=50, n_layers=L)
+    n = oracle.payload_bytes(w.hit, w.layout.row_bytes)
+    layers = [np.full(n, 0x10 + l, dtype=np.uint8) for l in range(L)]   # layer tag in every byte
+    mask = brute_hit_mask(8, 32, w.hit, w.dst.tables, w.dst.pool_blocks)
+    # host slot h is refilled with layer l's payload just before layer l is loaded
+    host = [np.zeros(n, np.uint8) for _ in range(H)]
+    slots = [W.sentinel_pool(w, "dst", 0xEE) for _ in range(S)]
+    seen = 0
+    gen = oracle.stream_layers(8, w.layout.row_bytes, w.hit, w.dst.tables, host, L, slots)
+    host[0][:] = layers[0]
+    for l in range(L):
+        ll, s, planes = next(gen)
+        assert (ll, s) == (l, l % S)
+        assert np.all(planes[0][mask] == 0x10 + l)       # the layer being computed is the one resident
+        assert np.all(planes[0][~mask] == 0xEE)
+        if l + 1 < L:
+            host[(l + 1) % H][:] = layers[l + 1]
+        seen += 1
+    assert seen == L
+
+
+# --------------------------------------------------------------------------
+# planted mistakes: each must trip at least one pin
+# --------------------------------------------------------------------------
+
+MUTANTS = [
+    ("swap div and mod", r"tables\[r\]\[t / bs\] \* bs \+ t % bs", "tables[r][t % bs] * bs + t / bs"),
+    ("drop row in block", r"\* bs \+ t % bs;", "* bs;"),
+    ("block stride off by one", r"tables\[r\]\[t / bs\] \* bs", "tables[r][t / bs] * (bs + 1)"),
+    ("request offset uses row count only", r"off \+= \(uint64_t\)hit\[r\] \* row;", "off += (uint64_t)hit[r];"),
+    ("plane base forgets T", r"base \+= T \* row;", "base += row;"),
+    ("hit loop one short", r"t < hit\[r\]; \+\+t", "t + 1 < hit[r]; ++t"),
+    ("row loop one short", r"j < row; \+\+j", "j + 1 < row; ++j"),
+    ("xfer index transposed", r"xfer\[off \+ t \* row \+ j\]", "xfer[off + j * hit[r] + t]"),
+    ("payload counts one plane", r"bytes \+= T \* \(uint64_t\)row_bytes\[p\];", "bytes = T * (uint64_t)row_bytes[p];"),
+]
+
+
+def _battery_against(so_path):
+    """Run every pin against another build of the oracle; exit code 1 if one trips."""
+    with KO.use_library(so_path):
+        for pin in PINS:
+            try:
+                pin()
+            except (AssertionError, ValueError, RuntimeError, IndexError):
+                return 1
+    return 0
+
+
+@pytest.mark.parametrize("name,pat,rep", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(name, pat, rep):
+    src = open(KO._SRC).read()
+    mutated, n = re.subn(pat, rep, src)
+    assert n >= 1, "mutation pattern no longer matches the oracle source"
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    with tempfile.TemporaryDirectory() as d:
+        c = os.path.join(d, "m.c")
+        so = os.path.join(d, "m.so")
+        open(c, "w").write(mutated)
+        subprocess.check_call(["gcc", "-std=c99", "-O1", "-w", "-fPIC", "-shared", "-o", so, c])
+        # a planted indexing mistake may write out of bounds, so the battery
+        # runs in a child process; a crash there also counts as noticed
+        code = ("import sys; sys.path.insert(0, %r); sys.path.insert(0, %r); "
+                "import test_oracle_pins as t; sys.exit(t._battery_against(%r))"
+                % (root, os.path.join(root, "tests"), so))
+        rc = subprocess.run([sys.executable, "-c", code], capture_output=True).returncode
+        assert rc != 0, f"no pin noticed: {name}"
