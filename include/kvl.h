@@ -1,0 +1,262 @@
+/*
+ * kvl -- layer-wise KV-cache load for one MI355X (gfx950), C ABI.
+ *
+ * The paper's dual-path loading (Section 4.1) brings the cache of a request's
+ * hit tokens -- the prefix of its context that is already cached -- into the
+ * prefill engine's HBM one layer at a time, either from the prefill engine's
+ * own host buffer or from a decode engine's buffer, while the layers before it
+ * are being computed.  The unit of that traffic is the Layer Block of
+ * Appendix A.5: a byte tensor [1, tokens, bytes] with one layer's cache of
+ * block_size tokens.  This library is the GPU side of that load:
+ *
+ *   kvl_plan              host: turn block tables into copy descriptors (once
+ *                         per batch; the same tables serve every layer, since a
+ *                         Full Block is the concatenation of one block's Layer
+ *                         Blocks, Appendix A.5)
+ *   kvl_pack_layer        decode side: gather hit rows of one layer from a
+ *                         paged pool into a dense transfer buffer
+ *   kvl_unpack_layer      prefill side: scatter a transfer buffer into a paged
+ *                         pool
+ *   kvl_h2d_unpack_layer  the same with the transfer buffer in pinned host
+ *                         memory (the prefill engine's host buffer)
+ *   kvl_stream_layers     all layers: load of layer l+1 under compute of layer l
+ *
+ * Transfer-buffer layout (one layer), with T = sum of hit tokens of the batch:
+ *   plane p starts at byte  sum_{q<p} T * row_bytes[q];
+ *   inside plane p request r starts at  sum_{s<r} hit_s * row_bytes[p];
+ *   token t of request r follows at t * row_bytes[p].  Dense, no padding.
+ * Pool layout (one layer, one plane): bytes [pool_blocks][block_tokens][row_bytes[p]];
+ *   token t of request r lives in block table[t / block_tokens], row
+ *   t % block_tokens.  Only tokens t < hit_tokens are ever moved; the appended
+ *   tokens' rows are never read or written.
+ *
+ * A gather plan and a scatter plan built from the same hit_tokens list give
+ * the same transfer-buffer layout; that is what lets the buffer cross from one
+ * engine to the other.
+ *
+ * Conventions.  Every function returns 0 (KVL_OK) or a negative KVL_E* code
+ * and never throws.  "device" pointers are HIP device memory of the device
+ * that was current when the plan was made; "host" pointers are ordinary host
+ * memory unless "pinned" is said.  The caller owns every pool, buffer and
+ * stream; the library owns only the plan (with its small device descriptor
+ * array and a few events).  Stream arguments are hipStream_t passed as void*;
+ * NULL means the default stream.  pack/unpack/h2d_unpack only enqueue work and
+ * return; results are ready when the stream reaches that point.
+ * A plan may be used by one thread at a time.
+ */
+#ifndef KVL_H
+#define KVL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVL_MAX_PLANES 4
+
+/* error codes */
+#define KVL_OK       0
+#define KVL_EINVAL  -1   /* null pointer, zero size, bad flag, plan of the wrong kind */
+#define KVL_ERANGE  -2   /* block id outside the pool, table too short, size beyond 32-bit row index */
+#define KVL_EALIAS  -3   /* scatter plan names one destination block twice */
+#define KVL_ESPACE  -4   /* buffer, staging area or chunk too small */
+#define KVL_EHIP    -5   /* a HIP call failed: see kvl_last_hip_error */
+#define KVL_ENOMEM  -6   /* host allocation failed */
+
+/* plan flags */
+#define KVL_GATHER     1u  /* plan may be used with kvl_pack_layer */
+#define KVL_SCATTER    2u  /* plan may be used with unpack / h2d_unpack / stream_layers;
+                              destination blocks must be distinct */
+#define KVL_HOST_ONLY  4u  /* make descriptors on the host only (no device is touched);
+                              such a plan can be inspected but not executed */
+#define KVL_NO_MERGE   8u  /* do not merge physically adjacent blocks into one run */
+
+typedef struct kvl_plan_s kvl_plan_t;   /* opaque, library-owned */
+
+/* Geometry of one layer of a paged cache (Appendix A.5). */
+typedef struct {
+    uint32_t n_layers;                   /* layers of the model; used by kvl_stream_layers */
+    uint32_t block_tokens;               /* block_size: tokens per block */
+    uint32_t n_planes;                   /* 1 (e.g. MLA latent+rope) or 2 (separate K and V), <= KVL_MAX_PLANES */
+    uint32_t row_bytes[KVL_MAX_PLANES];  /* cache bytes per token per layer, per plane */
+    uint64_t pool_blocks;                /* blocks in the pool the tables index */
+} kvl_layout_t;
+
+/* One request of the batch: a hit prefix plus a short appended tail
+ * (Section 2: each turn's prompt is the cached context plus appended tokens). */
+typedef struct {
+    uint32_t hit_tokens;         /* cached prefix length; these rows are moved */
+    uint32_t append_tokens;      /* tail computed by prefill; never moved */
+    uint32_t n_blocks;           /* entries in block_table, >= ceil((hit+append)/block_tokens) */
+    const int32_t *block_table;  /* host pointer, borrowed for the duration of kvl_plan */
+} kvl_request_t;
+
+/* One copy descriptor: n_rows consecutive token rows, contiguous on both sides.
+ * pool_row = block * block_tokens + row_in_block; xfer_row = index of the row
+ * among the batch's hit tokens.  The same descriptors serve every plane. */
+typedef struct {
+    uint32_t pool_row;
+    uint32_t xfer_row;
+    uint32_t n_rows;
+    uint32_t reserved;
+} kvl_unit_t;
+
+/* Optional tuning; a zero field means "library default". */
+typedef struct {
+    uint32_t unit_bytes;     /* target bytes of one descriptor (runs are split evenly to stay at or below it) */
+    uint32_t block_threads;  /* threads per workgroup: 64, 128, 256, 512 or 1024 */
+    uint32_t variant;        /* kernel variant, see kvl_variant_name */
+    uint32_t reserved;
+} kvl_tuning_t;
+
+/* Build a plan.  Validates the batch (KVL_ERANGE: a block id outside
+ * [0, pool_blocks), a table shorter than the request needs, or more than 2^32-1
+ * pool rows or hit tokens; KVL_EALIAS: with KVL_SCATTER, a block that receives
+ * hit rows is named twice), lays out the transfer buffer, merges physically
+ * adjacent blocks of a request into runs, splits runs into descriptors and,
+ * unless KVL_HOST_ONLY, uploads them to the current device.
+ * requests: host array of n_req entries (n_req may be 0).  *out receives the
+ * plan; free it with kvl_plan_destroy.  tuning may be NULL. */
+int kvl_plan(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t n_req,
+             uint32_t flags, kvl_plan_t **out);
+int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t n_req,
+                   uint32_t flags, const kvl_tuning_t *tuning, kvl_plan_t **out);
+void kvl_plan_destroy(kvl_plan_t *plan);
+
+/* Change launch tuning (block_threads, variant) of an existing plan;
+ * unit_bytes is fixed at plan time and ignored here. */
+int kvl_plan_set_tuning(kvl_plan_t *plan, const kvl_tuning_t *tuning);
+
+/* Plan inspection (host side, valid for any plan). */
+int kvl_plan_payload_bytes(const kvl_plan_t *plan, uint64_t *bytes_per_layer); /* all planes */
+int kvl_plan_hit_tokens(const kvl_plan_t *plan, uint64_t *tokens);             /* T */
+int kvl_plan_n_units(const kvl_plan_t *plan, uint64_t *n_units);
+/* Copy up to capacity descriptors into out (host array); *n_units gets the total. */
+int kvl_plan_get_units(const kvl_plan_t *plan, kvl_unit_t *out, uint64_t capacity, uint64_t *n_units);
+
+/* One host-to-device chunk of the h2d path: descriptors [unit_begin, unit_end)
+ * of plane `plane`, whose rows are the contiguous bytes
+ * [host_offset, host_offset + bytes) of the transfer buffer. */
+typedef struct {
+    uint32_t plane;
+    uint32_t unit_begin;
+    uint32_t unit_end;
+    uint32_t reserved;
+    uint64_t host_offset;
+    uint64_t bytes;
+} kvl_chunk_t;
+/* How kvl_h2d_unpack_layer would cut a layer into chunks of at most chunk_bytes
+ * (KVL_ESPACE if one descriptor alone is larger).  Host side only. */
+int kvl_plan_get_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes,
+                        kvl_chunk_t *out, uint64_t capacity, uint64_t *n_chunks);
+
+/* Decode side (Section 4.1, decode-engine read path: the layer's hit cache
+ * leaves the decode engine's buffer as Layer Blocks): gather.
+ * pool_planes: host array of n_planes device pointers, layer l's plane bases.
+ * xfer: device buffer of xfer_capacity >= payload bytes (else KVL_ESPACE).
+ * Needs a KVL_GATHER plan.  Enqueues on stream. */
+int kvl_pack_layer(const kvl_plan_t *plan, const void *const *pool_planes,
+                   void *xfer, uint64_t xfer_capacity, void *stream);
+
+/* Prefill side (Section 4.1: before a layer's attention is computed its hit
+ * cache is placed in the prefill engine's HBM): scatter.  Rows that hold no
+ * hit token keep their bytes.  xfer_bytes must be >= payload bytes (KVL_ESPACE).
+ * Needs a KVL_SCATTER plan.  Enqueues on stream. */
+int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_bytes,
+                     void *const *pool_planes, void *stream);
+
+/* Prefill-engine read path, host buffer -> HBM for one layer (Section 4.1,
+ * steps 3-4 of that path): the transfer buffer lies in PINNED host memory; it is
+ * copied in chunks of at most chunk_bytes with hipMemcpyAsync on copy_stream
+ * into a ring of floor(staging_bytes / chunk_bytes) slots in dev_staging
+ * (device memory, 16-byte aligned) and every landed chunk is scattered by a
+ * kernel on kernel_stream.  The call first orders copy_stream after the work
+ * already enqueued on kernel_stream, so a staging area may be reused by the
+ * next call at once.  The pool is complete when kernel_stream reaches the end
+ * of the enqueued work.  KVL_ESPACE: staging smaller than one chunk, or a
+ * chunk smaller than one descriptor.  copy_stream and kernel_stream should
+ * differ for the copies to overlap the scatter. */
+int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
+                         void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
+                         void *const *pool_planes, void *copy_stream, void *kernel_stream);
+
+/* A 16-byte sample of what the compute of a layer sees. */
+typedef struct {
+    uint32_t plane;
+    uint32_t reserved;
+    uint64_t byte_offset;   /* into the slot's plane, multiple of 16 */
+} kvl_probe_t;
+
+/* Called on the calling thread before layer `layer`'s host buffer
+ * (host_layers[layer % n_host_slots]) is read, once all earlier reads of that
+ * slot have completed: the place where the storage read of that layer would
+ * deliver its bytes.  Return non-zero to abort the run. */
+typedef int (*kvl_host_fill_fn)(void *user, uint32_t layer, void *host_slot, uint64_t bytes);
+
+typedef struct {
+    uint32_t n_layers;                 /* 0: take layout.n_layers */
+    uint32_t n_host_slots;             /* H >= 1 */
+    void *const *host_layers;          /* [H] pinned host transfer buffers */
+    uint32_t n_dev_slots;              /* S >= 1 resident destination layers */
+    void *const *dev_slot_planes;      /* [S * n_planes] device plane bases, slot-major */
+    void *dev_staging;                 /* as in kvl_h2d_unpack_layer */
+    uint64_t staging_bytes;
+    uint64_t chunk_bytes;
+    uint32_t compute_us;               /* duration of the synthetic per-layer compute kernel */
+    uint32_t n_probes;                 /* optional samples taken by the compute kernel */
+    const kvl_probe_t *probes;         /* host array [n_probes] */
+    void *probe_out;                   /* device, n_layers * n_probes * 16 bytes */
+    void *const *snapshot_planes;      /* optional [n_layers * n_planes] device buffers: a copy of the
+                                          slot taken on the compute stream right after compute(l) */
+    kvl_host_fill_fn host_fill;        /* optional */
+    void *host_fill_user;
+    void *copy_stream;                 /* three distinct non-default streams recommended */
+    void *kernel_stream;
+    void *compute_stream;
+} kvl_stream_cfg_t;
+
+typedef struct {
+    double total_ms;         /* first copy enqueued .. last compute finished (device clock) */
+    double h2d_bytes;        /* bytes that crossed the host link */
+    double link_gbps;        /* h2d_bytes / total_ms, GB/s */
+    double exposed_ms;       /* total_ms minus n_layers * compute_us: load time not hidden */
+    /* optional per-layer times in ms since the start, host arrays of n_layers or NULL */
+    float *t_loaded;         /* layer's scatter finished */
+    float *t_compute_begin;
+    float *t_compute_end;
+} kvl_stream_stats_t;
+
+/* Layer-wise load of all layers (Section 4.1: the load of a layer overlaps the
+ * computation of the layers before it; layer-wise prefill keeps only a few
+ * layers' cache resident).  For l = 0 .. n_layers-1: layer l is loaded from
+ * host_layers[l % H] into destination slot l % S by the h2d path; the compute
+ * of layer l (a kernel that spins compute_us on the compute stream) starts
+ * after that load; the load of layer l + S starts scattering only after the
+ * compute of layer l has finished.  Blocks until everything has finished and
+ * fills *stats (may be NULL).  Needs a KVL_SCATTER plan. */
+int kvl_stream_layers(const kvl_plan_t *plan, const kvl_stream_cfg_t *cfg, kvl_stream_stats_t *stats);
+
+/* Measure the host link: time `reps` host-to-device hipMemcpyAsync of `bytes`
+ * from pinned host memory on `stream`; *gbps gets the best rate in GB/s. */
+int kvl_measure_h2d_peak(const void *pinned_host, void *dev, uint64_t bytes, uint32_t reps,
+                         void *stream, double *gbps);
+
+/* Plain device-to-device streaming copy with the same load/store code as the
+ * pack kernel (bytes multiple of 16, pointers 16-byte aligned): the ceiling a
+ * gather with perfect locality could reach, and the known-size kernel used to
+ * calibrate HBM byte counters. */
+int kvl_copy_linear(const void *src, void *dst, uint64_t bytes, void *stream);
+
+const char *kvl_strerror(int code);
+/* hipError_t of the last KVL_EHIP on this thread, and its text. */
+int kvl_last_hip_error(void);
+const char *kvl_last_hip_error_string(void);
+const char *kvl_variant_name(uint32_t variant);   /* NULL beyond the last variant */
+const char *kvl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVL_H */

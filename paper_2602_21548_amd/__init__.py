@@ -1,0 +1,21 @@
+"""Layer-wise KV-cache load for MI355X: Python binding of libkvl.so (see include/kvl.h).
+
+The binding (and with it the shared library) is loaded on first use, so that
+``paper_2602_21548_amd.build`` can be imported and run while no library exists yet.
+"""
+import importlib
+
+_EXPORTS = (
+    "KvlError", "Plan", "make_layout", "kvl_plan", "kvl_pack_layer", "kvl_unpack_layer",
+    "kvl_h2d_unpack_layer", "kvl_stream_layers", "kvl_measure_h2d_peak", "kvl_copy_linear",
+    "kvl_strerror", "kvl_variant_name", "kvl_version", "LIB_PATH",
+    "KVL_OK", "KVL_EINVAL", "KVL_ERANGE", "KVL_EALIAS", "KVL_ESPACE", "KVL_EHIP", "KVL_ENOMEM",
+    "KVL_GATHER", "KVL_SCATTER", "KVL_HOST_ONLY", "KVL_NO_MERGE", "KVL_MAX_PLANES",
+)
+__all__ = list(_EXPORTS)
+
+
+def __getattr__(name):
+    if name in _EXPORTS:
+        return getattr(importlib.import_module(".binding", __name__), name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

@@ -1,0 +1,118 @@
+// Host-buffer load path: pinned host transfer buffer -> staging ring in HBM
+// (hipMemcpyAsync on a copy stream) -> scatter kernel per landed chunk.
+//
+// The paper notes that handing many small copies to a copy engine is bound by
+// the per-copy submission cost (Section 5.2), so the host buffer is not copied
+// block by block: it is dense, and is cut into multi-megabyte chunks whose ends
+// fall on descriptor boundaries; the fine-grained part of the work (finding each
+// block's place in the paged pool) is left to the scatter kernel in HBM.
+#include <algorithm>
+#include <vector>
+
+#include "kvl_internal.h"
+
+namespace kvl {
+
+// Enqueue one layer.  `wait_before_scatter`, if not null, is an event the kernel
+// stream must pass before the first scatter of this layer touches the pool.
+int enqueue_h2d_layer(kvl_plan_t *plan, const std::vector<kvl_chunk_t> &chunks,
+                      const void *host_xfer, void *dev_staging, uint64_t chunk_bytes, size_t slots,
+                      void *const *pool_planes, hipStream_t copy_s, hipStream_t kern_s,
+                      hipEvent_t wait_before_scatter, size_t *ring_pos) {
+    const char *host = static_cast<const char *>(host_xfer);
+    char *stage = static_cast<char *>(dev_staging);
+    if (wait_before_scatter) KVL_HIP(hipStreamWaitEvent(kern_s, wait_before_scatter, 0));
+    for (const kvl_chunk_t &c : chunks) {
+        if (c.bytes == 0) continue;
+        const size_t use = *ring_pos;          // total chunks enqueued so far with this ring
+        const size_t slot = use % slots;
+        char *dst = stage + slot * chunk_bytes;
+        // the slot's previous occupant must have been scattered
+        if (use >= slots) KVL_HIP(hipStreamWaitEvent(copy_s, plan->ev_free[slot], 0));
+        KVL_HIP(hipMemcpyAsync(dst, host + c.host_offset, c.bytes, hipMemcpyHostToDevice, copy_s));
+        KVL_HIP(hipEventRecord(plan->ev_landed[slot], copy_s));
+        KVL_HIP(hipStreamWaitEvent(kern_s, plan->ev_landed[slot], 0));
+        // address at which transfer row 0 of this plane would lie if the whole
+        // plane were laid out around this slot
+        const uint64_t row = plan->layout.row_bytes[c.plane];
+        const uint64_t first_row_off = (uint64_t)plan->units[c.unit_begin].xfer_row * row;
+        uintptr_t xp[KVL_MAX_PLANES] = {};
+        xp[c.plane] = reinterpret_cast<uintptr_t>(dst) - first_row_off;
+        int rc = launch_units(plan, false, c.unit_begin, c.unit_end, c.plane, c.plane + 1,
+                              pool_planes, xp, kern_s);
+        if (rc != KVL_OK) return rc;
+        KVL_HIP(hipEventRecord(plan->ev_free[slot], kern_s));
+        ++*ring_pos;
+    }
+    return KVL_OK;
+}
+
+int check_h2d_args(const kvl_plan_t *plan, const void *host, const void *staging,
+                   uint64_t staging_bytes, uint64_t chunk_bytes, size_t *slots) {
+    if (!plan) return KVL_EINVAL;
+    if (!(plan->flags & KVL_SCATTER) || (plan->flags & KVL_HOST_ONLY)) return KVL_EINVAL;
+    if (chunk_bytes == 0 || chunk_bytes % 16) return KVL_EINVAL;
+    if (staging_bytes < chunk_bytes) return KVL_ESPACE;
+    if (!plan->units.empty() && (!host || !staging)) return KVL_EINVAL;
+    if (reinterpret_cast<uintptr_t>(staging) % 16) return KVL_EINVAL;
+    *slots = (size_t)std::min<uint64_t>(staging_bytes / chunk_bytes, 64);
+    return KVL_OK;
+}
+
+}  // namespace kvl
+
+extern "C" {
+
+int kvl_h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xfer, void *dev_staging,
+                         uint64_t staging_bytes, uint64_t chunk_bytes, void *const *pool_planes,
+                         void *copy_stream, void *kernel_stream) {
+    kvl_plan_t *plan = const_cast<kvl_plan_t *>(plan_c);   // the plan's event ring is scratch state
+    size_t slots = 0;
+    int rc = kvl::check_h2d_args(plan, pinned_host_xfer, dev_staging, staging_bytes, chunk_bytes, &slots);
+    if (rc != KVL_OK) return rc;
+    if (!pool_planes) return KVL_EINVAL;
+    if (plan->units.empty()) return KVL_OK;
+    std::vector<kvl_chunk_t> chunks;
+    try {
+        rc = kvl::make_chunks(plan, chunk_bytes, chunks);
+    } catch (const std::bad_alloc &) {
+        return KVL_ENOMEM;
+    }
+    if (rc != KVL_OK) return rc;
+    rc = kvl::ensure_ring_events(plan, slots);
+    if (rc != KVL_OK) return rc;
+    hipStream_t cs = (hipStream_t)copy_stream, ks = (hipStream_t)kernel_stream;
+    // the staging ring may still be read by scatters enqueued earlier
+    KVL_HIP(hipEventRecord(plan->ev_entry, ks));
+    KVL_HIP(hipStreamWaitEvent(cs, plan->ev_entry, 0));
+    size_t ring_pos = 0;
+    return kvl::enqueue_h2d_layer(plan, chunks, pinned_host_xfer, dev_staging, chunk_bytes, slots,
+                                  pool_planes, cs, ks, nullptr, &ring_pos);
+}
+
+int kvl_measure_h2d_peak(const void *pinned_host, void *dev, uint64_t bytes, uint32_t reps,
+                         void *stream, double *gbps) {
+    if (!pinned_host || !dev || !gbps || bytes == 0 || reps == 0) return KVL_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t a = nullptr, b = nullptr;
+    KVL_HIP(hipEventCreate(&a));
+    hipError_t e = hipEventCreate(&b);
+    if (e != hipSuccess) { (void)hipEventDestroy(a); kvl::set_hip_error(e); return KVL_EHIP; }
+    double best = 0.0;
+    for (uint32_t i = 0; i < reps && e == hipSuccess; ++i) {
+        e = hipEventRecord(a, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(dev, pinned_host, bytes, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipEventRecord(b, s);
+        if (e == hipSuccess) e = hipEventSynchronize(b);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+        if (e == hipSuccess && ms > 0.f) best = std::max(best, (double)bytes / (ms * 1e-3) / 1e9);
+    }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    if (e != hipSuccess) { kvl::set_hip_error(e); return KVL_EHIP; }
+    *gbps = best;
+    return KVL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,62 @@
+// Internal declarations shared by the library's translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <vector>
+
+#include "kvl.h"
+
+struct kvl_plan_s {
+    kvl_layout_t layout{};
+    uint32_t flags = 0;
+    uint32_t n_req = 0;
+    uint64_t hit_tokens = 0;                     // T
+    uint64_t payload_bytes = 0;                  // all planes
+    uint64_t plane_base[KVL_MAX_PLANES] = {};    // byte offset of each plane in the transfer buffer
+    uint32_t max_unit_rows = 0;
+    bool vec16 = false;                          // every row size is a multiple of 16 bytes
+    std::vector<kvl_unit_t> units;               // host copy of the descriptors
+    kvl_unit_t *d_units = nullptr;               // device copy (absent for KVL_HOST_ONLY)
+    int device = -1;
+    kvl_tuning_t tuning{};                       // resolved (no zero fields)
+    // events reused by the h2d path: one "landed" and one "slot free" per ring slot
+    std::vector<hipEvent_t> ev_landed, ev_free;
+    hipEvent_t ev_entry = nullptr;
+};
+
+namespace kvl {
+
+void set_hip_error(hipError_t e);
+
+#define KVL_HIP(expr)                                   \
+    do {                                                \
+        hipError_t kvl_e_ = (expr);                     \
+        if (kvl_e_ != hipSuccess) {                     \
+            ::kvl::set_hip_error(kvl_e_);               \
+            return KVL_EHIP;                            \
+        }                                               \
+    } while (0)
+
+constexpr uint32_t kDefaultUnitBytes = 64u << 10;
+constexpr uint32_t kDefaultBlockThreads = 256;
+constexpr uint32_t kDefaultVariant = 0;
+constexpr uint32_t kNumVariants = 16;
+
+bool valid_block_threads(uint32_t t);
+
+// Cut [0, n_units) of one plane into chunks of at most chunk_bytes.
+int make_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, std::vector<kvl_chunk_t> &out);
+
+// Enqueue the copy of descriptors [unit_begin, unit_end) of planes
+// [plane_begin, plane_end).  xfer_plane[p] is the address at which transfer row
+// 0 of plane p would lie (it may point before a staging slot; only rows of the
+// given descriptors are touched).
+int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_t unit_end,
+                 uint32_t plane_begin, uint32_t plane_end,
+                 void *const *pool_planes, const uintptr_t *xfer_plane, hipStream_t stream);
+
+int ensure_ring_events(kvl_plan_t *plan, size_t slots);
+
+}  // namespace kvl

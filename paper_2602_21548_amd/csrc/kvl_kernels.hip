@@ -1,0 +1,264 @@
+// Device side of pack / unpack: copy kernels for gfx950 and their launchers.
+//
+// The work is pure data movement (no arithmetic on the payload).  A copy
+// descriptor names a span of token rows that is contiguous in the paged pool and
+// in the transfer buffer, so each descriptor is a straight 16-byte-vector copy;
+// what the block table fragments is only where each span starts.  The kernels
+// therefore read a descriptor (wave-uniform, through the scalar cache), form two
+// 64-bit addresses and stream the span with several 16-byte loads in flight per
+// lane before the matching stores.  Consecutive lanes touch consecutive 16-byte
+// vectors, so every wavefront load or store covers 1 KiB of contiguous memory.
+//
+// Variant bits (kvl_tuning_t::variant):
+//   bit 0  0: one workgroup per descriptor        1: one wavefront per descriptor
+//   bit 1  non-temporal loads
+//   bit 2  non-temporal stores
+//   bit 3  0: 4 vectors in flight per lane        1: 8 vectors in flight per lane
+#include "kvl_internal.h"
+
+namespace kvl {
+
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+// Every buffer is device (or device-mapped) memory: say so, so that the
+// compiler emits global_load / global_store rather than flat accesses.
+typedef const v4u __attribute__((address_space(1))) *gsrc_t;
+typedef v4u __attribute__((address_space(1))) *gdst_t;
+
+struct CopyArgs {
+    const kvl_unit_t *units;       // device descriptors
+    uint32_t unit_begin;           // first descriptor of this launch
+    uint32_t n_units;              // descriptors in this launch
+    uint32_t plane_begin;          // blockIdx.y + plane_begin is the plane
+    uint32_t row_elems[KVL_MAX_PLANES];  // row size in 16-byte vectors (vector kernels) or bytes
+    uintptr_t pool[KVL_MAX_PLANES];      // plane base of the paged pool
+    uintptr_t xfer[KVL_MAX_PLANES];      // address of transfer row 0 of the plane
+};
+
+template <bool NT>
+__device__ __forceinline__ v4u load16(gsrc_t p) {
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store16(gdst_t p, v4u v) {
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// `lanes` threads copy n 16-byte vectors; this thread is `lane`.  U loads are
+// issued before the first store so that U KiB per wavefront are in flight.
+template <int U, bool NTL, bool NTS>
+__device__ __forceinline__ void copy_span(gsrc_t __restrict__ src, gdst_t __restrict__ dst,
+                                          uint32_t n, uint32_t lane, uint32_t lanes) {
+    // n is below 2^32: a descriptor never spans more than 1 GiB
+    const uint32_t step = lanes * U;
+    const uint32_t last = lanes * (U - 1);
+    uint32_t i = lane;
+    // no division: a lane takes a full step while its last vector is in range
+    for (; (uint64_t)i + last < n; i += step) {
+        v4u v[U];
+#pragma unroll
+        for (int k = 0; k < U; ++k) v[k] = load16<NTL>(src + i + k * lanes);
+#pragma unroll
+        for (int k = 0; k < U; ++k) store16<NTS>(dst + i + k * lanes, v[k]);
+    }
+    // ragged tail: this lane has at most U-1 vectors left
+    v4u v[U];
+#pragma unroll
+    for (int k = 0; k < U - 1; ++k) {
+        const uint64_t j = (uint64_t)i + (uint64_t)k * lanes;
+        if (j < n) v[k] = load16<NTL>(src + j);
+    }
+#pragma unroll
+    for (int k = 0; k < U - 1; ++k) {
+        const uint64_t j = (uint64_t)i + (uint64_t)k * lanes;
+        if (j < n) store16<NTS>(dst + j, v[k]);
+    }
+}
+
+template <bool PACK, bool WAVE, int U, bool NTL, bool NTS>
+__device__ __forceinline__ void units_body(const CopyArgs &a) {
+    uint32_t u_idx, lane, lanes;
+    if (WAVE) {
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        u_idx = blockIdx.x * (blockDim.x >> 6) + wave;
+        lane = threadIdx.x & 63u;
+        lanes = 64;
+    } else {
+        u_idx = blockIdx.x;
+        lane = threadIdx.x;
+        lanes = blockDim.x;
+    }
+    if (u_idx >= a.n_units) return;
+    const kvl_unit_t u = a.units[a.unit_begin + u_idx];
+    const uint32_t p = a.plane_begin + blockIdx.y;
+    const uint64_t row = a.row_elems[p];
+    const uintptr_t pool = a.pool[p] + (uint64_t)u.pool_row * row * 16u;
+    const uintptr_t xfer = a.xfer[p] + (uint64_t)u.xfer_row * row * 16u;
+    const uint32_t n = u.n_rows * (uint32_t)row;
+    if (PACK) copy_span<U, NTL, NTS>((gsrc_t)pool, (gdst_t)xfer, n, lane, lanes);
+    else copy_span<U, NTL, NTS>((gsrc_t)xfer, (gdst_t)pool, n, lane, lanes);
+}
+
+// gather: paged pool -> transfer buffer
+template <bool WAVE, int U, bool NTL, bool NTS>
+__global__ void __launch_bounds__(1024) kvl_pack_kernel(const CopyArgs a) {
+    units_body<true, WAVE, U, NTL, NTS>(a);
+}
+
+// scatter: transfer buffer -> paged pool
+template <bool WAVE, int U, bool NTL, bool NTS>
+__global__ void __launch_bounds__(1024) kvl_unpack_kernel(const CopyArgs a) {
+    units_body<false, WAVE, U, NTL, NTS>(a);
+}
+
+// Fallback for row sizes or addresses that are not multiples of 16 bytes: one
+// workgroup per descriptor, byte by byte.  Correct for any layout, not fast.
+template <bool PACK>
+__global__ void __launch_bounds__(1024) kvl_bytes_kernel(const CopyArgs a) {
+    const kvl_unit_t u = a.units[a.unit_begin + blockIdx.x];
+    const uint32_t p = a.plane_begin + blockIdx.y;
+    const uint64_t row = a.row_elems[p];
+    uint8_t *pool = reinterpret_cast<uint8_t *>(a.pool[p]) + (uint64_t)u.pool_row * row;
+    uint8_t *xfer = reinterpret_cast<uint8_t *>(a.xfer[p]) + (uint64_t)u.xfer_row * row;
+    const uint64_t n = (uint64_t)u.n_rows * row;
+    for (uint64_t i = threadIdx.x; i < n; i += blockDim.x) {
+        if (PACK) xfer[i] = pool[i];
+        else pool[i] = xfer[i];
+    }
+}
+
+// Straight copy in spans of `span` vectors, one workgroup per span.
+template <int U, bool NTL, bool NTS>
+__global__ void __launch_bounds__(1024) kvl_linear_kernel(const v4u *src, v4u *dst,
+                                                          uint64_t n, uint32_t span) {
+    const uint64_t first = (uint64_t)blockIdx.x * span;
+    if (first >= n) return;
+    const uint32_t len = (n - first < span) ? (uint32_t)(n - first) : span;
+    copy_span<U, NTL, NTS>((gsrc_t)(src + first), (gdst_t)(dst + first), len, threadIdx.x, blockDim.x);
+}
+
+template <bool PACK, bool WAVE, int U, bool NTL, bool NTS>
+static void launch_one(dim3 grid, dim3 block, hipStream_t s, const CopyArgs &a) {
+    if (PACK) hipLaunchKernelGGL((kvl_pack_kernel<WAVE, U, NTL, NTS>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((kvl_unpack_kernel<WAVE, U, NTL, NTS>), grid, block, 0, s, a);
+}
+
+template <bool PACK, bool WAVE, int U>
+static void launch_nt(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a) {
+    const bool ntl = v & 2u, nts = v & 4u;
+    if (ntl && nts) launch_one<PACK, WAVE, U, true, true>(g, b, s, a);
+    else if (ntl) launch_one<PACK, WAVE, U, true, false>(g, b, s, a);
+    else if (nts) launch_one<PACK, WAVE, U, false, true>(g, b, s, a);
+    else launch_one<PACK, WAVE, U, false, false>(g, b, s, a);
+}
+
+template <bool PACK>
+static void launch_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a) {
+    const bool wave = v & 1u, u8 = v & 8u;
+    if (wave) {
+        if (u8) launch_nt<PACK, true, 8>(v, g, b, s, a);
+        else launch_nt<PACK, true, 4>(v, g, b, s, a);
+    } else {
+        if (u8) launch_nt<PACK, false, 8>(v, g, b, s, a);
+        else launch_nt<PACK, false, 4>(v, g, b, s, a);
+    }
+}
+
+int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_t unit_end,
+                 uint32_t plane_begin, uint32_t plane_end,
+                 void *const *pool_planes, const uintptr_t *xfer_plane, hipStream_t stream) {
+    if (unit_end <= unit_begin || plane_end <= plane_begin) return KVL_OK;
+    if (!plan->d_units || unit_end > plan->units.size() || plane_end > plan->layout.n_planes)
+        return KVL_EINVAL;
+    CopyArgs a{};
+    a.units = plan->d_units;
+    a.unit_begin = unit_begin;
+    a.n_units = unit_end - unit_begin;
+    a.plane_begin = plane_begin;
+    bool vec = plan->vec16;
+    for (uint32_t p = plane_begin; p < plane_end; ++p) {
+        if (!pool_planes[p]) return KVL_EINVAL;
+        a.pool[p] = reinterpret_cast<uintptr_t>(pool_planes[p]);
+        a.xfer[p] = xfer_plane[p];
+        vec = vec && (a.pool[p] % 16 == 0) && (a.xfer[p] % 16 == 0);
+    }
+    for (uint32_t p = plane_begin; p < plane_end; ++p)
+        a.row_elems[p] = vec ? plan->layout.row_bytes[p] / 16 : plan->layout.row_bytes[p];
+
+    const uint32_t threads = plan->tuning.block_threads;
+    const uint32_t v = plan->tuning.variant;
+    dim3 block(threads);
+    if (!vec) {
+        dim3 grid(a.n_units, plane_end - plane_begin);
+        if (pack) hipLaunchKernelGGL(kvl_bytes_kernel<true>, grid, block, 0, stream, a);
+        else hipLaunchKernelGGL(kvl_bytes_kernel<false>, grid, block, 0, stream, a);
+    } else {
+        const uint32_t per_wg = (v & 1u) ? threads / 64 : 1;
+        dim3 grid((a.n_units + per_wg - 1) / per_wg, plane_end - plane_begin);
+        if (pack) launch_variant<true>(v, grid, block, stream, a);
+        else launch_variant<false>(v, grid, block, stream, a);
+    }
+    KVL_HIP(hipGetLastError());
+    return KVL_OK;
+}
+
+}  // namespace kvl
+
+extern "C" {
+
+int kvl_pack_layer(const kvl_plan_t *plan, const void *const *pool_planes, void *xfer,
+                   uint64_t xfer_capacity, void *stream) {
+    if (!plan || !pool_planes) return KVL_EINVAL;
+    if (!(plan->flags & KVL_GATHER) || (plan->flags & KVL_HOST_ONLY)) return KVL_EINVAL;
+    if (xfer_capacity < plan->payload_bytes) return KVL_ESPACE;
+    if (plan->units.empty()) return KVL_OK;
+    if (!xfer) return KVL_EINVAL;
+    uintptr_t xp[KVL_MAX_PLANES];
+    for (uint32_t p = 0; p < plan->layout.n_planes; ++p)
+        xp[p] = reinterpret_cast<uintptr_t>(xfer) + plan->plane_base[p];
+    return kvl::launch_units(plan, true, 0, (uint32_t)plan->units.size(), 0, plan->layout.n_planes,
+                             const_cast<void *const *>(pool_planes), xp, (hipStream_t)stream);
+}
+
+int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_bytes,
+                     void *const *pool_planes, void *stream) {
+    if (!plan || !pool_planes) return KVL_EINVAL;
+    if (!(plan->flags & KVL_SCATTER) || (plan->flags & KVL_HOST_ONLY)) return KVL_EINVAL;
+    if (xfer_bytes < plan->payload_bytes) return KVL_ESPACE;
+    if (plan->units.empty()) return KVL_OK;
+    if (!xfer) return KVL_EINVAL;
+    uintptr_t xp[KVL_MAX_PLANES];
+    for (uint32_t p = 0; p < plan->layout.n_planes; ++p)
+        xp[p] = reinterpret_cast<uintptr_t>(xfer) + plan->plane_base[p];
+    return kvl::launch_units(plan, false, 0, (uint32_t)plan->units.size(), 0, plan->layout.n_planes,
+                             pool_planes, xp, (hipStream_t)stream);
+}
+
+int kvl_copy_linear(const void *src, void *dst, uint64_t bytes, void *stream) {
+    if (bytes == 0) return KVL_OK;
+    if (!src || !dst) return KVL_EINVAL;
+    if (bytes % 16 || reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(dst) % 16)
+        return KVL_EINVAL;
+    const uint64_t n = bytes / 16;
+    const uint32_t span = kvl::kDefaultUnitBytes / 16;
+    const uint64_t blocks = (n + span - 1) / span;
+    if (blocks > (uint64_t)INT32_MAX) return KVL_ERANGE;
+    hipLaunchKernelGGL((kvl::kvl_linear_kernel<4, false, false>), dim3((uint32_t)blocks),
+                       dim3(kvl::kDefaultBlockThreads), 0, (hipStream_t)stream,
+                       static_cast<const kvl::v4u *>(src), static_cast<kvl::v4u *>(dst), n, span);
+    KVL_HIP(hipGetLastError());
+    return KVL_OK;
+}
+
+const char *kvl_variant_name(uint32_t v) {
+    static const char *names[kvl::kNumVariants] = {
+        "wg/unit u4",          "wave/unit u4",          "wg/unit u4 ntl",     "wave/unit u4 ntl",
+        "wg/unit u4 nts",      "wave/unit u4 nts",      "wg/unit u4 ntl+nts", "wave/unit u4 ntl+nts",
+        "wg/unit u8",          "wave/unit u8",          "wg/unit u8 ntl",     "wave/unit u8 ntl",
+        "wg/unit u8 nts",      "wave/unit u8 nts",      "wg/unit u8 ntl+nts", "wave/unit u8 ntl+nts"};
+    return v < kvl::kNumVariants ? names[v] : nullptr;
+}
+
+}  // extern "C"

@@ -1,0 +1,289 @@
+// Host side of the library: batch validation, transfer-buffer layout and copy
+// descriptors (kvl_plan), plan inspection, error text.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "kvl_internal.h"
+
+namespace kvl {
+
+static thread_local hipError_t g_last_hip = hipSuccess;
+
+void set_hip_error(hipError_t e) { g_last_hip = e; }
+
+bool valid_block_threads(uint32_t t) {
+    return t == 64 || t == 128 || t == 256 || t == 512 || t == 1024;
+}
+
+int make_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, std::vector<kvl_chunk_t> &out) {
+    out.clear();
+    if (chunk_bytes == 0) return KVL_EINVAL;
+    const auto &u = plan->units;
+    for (uint32_t p = 0; p < plan->layout.n_planes; ++p) {
+        const uint64_t row = plan->layout.row_bytes[p];
+        if ((uint64_t)plan->max_unit_rows * row > chunk_bytes) return KVL_ESPACE;
+        size_t i = 0;
+        while (i < u.size()) {
+            kvl_chunk_t c{};
+            c.plane = p;
+            c.unit_begin = (uint32_t)i;
+            c.host_offset = plan->plane_base[p] + (uint64_t)u[i].xfer_row * row;
+            uint64_t bytes = 0;
+            while (i < u.size() && bytes + (uint64_t)u[i].n_rows * row <= chunk_bytes) {
+                bytes += (uint64_t)u[i].n_rows * row;
+                ++i;
+            }
+            c.unit_end = (uint32_t)i;
+            c.bytes = bytes;
+            out.push_back(c);
+        }
+    }
+    return KVL_OK;
+}
+
+int ensure_ring_events(kvl_plan_t *plan, size_t slots) {
+    while (plan->ev_landed.size() < slots) {
+        hipEvent_t a = nullptr, b = nullptr;
+        KVL_HIP(hipEventCreateWithFlags(&a, hipEventDisableTiming));
+        plan->ev_landed.push_back(a);
+        KVL_HIP(hipEventCreateWithFlags(&b, hipEventDisableTiming));
+        plan->ev_free.push_back(b);
+    }
+    if (!plan->ev_entry) KVL_HIP(hipEventCreateWithFlags(&plan->ev_entry, hipEventDisableTiming));
+    return KVL_OK;
+}
+
+static int resolve_tuning(const kvl_tuning_t *in, kvl_tuning_t *out) {
+    kvl_tuning_t t{};
+    if (in) t = *in;
+    if (t.unit_bytes == 0) t.unit_bytes = kDefaultUnitBytes;
+    if (t.block_threads == 0) t.block_threads = kDefaultBlockThreads;
+    if (!valid_block_threads(t.block_threads)) return KVL_EINVAL;
+    if (t.variant >= kNumVariants) return KVL_EINVAL;
+    if (t.unit_bytes > (1u << 30)) t.unit_bytes = 1u << 30;
+    t.reserved = 0;
+    *out = t;
+    return KVL_OK;
+}
+
+static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t n_req,
+                 uint32_t flags, const kvl_tuning_t *tuning, kvl_plan_t **out) {
+    if (!layout || !out || (n_req && !req)) return KVL_EINVAL;
+    *out = nullptr;
+    if (!(flags & (KVL_GATHER | KVL_SCATTER))) return KVL_EINVAL;
+    if (flags & ~(KVL_GATHER | KVL_SCATTER | KVL_HOST_ONLY | KVL_NO_MERGE)) return KVL_EINVAL;
+    if (layout->block_tokens == 0 || layout->n_planes == 0 || layout->n_planes > KVL_MAX_PLANES)
+        return KVL_EINVAL;
+    const uint64_t bs = layout->block_tokens;
+    uint32_t max_row = 0;
+    bool vec16 = true;
+    for (uint32_t p = 0; p < layout->n_planes; ++p) {
+        if (layout->row_bytes[p] == 0) return KVL_EINVAL;
+        max_row = std::max(max_row, layout->row_bytes[p]);
+        vec16 = vec16 && (layout->row_bytes[p] % 16 == 0);
+    }
+    // descriptors index token rows with 32 bits
+    if (layout->pool_blocks > UINT32_MAX / bs) return KVL_ERANGE;
+
+    kvl_plan_t *plan = new (std::nothrow) kvl_plan_t;
+    if (!plan) return KVL_ENOMEM;
+    plan->layout = *layout;
+    for (uint32_t p = layout->n_planes; p < KVL_MAX_PLANES; ++p) plan->layout.row_bytes[p] = 0;
+    plan->flags = flags;
+    plan->n_req = n_req;
+    plan->vec16 = vec16;
+    int rc = resolve_tuning(tuning, &plan->tuning);
+    if (rc != KVL_OK) { delete plan; return rc; }
+
+    const uint64_t max_rows = std::max<uint64_t>(1, plan->tuning.unit_bytes / max_row);
+    const bool scatter = (flags & KVL_SCATTER) != 0;
+    const bool merge = !(flags & KVL_NO_MERGE);
+
+    try {
+        std::vector<uint8_t> taken;
+        if (scatter) taken.assign(layout->pool_blocks ? layout->pool_blocks : 1, 0);
+
+        uint64_t T = 0;
+        for (uint32_t r = 0; r < n_req; ++r) T += req[r].hit_tokens;
+        if (T > UINT32_MAX) { delete plan; return KVL_ERANGE; }
+        plan->hit_tokens = T;
+
+        uint64_t xfer_row = 0;
+        uint32_t longest = 0;
+        for (uint32_t r = 0; r < n_req; ++r) {
+            const kvl_request_t &q = req[r];
+            const uint64_t tokens = (uint64_t)q.hit_tokens + q.append_tokens;
+            const uint64_t need = (tokens + bs - 1) / bs;
+            if (q.n_blocks < need) { delete plan; return KVL_ERANGE; }
+            if (need && !q.block_table) { delete plan; return KVL_EINVAL; }
+            for (uint64_t b = 0; b < need; ++b) {
+                const int64_t id = q.block_table[b];
+                if (id < 0 || (uint64_t)id >= layout->pool_blocks) { delete plan; return KVL_ERANGE; }
+            }
+            const uint64_t hit_blocks = ((uint64_t)q.hit_tokens + bs - 1) / bs;
+            if (scatter) {
+                for (uint64_t b = 0; b < hit_blocks; ++b) {
+                    uint8_t &t = taken[(size_t)q.block_table[b]];
+                    if (t) { delete plan; return KVL_EALIAS; }
+                    t = 1;
+                }
+            }
+            // walk the hit blocks, growing a run while the next block is the
+            // physical successor of a full block
+            uint64_t b = 0;
+            while (b < hit_blocks) {
+                const uint64_t first = (uint64_t)q.block_table[b];
+                uint64_t rows = std::min<uint64_t>(bs, q.hit_tokens - b * bs);
+                uint64_t e = b + 1;
+                while (merge && e < hit_blocks && rows == (e - b) * bs &&
+                       (uint64_t)q.block_table[e] == first + (e - b)) {
+                    rows += std::min<uint64_t>(bs, q.hit_tokens - e * bs);
+                    ++e;
+                }
+                // split the run evenly into pieces of at most max_rows rows
+                const uint64_t pieces = (rows + max_rows - 1) / max_rows;
+                const uint64_t base = rows / pieces, extra = rows % pieces;
+                uint64_t pool_row = first * bs;
+                for (uint64_t k = 0; k < pieces; ++k) {
+                    const uint64_t n = base + (k < extra ? 1 : 0);
+                    kvl_unit_t u{(uint32_t)pool_row, (uint32_t)xfer_row, (uint32_t)n, 0};
+                    plan->units.push_back(u);
+                    longest = std::max<uint32_t>(longest, (uint32_t)n);
+                    pool_row += n;
+                    xfer_row += n;
+                }
+                b = e;
+            }
+        }
+        if (plan->units.size() > (size_t)INT32_MAX) { delete plan; return KVL_ERANGE; }
+        plan->max_unit_rows = longest;
+    } catch (const std::bad_alloc &) {
+        delete plan;
+        return KVL_ENOMEM;
+    }
+
+    uint64_t base = 0;
+    for (uint32_t p = 0; p < layout->n_planes; ++p) {
+        plan->plane_base[p] = base;
+        base += plan->hit_tokens * layout->row_bytes[p];
+    }
+    plan->payload_bytes = base;
+
+    if (!(flags & KVL_HOST_ONLY)) {
+        hipError_t e = hipGetDevice(&plan->device);
+        if (e == hipSuccess && !plan->units.empty()) {
+            const size_t bytes = plan->units.size() * sizeof(kvl_unit_t);
+            e = hipMalloc((void **)&plan->d_units, bytes);
+            if (e == hipSuccess)
+                e = hipMemcpy(plan->d_units, plan->units.data(), bytes, hipMemcpyHostToDevice);
+        }
+        if (e != hipSuccess) {
+            set_hip_error(e);
+            kvl_plan_destroy(plan);
+            return KVL_EHIP;
+        }
+    }
+    *out = plan;
+    return KVL_OK;
+}
+
+}  // namespace kvl
+
+extern "C" {
+
+int kvl_plan(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t n_req,
+             uint32_t flags, kvl_plan_t **out) {
+    return kvl::build(layout, requests, n_req, flags, nullptr, out);
+}
+
+int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t n_req,
+                   uint32_t flags, const kvl_tuning_t *tuning, kvl_plan_t **out) {
+    return kvl::build(layout, requests, n_req, flags, tuning, out);
+}
+
+void kvl_plan_destroy(kvl_plan_t *plan) {
+    if (!plan) return;
+    if (plan->d_units) (void)hipFree(plan->d_units);
+    for (hipEvent_t e : plan->ev_landed) (void)hipEventDestroy(e);
+    for (hipEvent_t e : plan->ev_free) (void)hipEventDestroy(e);
+    if (plan->ev_entry) (void)hipEventDestroy(plan->ev_entry);
+    delete plan;
+}
+
+int kvl_plan_set_tuning(kvl_plan_t *plan, const kvl_tuning_t *tuning) {
+    if (!plan || !tuning) return KVL_EINVAL;
+    kvl_tuning_t t = plan->tuning;
+    if (tuning->block_threads) {
+        if (!kvl::valid_block_threads(tuning->block_threads)) return KVL_EINVAL;
+        t.block_threads = tuning->block_threads;
+    }
+    if (tuning->variant >= kvl::kNumVariants) return KVL_EINVAL;
+    t.variant = tuning->variant;
+    plan->tuning = t;
+    return KVL_OK;
+}
+
+int kvl_plan_payload_bytes(const kvl_plan_t *plan, uint64_t *bytes) {
+    if (!plan || !bytes) return KVL_EINVAL;
+    *bytes = plan->payload_bytes;
+    return KVL_OK;
+}
+
+int kvl_plan_hit_tokens(const kvl_plan_t *plan, uint64_t *tokens) {
+    if (!plan || !tokens) return KVL_EINVAL;
+    *tokens = plan->hit_tokens;
+    return KVL_OK;
+}
+
+int kvl_plan_n_units(const kvl_plan_t *plan, uint64_t *n) {
+    if (!plan || !n) return KVL_EINVAL;
+    *n = plan->units.size();
+    return KVL_OK;
+}
+
+int kvl_plan_get_units(const kvl_plan_t *plan, kvl_unit_t *out, uint64_t capacity, uint64_t *n) {
+    if (!plan || !n || (capacity && !out)) return KVL_EINVAL;
+    *n = plan->units.size();
+    const size_t k = (size_t)std::min<uint64_t>(capacity, plan->units.size());
+    if (k) std::memcpy(out, plan->units.data(), k * sizeof(kvl_unit_t));
+    return KVL_OK;
+}
+
+int kvl_plan_get_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, kvl_chunk_t *out,
+                        uint64_t capacity, uint64_t *n) {
+    if (!plan || !n || (capacity && !out)) return KVL_EINVAL;
+    std::vector<kvl_chunk_t> c;
+    int rc;
+    try {
+        rc = kvl::make_chunks(plan, chunk_bytes, c);
+    } catch (const std::bad_alloc &) {
+        return KVL_ENOMEM;
+    }
+    if (rc != KVL_OK) return rc;
+    *n = c.size();
+    const size_t k = (size_t)std::min<uint64_t>(capacity, c.size());
+    if (k) std::memcpy(out, c.data(), k * sizeof(kvl_chunk_t));
+    return KVL_OK;
+}
+
+const char *kvl_strerror(int code) {
+    switch (code) {
+        case KVL_OK: return "ok";
+        case KVL_EINVAL: return "invalid argument";
+        case KVL_ERANGE: return "block id, table length or size out of range";
+        case KVL_EALIAS: return "destination block named twice in a scatter plan";
+        case KVL_ESPACE: return "buffer, staging area or chunk too small";
+        case KVL_EHIP: return "HIP call failed";
+        case KVL_ENOMEM: return "out of host memory";
+        default: return "unknown kvl error";
+    }
+}
+
+int kvl_last_hip_error(void) { return (int)kvl::g_last_hip; }
+
+const char *kvl_last_hip_error_string(void) { return hipGetErrorString(kvl::g_last_hip); }
+
+const char *kvl_version(void) { return "kvl 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,212 @@
+// Layer-wise streamed load: the host-buffer load of layer l+1 runs under the
+// compute of layer l (Section 4.1: transfers overlap the forward pass; with
+// layer-wise prefill only a few layers' cache is resident at a time).
+//
+// Three streams and a handful of events carry the ordering:
+//   copy stream    host -> staging chunks, throttled by the staging ring
+//   kernel stream  scatter of each landed chunk; the first scatter of layer l
+//                  waits for "compute of layer l - S finished" (the slot it is
+//                  about to overwrite is no longer being read)
+//   compute stream compute(l) waits for "layer l loaded"
+#include <algorithm>
+#include <vector>
+
+#include "kvl_internal.h"
+
+namespace kvl {
+
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+int enqueue_h2d_layer(kvl_plan_t *plan, const std::vector<kvl_chunk_t> &chunks,
+                      const void *host_xfer, void *dev_staging, uint64_t chunk_bytes, size_t slots,
+                      void *const *pool_planes, hipStream_t copy_s, hipStream_t kern_s,
+                      hipEvent_t wait_before_scatter, size_t *ring_pos);
+int check_h2d_args(const kvl_plan_t *plan, const void *host, const void *staging,
+                   uint64_t staging_bytes, uint64_t chunk_bytes, size_t *slots);
+
+struct SlotPlanes {
+    uintptr_t base[KVL_MAX_PLANES];
+};
+
+// Stand-in for one layer's forward computation: samples what it can see of the
+// loaded cache, then holds the compute stream for a fixed time on the device's
+// constant-rate wall clock.  One wavefront; the spin ends on the clock or, as a
+// backstop, after max_polls polls.
+__global__ void __launch_bounds__(64) kvl_compute_kernel(SlotPlanes slot, const kvl_probe_t *probes,
+                                                         uint32_t n_probes, v4u *probe_out,
+                                                         uint64_t ticks, uint32_t max_polls) {
+    for (uint32_t i = threadIdx.x; i < n_probes; i += blockDim.x) {
+        const kvl_probe_t pr = probes[i];
+        probe_out[i] = *reinterpret_cast<const v4u *>(slot.base[pr.plane] + pr.byte_offset);
+    }
+    if (threadIdx.x == 0) {
+        const uint64_t t0 = wall_clock64();
+        for (uint32_t k = 0; k < max_polls; ++k) {
+            if (wall_clock64() - t0 >= ticks) break;
+            __builtin_amdgcn_s_sleep(8);
+        }
+    }
+}
+
+struct RunState {
+    std::vector<hipEvent_t> events;
+    kvl_probe_t *d_probes = nullptr;
+    hipStream_t streams[3] = {nullptr, nullptr, nullptr};
+
+    int make(hipEvent_t *e, bool timing) {
+        KVL_HIP(hipEventCreateWithFlags(e, timing ? hipEventDefault : hipEventDisableTiming));
+        events.push_back(*e);
+        return KVL_OK;
+    }
+    ~RunState() {
+        // nothing enqueued by the run may outlive what it refers to
+        for (hipStream_t s : streams) (void)hipStreamSynchronize(s);
+        for (hipEvent_t e : events) (void)hipEventDestroy(e);
+        if (d_probes) (void)hipFree(d_probes);
+    }
+};
+
+}  // namespace kvl
+
+extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg,
+                                 kvl_stream_stats_t *stats) {
+    using namespace kvl;
+    kvl_plan_t *plan = const_cast<kvl_plan_t *>(plan_c);
+    if (!plan || !cfg) return KVL_EINVAL;
+    const uint32_t L = cfg->n_layers ? cfg->n_layers : plan->layout.n_layers;
+    const uint32_t H = cfg->n_host_slots, S = cfg->n_dev_slots, P = plan->layout.n_planes;
+    if (L == 0 || H == 0 || S == 0 || !cfg->host_layers || !cfg->dev_slot_planes) return KVL_EINVAL;
+    if (cfg->compute_us > 1000000u) return KVL_EINVAL;
+    if (cfg->n_probes && (!cfg->probes || !cfg->probe_out)) return KVL_EINVAL;
+    size_t slots = 0;
+    int rc = check_h2d_args(plan, cfg->host_layers[0], cfg->dev_staging, cfg->staging_bytes,
+                            cfg->chunk_bytes, &slots);
+    if (rc != KVL_OK) return rc;
+    for (uint32_t h = 0; h < H; ++h)
+        if (!cfg->host_layers[h] && !plan->units.empty()) return KVL_EINVAL;
+    for (uint32_t i = 0; i < S * P; ++i)
+        if (!cfg->dev_slot_planes[i]) return KVL_EINVAL;
+    for (uint32_t i = 0; i < cfg->n_probes; ++i) {
+        const kvl_probe_t &pr = cfg->probes[i];
+        const uint64_t plane_bytes = plan->layout.pool_blocks * plan->layout.block_tokens *
+                                     (uint64_t)plan->layout.row_bytes[pr.plane < P ? pr.plane : 0];
+        if (pr.plane >= P || pr.byte_offset % 16 || pr.byte_offset + 16 > plane_bytes) return KVL_EINVAL;
+    }
+
+    std::vector<kvl_chunk_t> chunks;
+    try {
+        rc = make_chunks(plan, cfg->chunk_bytes, chunks);
+    } catch (const std::bad_alloc &) {
+        return KVL_ENOMEM;
+    }
+    if (rc != KVL_OK) return rc;
+    rc = ensure_ring_events(plan, slots);
+    if (rc != KVL_OK) return rc;
+
+    hipStream_t cs = (hipStream_t)cfg->copy_stream, ks = (hipStream_t)cfg->kernel_stream,
+                ms = (hipStream_t)cfg->compute_stream;
+    int clock_khz = 0;
+    KVL_HIP(hipDeviceGetAttribute(&clock_khz, hipDeviceAttributeWallClockRate, plan->device));
+    if (clock_khz <= 0) clock_khz = 100000;
+    const uint64_t ticks = (uint64_t)cfg->compute_us * (uint64_t)clock_khz / 1000u;
+    // each poll sleeps a fraction of a microsecond; this bound is far beyond compute_us
+    const uint32_t max_polls = cfg->compute_us * 64u + 1024u;
+
+    RunState st;
+    st.streams[0] = cs; st.streams[1] = ks; st.streams[2] = ms;
+    hipEvent_t ev_start = nullptr, ev_sync = nullptr;
+    std::vector<hipEvent_t> loaded(L), cbeg(L), cend(L), h2d_done(L);
+    try {
+        st.events.reserve(4 * (size_t)L + 2);
+    } catch (const std::bad_alloc &) {
+        return KVL_ENOMEM;
+    }
+    if ((rc = st.make(&ev_start, true)) != KVL_OK) return rc;
+    if ((rc = st.make(&ev_sync, false)) != KVL_OK) return rc;
+    for (uint32_t l = 0; l < L; ++l) {
+        if ((rc = st.make(&loaded[l], true)) != KVL_OK) return rc;
+        if ((rc = st.make(&cbeg[l], true)) != KVL_OK) return rc;
+        if ((rc = st.make(&cend[l], true)) != KVL_OK) return rc;
+        if ((rc = st.make(&h2d_done[l], false)) != KVL_OK) return rc;
+    }
+    if (cfg->n_probes) {
+        const size_t bytes = cfg->n_probes * sizeof(kvl_probe_t);
+        KVL_HIP(hipMalloc((void **)&st.d_probes, bytes));
+        KVL_HIP(hipMemcpy(st.d_probes, cfg->probes, bytes, hipMemcpyHostToDevice));
+    }
+
+    // start line: the copy stream begins after whatever the other two hold
+    KVL_HIP(hipEventRecord(ev_sync, ks));
+    KVL_HIP(hipStreamWaitEvent(cs, ev_sync, 0));
+    KVL_HIP(hipEventRecord(plan->ev_entry, ms));
+    KVL_HIP(hipStreamWaitEvent(cs, plan->ev_entry, 0));
+    KVL_HIP(hipEventRecord(ev_start, cs));
+    KVL_HIP(hipStreamWaitEvent(ks, ev_start, 0));
+    KVL_HIP(hipStreamWaitEvent(ms, ev_start, 0));
+
+    size_t ring_pos = 0;
+    for (uint32_t l = 0; l < L; ++l) {
+        const uint32_t h = l % H, s = l % S;
+        void *host_slot = cfg->host_layers[h];
+        if (cfg->host_fill) {
+            if (l >= H) KVL_HIP(hipEventSynchronize(h2d_done[l - H]));
+            if (cfg->host_fill(cfg->host_fill_user, l, host_slot, plan->payload_bytes) != 0)
+                return KVL_EINVAL;
+        }
+        void *const *slot_planes = cfg->dev_slot_planes + (size_t)s * P;
+        rc = enqueue_h2d_layer(plan, chunks, host_slot, cfg->dev_staging, cfg->chunk_bytes, slots,
+                               slot_planes, cs, ks, l >= S ? cend[l - S] : nullptr, &ring_pos);
+        if (rc != KVL_OK) return rc;
+        KVL_HIP(hipEventRecord(h2d_done[l], cs));
+        KVL_HIP(hipEventRecord(loaded[l], ks));
+
+        KVL_HIP(hipStreamWaitEvent(ms, loaded[l], 0));
+        KVL_HIP(hipEventRecord(cbeg[l], ms));
+        SlotPlanes sp{};
+        for (uint32_t p = 0; p < P; ++p) sp.base[p] = reinterpret_cast<uintptr_t>(slot_planes[p]);
+        v4u *pout = cfg->n_probes
+                        ? static_cast<v4u *>(cfg->probe_out) + (size_t)l * cfg->n_probes
+                        : nullptr;
+        hipLaunchKernelGGL(kvl_compute_kernel, dim3(1), dim3(64), 0, ms, sp, st.d_probes,
+                           cfg->n_probes, pout, ticks, max_polls);
+        KVL_HIP(hipGetLastError());
+        if (cfg->snapshot_planes) {
+            for (uint32_t p = 0; p < P; ++p) {
+                void *snap = cfg->snapshot_planes[(size_t)l * P + p];
+                if (!snap) continue;
+                const uint64_t bytes = plan->layout.pool_blocks * plan->layout.block_tokens *
+                                       (uint64_t)plan->layout.row_bytes[p];
+                KVL_HIP(hipMemcpyAsync(snap, slot_planes[p], bytes, hipMemcpyDeviceToDevice, ms));
+            }
+        }
+        KVL_HIP(hipEventRecord(cend[l], ms));
+    }
+    KVL_HIP(hipEventSynchronize(cend[L - 1]));
+    KVL_HIP(hipStreamSynchronize(ks));
+    KVL_HIP(hipStreamSynchronize(cs));
+
+    if (stats) {
+        float total = 0.f;
+        KVL_HIP(hipEventElapsedTime(&total, ev_start, cend[L - 1]));
+        stats->total_ms = total;
+        stats->h2d_bytes = (double)plan->payload_bytes * L;
+        stats->link_gbps = total > 0.f ? stats->h2d_bytes / (total * 1e-3) / 1e9 : 0.0;
+        stats->exposed_ms = total - (double)L * cfg->compute_us * 1e-3;
+        for (uint32_t l = 0; l < L; ++l) {
+            float t = 0.f;
+            if (stats->t_loaded) {
+                KVL_HIP(hipEventElapsedTime(&t, ev_start, loaded[l]));
+                stats->t_loaded[l] = t;
+            }
+            if (stats->t_compute_begin) {
+                KVL_HIP(hipEventElapsedTime(&t, ev_start, cbeg[l]));
+                stats->t_compute_begin[l] = t;
+            }
+            if (stats->t_compute_end) {
+                KVL_HIP(hipEventElapsedTime(&t, ev_start, cend[l]));
+                stats->t_compute_end[l] = t;
+            }
+        }
+    }
+    return KVL_OK;
+}

@@ -1,0 +1,50 @@
+"""The C-ABI library loads without a GPU and exports every symbol the header declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "kvl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)            # drop comments
+    names = re.findall(r"^\s*(?:const\s+)?[A-Za-z_][\w\s]*?[\s\*]+(kvl_\w+)\s*\(", text, flags=re.M)
+    return sorted(set(n for n in names if not n.endswith("_fn")))
+
+
+def test_header_lists_the_entry_points():
+    fns = declared_functions()
+    for must in ("kvl_plan", "kvl_pack_layer", "kvl_unpack_layer", "kvl_h2d_unpack_layer", "kvl_stream_layers"):
+        assert must in fns
+    assert len(fns) >= 15
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2602_21548_amd import binding as B
+    assert os.path.exists(B.LIB_PATH)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in kvl.h but not exported"
+    # and the binding wraps exactly the declared set
+    assert sorted(B._SIGNATURES) == declared_functions()
+
+
+def test_strerror_and_versions():
+    import paper_2602_21548_amd as K
+    assert K.kvl_strerror(0) == "ok"
+    for code in (K.KVL_EINVAL, K.KVL_ERANGE, K.KVL_EALIAS, K.KVL_ESPACE, K.KVL_EHIP, K.KVL_ENOMEM):
+        assert K.kvl_strerror(code) not in ("ok", "unknown kvl error")
+    assert K.kvl_strerror(-99) == "unknown kvl error"
+    assert "gfx950" in K.kvl_version()
+    assert K.kvl_variant_name(0) and K.kvl_variant_name(15) and K.kvl_variant_name(16) is None
+
+
+def test_struct_sizes_match_the_header():
+    from paper_2602_21548_amd import binding as B
+    assert ctypes.sizeof(B.kvl_unit_t) == 16
+    assert ctypes.sizeof(B.kvl_layout_t) == 40
+    assert ctypes.sizeof(B.kvl_request_t) == 24
+    assert ctypes.sizeof(B.kvl_chunk_t) == 32
+    assert ctypes.sizeof(B.kvl_probe_t) == 16
+    assert ctypes.sizeof(B.kvl_tuning_t) == 16

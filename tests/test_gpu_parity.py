@@ -1,0 +1,282 @@
+"""GPU parity: the HIP path against the CPU oracle, bit for bit, through the C ABI.
+
+Every payload is an opaque byte copy, so the bar is exact equality of every
+byte (compared as bytes, never as floats: NaN patterns must survive).
+"""
+import numpy as np
+import pytest
+import torch
+
+import kvl_workloads as W
+import oracle
+import paper_2602_21548_amd as K
+from gpu_util import dev_plan, pinned_from, planes_to_dev, same_bytes, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+GUARD = 4096
+
+CASES = [
+    ("tiny-random", lambda: W.tiny(201, 6, 16, (48,), 64, 90)),
+    ("tiny-runs-2planes", lambda: W.tiny(202, 7, 4, (32, 16), 200, 60, kind="runs")),
+    ("tiny-contig", lambda: W.tiny(203, 5, 8, (16,), 100, 120, kind="contiguous")),
+    ("tiny-oddrow", lambda: W.tiny(204, 4, 3, (5,), 60, 40)),              # byte fallback kernel
+    ("tiny-row-mult-of-4", lambda: W.tiny(205, 4, 8, (36,), 60, 100)),     # byte fallback kernel
+    ("tiny-3planes", lambda: W.tiny(206, 5, 16, (16, 656, 64), 40, 150)),
+    ("cfg1", lambda: W.config(1)),
+    ("cfg2-small", lambda: W.config(2, n_requests=7, token_scale=1 / 32)),
+    ("cfg3-small", lambda: W.config(3, n_requests=12, token_scale=1 / 16)),
+    ("cfg4-small", lambda: W.config(4, n_requests=12, token_scale=1 / 32)),
+]
+
+
+def run_hop(w, layer=0, **tuning):
+    """pack on the source pool, unpack into a sentinel pool; compare both with the oracle."""
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    src = W.fill_pool(w, layer, "src")
+    want_x = oracle.pack(bs, rows, w.hit, w.src.tables, src, threads=8)
+    want_dst = W.sentinel_pool(w, "dst")
+    oracle.unpack(bs, rows, w.hit, w.dst.tables, want_x, want_dst, threads=8)
+
+    g = dev_plan(w, "src", K.KVL_GATHER, **tuning)
+    s = dev_plan(w, "dst", K.KVL_SCATTER, **tuning)
+    n = g.payload_bytes
+    assert n == want_x.size == s.payload_bytes
+    d_src = planes_to_dev(src)
+    d_x = torch.full((n + GUARD,), 0x3C, dtype=torch.uint8, device="cuda")
+    K.kvl_pack_layer(g, d_src, d_x)
+    d_dst = planes_to_dev(W.sentinel_pool(w, "dst"))
+    K.kvl_unpack_layer(s, d_x, d_dst)
+    torch.cuda.synchronize()
+    got_x = to_host(d_x)
+    assert same_bytes(got_x[:n], want_x), "pack differs from the oracle"
+    assert np.all(got_x[n:] == 0x3C), "pack wrote past the payload"
+    for p, (a, b) in enumerate(zip(d_dst, want_dst)):
+        assert same_bytes(to_host(a), b), f"unpack differs from the oracle in plane {p}"
+    for a, b in zip(d_src, src):
+        assert same_bytes(to_host(a), b), "pack modified its source"
+    g.destroy()
+    s.destroy()
+
+
+@pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
+def test_pack_unpack_default(name, make):
+    run_hop(make())
+
+
+@pytest.mark.parametrize("variant", range(16))
+@pytest.mark.parametrize("threads", [64, 256, 1024])
+def test_every_variant(variant, threads):
+    # units of 5 KiB against 64..1024 threads x 4..8 vectors: full steps, ragged tails and idle lanes
+    w = W.config(3, n_requests=6, token_scale=1 / 64)
+    run_hop(w, layer=variant % 3, variant=variant, block_threads=threads, unit_bytes=5 * 1152)
+
+
+@pytest.mark.parametrize("unit_bytes", [1152, 16 * 1152, 64 * 1152, 1 << 20])
+def test_unit_sizes(unit_bytes):
+    w = W.tiny(207, 10, 64, (1152,), 400, 1500, kind="runs")
+    run_hop(w, unit_bytes=unit_bytes)
+    run_hop(w, unit_bytes=unit_bytes, variant=1)
+
+
+def test_layers_are_independent_pools():
+    w = W.config(1)
+    for layer in range(w.layout.n_layers):
+        run_hop(w, layer=layer)
+
+
+def test_nan_and_inf_patterns_survive():
+    w = W.tiny(208, 3, 16, (32,), 16, 60)
+    bs, rows = 16, (32,)
+    pool = np.zeros(16 * 16 * 32, dtype=np.uint8)
+    v = pool.view(np.uint16)
+    v[0::4], v[1::4], v[2::4], v[3::4] = 0x7FC1, 0xFF80, 0x7F80, 0xFFFF     # bf16 NaN, -inf, +inf, NaN
+    want = oracle.pack(bs, rows, w.hit, w.src.tables, [pool])
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    d_x = torch.zeros(g.payload_bytes, dtype=torch.uint8, device="cuda")
+    K.kvl_pack_layer(g, [to_dev(pool)], d_x)
+    assert same_bytes(to_host(d_x), want)
+
+
+def test_empty_and_zero_hit_batches():
+    lay = K.make_layout(1, 16, (32,), 8)
+    pool = torch.full((8 * 16 * 32,), 7, dtype=torch.uint8, device="cuda")
+    x = torch.full((64,), 9, dtype=torch.uint8, device="cuda")
+    for hit, app, tabs in (([], [], []), ([0, 0], [0, 5], [np.zeros(0, np.int32), np.array([3], np.int32)])):
+        g = K.kvl_plan(lay, hit, app, tabs, K.KVL_GATHER | K.KVL_SCATTER)
+        assert g.payload_bytes == 0
+        K.kvl_pack_layer(g, [pool], x)
+        K.kvl_unpack_layer(g, x, [pool])
+        torch.cuda.synchronize()
+        assert torch.all(pool == 7) and torch.all(x == 9)
+
+
+def test_errors_from_the_device_entry_points():
+    w = W.tiny(209, 3, 16, (32,), 32, 60, allow_zero_hit=False)
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    pool = [torch.zeros(32 * 16 * 32, dtype=torch.uint8, device="cuda")]
+    small = torch.zeros(g.payload_bytes - 16, dtype=torch.uint8, device="cuda")
+    full = torch.zeros(g.payload_bytes, dtype=torch.uint8, device="cuda")
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_pack_layer(g, pool, small)
+    assert e.value.code == K.KVL_ESPACE
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_unpack_layer(s, small, pool)
+    assert e.value.code == K.KVL_ESPACE
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_pack_layer(s, pool, full)            # scatter plan used to gather
+    assert e.value.code == K.KVL_EINVAL
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_unpack_layer(g, full, pool)          # gather plan used to scatter
+    assert e.value.code == K.KVL_EINVAL
+    with pytest.raises(ValueError):                # the binding knows the pool is too small
+        K.kvl_pack_layer(g, [pool[0][:100]], full)
+
+
+def test_misaligned_buffers_take_the_byte_path():
+    w = W.tiny(210, 4, 16, (48,), 40, 100)
+    bs, rows = 16, (48,)
+    src = W.fill_pool(w, 0, "src")
+    want = oracle.pack(bs, rows, w.hit, w.src.tables, src)
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    big = torch.zeros(src[0].size + 16, dtype=torch.uint8, device="cuda")
+    big[3:3 + src[0].size] = to_dev(src[0])
+    xb = torch.zeros(want.size + 16, dtype=torch.uint8, device="cuda")
+    K.kvl_pack_layer(g, [big[3:3 + src[0].size]], xb[5:5 + want.size])
+    assert same_bytes(to_host(xb[5:5 + want.size]), want)
+    assert int(xb[:5].sum()) == 0 and int(xb[5 + want.size:].sum()) == 0
+
+
+def test_non_default_stream():
+    w = W.config(1)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    src = W.fill_pool(w, 1, "src")
+    want = oracle.pack(bs, rows, w.hit, w.src.tables, src)
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    d_src = planes_to_dev(src)
+    d_x = torch.zeros(g.payload_bytes, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    K.kvl_pack_layer(g, d_src, d_x, stream=st)
+    st.synchronize()
+    assert same_bytes(to_host(d_x), want)
+
+
+def test_copy_linear():
+    a = to_dev(np.random.Generator(np.random.PCG64(1)).integers(0, 256, size=(1 << 20) + 4096 + 16, dtype=np.uint8))
+    b = torch.zeros_like(a)
+    K.kvl_copy_linear(a, b)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+# --------------------------------------------------------------------------
+# host buffer -> HBM
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,make", [CASES[1], CASES[3], CASES[6], CASES[7], CASES[9]],
+                         ids=[CASES[i][0] for i in (1, 3, 6, 7, 9)])
+@pytest.mark.parametrize("chunk_kb,slots", [(64, 1), (64, 3), (1024, 2)])
+def test_h2d_unpack(name, make, chunk_kb, slots):
+    w = make()
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    n = oracle.payload_bytes(w.hit, rows)
+    x = W.random_payload(w, 0, n)
+    want = W.sentinel_pool(w, "dst")
+    oracle.unpack(bs, rows, w.hit, w.dst.tables, x, want)
+    s = dev_plan(w, "dst", K.KVL_SCATTER, unit_bytes=16384)
+    host = pinned_from(x)
+    chunk = chunk_kb * 1024
+    staging = torch.zeros(chunk * slots, dtype=torch.uint8, device="cuda")
+    d_dst = planes_to_dev(W.sentinel_pool(w, "dst"))
+    torch.cuda.synchronize()
+    cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+    K.kvl_h2d_unpack_layer(s, host, staging, chunk, d_dst, cs, ks)
+    # a second layer through the same staging ring, queued at once
+    x2 = W.random_payload(w, 1, n)
+    host2 = pinned_from(x2)
+    d_dst2 = planes_to_dev(W.sentinel_pool(w, "dst"))
+    K.kvl_h2d_unpack_layer(s, host2, staging, chunk, d_dst2, cs, ks)
+    ks.synchronize()
+    cs.synchronize()
+    for a, b in zip(d_dst, want):
+        assert same_bytes(to_host(a), b)
+    want2 = W.sentinel_pool(w, "dst")
+    oracle.unpack(bs, rows, w.hit, w.dst.tables, x2, want2)
+    for a, b in zip(d_dst2, want2):
+        assert same_bytes(to_host(a), b)
+
+
+def test_h2d_errors():
+    w = W.tiny(211, 3, 16, (32,), 32, 60, allow_zero_hit=False)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    host = torch.zeros(s.payload_bytes, dtype=torch.uint8, pin_memory=True)
+    pool = [torch.zeros(32 * 16 * 32, dtype=torch.uint8, device="cuda")]
+    staging = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_h2d_unpack_layer(s, host, staging, 1 << 17, pool, cs, ks)    # staging smaller than a chunk
+    assert e.value.code == K.KVL_ESPACE
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_h2d_unpack_layer(s, host, staging, 16, pool, cs, ks)         # chunk smaller than a descriptor
+    assert e.value.code == K.KVL_ESPACE
+    with pytest.raises(TypeError):
+        K.kvl_h2d_unpack_layer(s, torch.zeros(s.payload_bytes, dtype=torch.uint8), staging, 1 << 16, pool, cs, ks)
+
+
+# --------------------------------------------------------------------------
+# layer-wise streaming
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("S", [1, 2, 3])
+@pytest.mark.parametrize("H", [1, 2, 6])
+def test_stream_layers_observables(S, H):
+    L = 6
+    w = W.tiny(212, 6, 16, (64, 32), 96, 200, n_layers=L)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    n = oracle.payload_bytes(w.hit, rows)
+    payloads = [W.random_payload(w, l, n) for l in range(L)]
+    # oracle: what the compute of each layer must see in its slot
+    o_slots = [W.sentinel_pool(w, "dst", 0xEE) for _ in range(S)]
+    o_host = [np.zeros(n, np.uint8) for _ in range(H)]
+    want = []
+    gen = oracle.stream_layers(bs, rows, w.hit, w.dst.tables, o_host, L, o_slots)
+    for l in range(L):
+        o_host[l % H][:] = payloads[l]
+        _, s_idx, planes = next(gen)
+        want.append([p.copy() for p in planes])
+
+    s = dev_plan(w, "dst", K.KVL_SCATTER, unit_bytes=4096)
+    host = [torch.zeros(n, dtype=torch.uint8, pin_memory=True) for _ in range(H)]
+    slots = [planes_to_dev(W.sentinel_pool(w, "dst", 0xEE)) for _ in range(S)]
+    snaps = [[torch.zeros_like(pl) for pl in slots[0]] for _ in range(L)]
+    # probes: first 16 bytes of a few rows
+    probes = [(0, 0), (1, 32 * 5), (0, 64 * 17)]
+    probe_out = torch.zeros(L * len(probes) * 16, dtype=torch.uint8, device="cuda")
+    staging = torch.zeros(3 * 8192, dtype=torch.uint8, device="cuda")
+    filled = []
+
+    def fill(layer, slot):
+        host[slot].numpy()[:] = payloads[layer]
+        filled.append((layer, slot))
+
+    torch.cuda.synchronize()
+    cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    st = K.kvl_stream_layers(s, host, slots, staging, 8192, 50, cs, ks, ms, n_layers=L, probes=probes,
+                             probe_out=probe_out, snapshots=snaps, host_fill=fill, per_layer_times=True)
+    assert filled == [(l, l % H) for l in range(L)]
+    for l in range(L):
+        for p in range(len(rows)):
+            assert same_bytes(to_host(snaps[l][p]), want[l][p]), f"layer {l} plane {p}: compute saw the wrong cache"
+    po = to_host(probe_out).reshape(L, len(probes), 16)
+    for l in range(L):
+        for i, (pl, off) in enumerate(probes):
+            assert po[l, i].tobytes() == want[l][pl][off:off + 16].tobytes()
+    # ordering on the device clock: compute(l) after load(l); compute takes >= 50 us; layers in order
+    tl, tb, te = st["t_loaded"], st["t_compute_begin"], st["t_compute_end"]
+    assert np.all(tb >= tl - 1e-3)
+    assert np.all(te - tb >= 0.045)
+    assert np.all(np.diff(tb) > 0)
+    assert st["total_ms"] >= L * 0.05
+    assert st["h2d_bytes"] == n * L

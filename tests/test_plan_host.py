@@ -1,0 +1,190 @@
+"""Host logic of the library (no GPU): kvl_plan's descriptors, checked against the oracle.
+
+A KVL_HOST_ONLY plan yields the copy descriptors without touching a device.
+Replaying them with NumPy slices (a row-span copy per descriptor, which is all
+a descriptor means) must reproduce the oracle's pack and unpack bit for bit.
+"""
+import numpy as np
+import pytest
+
+import kvl_workloads as W
+import oracle
+import paper_2602_21548_amd as K
+
+
+def host_plan(w, side, flags, **tuning):
+    s = w.src if side == "src" else w.dst
+    lay = K.make_layout(w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes, s.pool_blocks)
+    return K.kvl_plan(lay, w.hit, w.app, s.tables, flags | K.KVL_HOST_ONLY, **tuning)
+
+
+def replay_pack(plan, row_bytes, pools):
+    T = plan.hit_tokens
+    out = np.zeros(plan.payload_bytes, dtype=np.uint8)
+    base = 0
+    for p, row in enumerate(row_bytes):
+        for pool_row, xfer_row, n, _ in plan.units():
+            a, b, k = int(pool_row) * row, base + int(xfer_row) * row, int(n) * row
+            out[b:b + k] = pools[p][a:a + k]
+        base += T * row
+    return out
+
+
+def replay_unpack(plan, row_bytes, xfer, pools):
+    T = plan.hit_tokens
+    base = 0
+    for p, row in enumerate(row_bytes):
+        for pool_row, xfer_row, n, _ in plan.units():
+            a, b, k = int(pool_row) * row, base + int(xfer_row) * row, int(n) * row
+            pools[p][a:a + k] = xfer[b:b + k]
+        base += T * row
+
+
+CASES = [
+    ("tiny-random", lambda: W.tiny(101, 6, 16, (48,), 64, 90)),
+    ("tiny-runs-2planes", lambda: W.tiny(102, 7, 4, (32, 16), 200, 60, kind="runs")),
+    ("tiny-contig", lambda: W.tiny(103, 5, 8, (16,), 100, 120, kind="contiguous")),
+    ("tiny-oddrow", lambda: W.tiny(104, 4, 3, (5,), 60, 40)),
+    ("cfg1", lambda: W.config(1)),
+    ("cfg2-small", lambda: W.config(2, n_requests=5, token_scale=1 / 128)),
+    ("cfg3-small", lambda: W.config(3, n_requests=8, token_scale=1 / 64)),
+    ("cfg4-small", lambda: W.config(4, n_requests=8, token_scale=1 / 128)),
+]
+
+
+@pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("unit_bytes", [0, 4096, 1 << 20])
+def test_descriptors_reproduce_the_oracle(name, make, unit_bytes):
+    w = make()
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    g = host_plan(w, "src", K.KVL_GATHER, unit_bytes=unit_bytes)
+    assert g.payload_bytes == oracle.payload_bytes(w.hit, rows)
+    assert g.hit_tokens == oracle.total_hit_tokens(w.hit)
+    src = W.fill_pool(w, 0, "src")
+    want = oracle.pack(bs, rows, w.hit, w.src.tables, src)
+    assert replay_pack(g, rows, src).tobytes() == want.tobytes()
+
+    s = host_plan(w, "dst", K.KVL_SCATTER, unit_bytes=unit_bytes)
+    got = W.sentinel_pool(w, "dst")
+    ref = W.sentinel_pool(w, "dst")
+    replay_unpack(s, rows, want, got)
+    oracle.unpack(bs, rows, w.hit, w.dst.tables, want, ref)
+    for a, b in zip(got, ref):
+        assert a.tobytes() == b.tobytes()
+
+
+def test_descriptors_tile_the_transfer_buffer():
+    w = W.tiny(105, 9, 16, (64,), 300, 200, kind="runs")
+    for ub in (0, 256, 2048, 1 << 16):
+        p = host_plan(w, "src", K.KVL_GATHER, unit_bytes=ub)
+        u = p.units().astype(np.int64)
+        assert np.all(u[:, 2] > 0)
+        assert u[0, 1] == 0
+        assert np.array_equal(u[1:, 1], u[:-1, 1] + u[:-1, 2])       # dense, in order
+        assert u[-1, 1] + u[-1, 2] == p.hit_tokens
+        max_rows = max(1, (ub or (64 << 10)) // 64)
+        assert u[:, 2].max() <= max_rows
+        assert np.all(u[:, 0] + u[:, 2] <= w.src.pool_blocks * 16)
+
+
+def test_merging_of_adjacent_blocks():
+    bs, row = 16, 32
+    lay = K.make_layout(1, bs, (row,), 64)
+    tbl = [np.arange(10, 30, dtype=np.int32)]                  # 20 physically consecutive blocks
+    hit, app = [20 * bs - 3], [0]
+    merged = K.kvl_plan(lay, hit, app, tbl, K.KVL_GATHER | K.KVL_HOST_ONLY, unit_bytes=1 << 20)
+    assert merged.n_units == 1 and merged.units()[0].tolist()[:3] == [10 * bs, 0, 20 * bs - 3]
+    split = K.kvl_plan(lay, hit, app, tbl, K.KVL_GATHER | K.KVL_HOST_ONLY, unit_bytes=bs * row * 4)
+    n = split.units()[:, 2]
+    assert split.n_units == 5 and n.max() - n.min() <= 1      # even split
+    single = K.kvl_plan(lay, hit, app, tbl, K.KVL_GATHER | K.KVL_HOST_ONLY | K.KVL_NO_MERGE, unit_bytes=1 << 20)
+    assert single.n_units == 20
+    # a descending table has no run to merge
+    rev = K.kvl_plan(lay, hit, app, [tbl[0][::-1].copy()], K.KVL_GATHER | K.KVL_HOST_ONLY, unit_bytes=1 << 20)
+    assert rev.n_units == 20
+    # fully fragmented tables: one descriptor per block
+    w = W.config(4, n_requests=6, token_scale=1 / 64)
+    p = host_plan(w, "src", K.KVL_GATHER, unit_bytes=64 * 656)
+    assert p.n_units == sum(-(-int(h) // 64) for h in w.hit)
+
+
+ERR = {oracle.OK: K.KVL_OK, oracle.E_TABLE: K.KVL_ERANGE, oracle.E_BLOCK: K.KVL_ERANGE, oracle.E_DUP: K.KVL_EALIAS}
+
+
+@pytest.mark.parametrize("case", [
+    dict(hit=[9, 2], app=[1, 2], tables=[[1, 2, 3], [5]]),
+    dict(hit=[9, 2], app=[4, 2], tables=[[1, 2, 3], [5]]),            # table too short
+    dict(hit=[9, 2], app=[1, 2], tables=[[1, 2, 10], [5]]),           # id == pool_blocks
+    dict(hit=[9, 2], app=[1, 2], tables=[[1, -1, 3], [5]]),           # negative id
+    dict(hit=[9, 2], app=[1, 2], tables=[[1, 2, 3], [2]]),            # duplicate destination
+    dict(hit=[8, 2], app=[4, 6], tables=[[1, 2, 3], [5, 3]]),         # shared block holds appended rows only
+    dict(hit=[0, 0], app=[0, 3], tables=[[], [7]]),
+])
+def test_validation_agrees_with_the_oracle(case):
+    bs, pool = 4, 10
+    lay = K.make_layout(1, bs, (16,), pool)
+    tabs = [np.array(t, dtype=np.int32) for t in case["tables"]]
+    for scatter in (False, True):
+        want = ERR[oracle.check(bs, pool, case["hit"], case["app"], tabs, scatter)]
+        flags = (K.KVL_SCATTER if scatter else K.KVL_GATHER) | K.KVL_HOST_ONLY
+        try:
+            K.kvl_plan(lay, case["hit"], case["app"], tabs, flags)
+            got = K.KVL_OK
+        except K.KvlError as e:
+            got = e.code
+        assert got == want, (case, scatter)
+
+
+def test_argument_errors():
+    tabs = [np.array([0], np.int32)]
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_plan(K.make_layout(1, 0, (16,), 4), [1], [0], tabs, K.KVL_GATHER | K.KVL_HOST_ONLY)
+    assert e.value.code == K.KVL_EINVAL
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_plan(K.make_layout(1, 4, (0,), 4), [1], [0], tabs, K.KVL_GATHER | K.KVL_HOST_ONLY)
+    assert e.value.code == K.KVL_EINVAL
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_plan(K.make_layout(1, 4, (16,), 4), [1], [0], tabs, K.KVL_HOST_ONLY)      # neither gather nor scatter
+    assert e.value.code == K.KVL_EINVAL
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_plan(K.make_layout(1, 4, (16,), 4), [1], [0], tabs, K.KVL_GATHER | K.KVL_HOST_ONLY, block_threads=96)
+    assert e.value.code == K.KVL_EINVAL
+    with pytest.raises(K.KvlError) as e:                                               # 2^32 pool rows
+        K.kvl_plan(K.make_layout(1, 64, (16,), 1 << 26), [1], [0], tabs, K.KVL_GATHER | K.KVL_HOST_ONLY)
+    assert e.value.code == K.KVL_ERANGE
+    # a host-only plan cannot be executed (checked before any pointer is used)
+    p = K.kvl_plan(K.make_layout(1, 4, (16,), 4), [1], [0], tabs, K.KVL_GATHER | K.KVL_HOST_ONLY)
+    from paper_2602_21548_amd import binding as B
+    import ctypes as C
+    arr = (C.c_void_p * 1)(0x1000)
+    assert B._lib.kvl_pack_layer(p.handle, arr, 0x1000, 1 << 20, None) == K.KVL_EINVAL
+    assert B._lib.kvl_unpack_layer(p.handle, 0x1000, 1 << 20, arr, None) == K.KVL_EINVAL
+
+
+def test_empty_batch_plan():
+    lay = K.make_layout(1, 16, (32,), 8)
+    p = K.kvl_plan(lay, [], [], [], K.KVL_GATHER | K.KVL_HOST_ONLY)
+    assert p.payload_bytes == 0 and p.n_units == 0 and p.chunks(1024) == []
+
+
+def test_h2d_chunks_cover_the_payload():
+    w = W.config(2, n_requests=5, token_scale=1 / 128)
+    p = host_plan(w, "dst", K.KVL_SCATTER, unit_bytes=16384)
+    T, rows = p.hit_tokens, w.layout.row_bytes
+    for cb in (16384, 100000, 1 << 20, 1 << 30):
+        ch = p.chunks(cb)
+        pos, base = 0, 0
+        for plane, row in enumerate(rows):
+            mine = [c for c in ch if c["plane"] == plane]
+            assert mine[0]["unit_begin"] == 0 and mine[-1]["unit_end"] == p.n_units
+            for a, b in zip(mine, mine[1:]):
+                assert a["unit_end"] == b["unit_begin"]
+            for c in mine:
+                assert 0 < c["bytes"] <= cb and c["host_offset"] == pos
+                pos += c["bytes"]
+            base += T * row
+            assert pos == base
+        assert pos == p.payload_bytes
+    with pytest.raises(K.KvlError) as e:
+        p.chunks(1024)                      # smaller than one descriptor
+    assert e.value.code == K.KVL_ESPACE
