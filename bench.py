@@ -1,0 +1,315 @@
+#!/usr/bin/env python3
+"""Benchmark of the layer-wise KV-cache load path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+
+A step is one batch through the whole device-resident path: kvl_plan for the
+decode side and the prefill side, then for every layer kvl_pack_layer (paged
+pool -> transfer buffer) and kvl_unpack_layer (transfer buffer -> second paged
+pool).  `value` is the rate at which cache bytes arrive in the prefill pool,
+layers x payload / step time, with every input resident in HBM.  The two
+entry points that take a pinned host buffer (kvl_h2d_unpack_layer,
+kvl_stream_layers) are timed after the steps and reported beside it, against
+the host-link rate measured in the same run; they never enter `value`.
+
+Prints one JSON line.  The CPU oracle is timed on a bounded sample of the same
+workload as a baseline (`cpu_baseline`), not as a target.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "KV-cache load GB/s per layer (pack, unpack, H2D+unpack) and % of HBM/link peak"
+HBM_PEAK_GBPS = 8000.0
+WORKLOADS = {
+    1: "cfg1 tiny MLA: 2 layers, 4 req x 1000 hit tokens, bs 16, 1152 B rows",
+    2: "cfg2 GQA: 32 layers, K and V planes of 2048 B rows, bs 64, 64 req, hit U[16K,64K], append U[256,1024], pool 1.1x, random tables",
+    3: "cfg3 MLA: 61 layers, 1152 B rows, bs 64, 128 req, hit lognormal(median 32K, cap 128K), 95% hit, random tables",
+    4: "cfg4 fp8 MLA: 61 layers, 656 B opaque rows, bs 64, 256 req, hit U[8K,128K], fully fragmented tables",
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def kernel_source_hash() -> str:
+    h = hashlib.sha256()
+    for f in ("kvl_kernels.hip", "kvl_internal.h"):
+        h.update(open(os.path.join(ROOT, "paper_2602_21548_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload_index: int, kernel: str):
+    """HBM bytes per launch from the committed counter runs, or None when the
+    kernel source has changed since they were taken."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        rec = json.load(open(path))
+    except (OSError, ValueError):
+        return None
+    if rec.get("kernel_source_hash") != kernel_source_hash():
+        return None
+    return rec.get(f"cfg{workload_index}", {}).get(kernel)
+
+
+def cpu_baseline(index: int, sample_requests: int) -> dict:
+    """The oracle, as it stands, on a sample of the workload: one layer of the
+    first `sample_requests` requests, pack then unpack, on the host cores."""
+    import kvl_workloads as W
+    import oracle
+    w = W.config(index, n_requests=sample_requests)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    src = W.fill_pool_fast(w, 0, "src")
+    dst = W.sentinel_pool(w, "dst")
+    n = oracle.payload_bytes(w.hit, rows)
+    x = np.empty(n, dtype=np.uint8)
+    cores = len(os.sched_getaffinity(0))
+    out = {}
+    for label, threads in (("single", 1), ("sharded", max(1, min(cores, sample_requests)))):
+        t0 = time.perf_counter()
+        oracle.pack(bs, rows, w.hit, w.src.tables, src, xfer=x, threads=threads)
+        oracle.unpack(bs, rows, w.hit, w.dst.tables, x, dst, threads=threads)
+        dt = time.perf_counter() - t0
+        out[label] = (n / dt / 1e9, threads, dt)
+    v, c, dt = out["sharded"]
+    return {"value": round(v, 3), "unit": "GB/s", "cores": c, "kind": "oracle",
+            "sample": f"1 layer of the first {sample_requests} requests of cfg{index} "
+                      f"({n / 1e9:.2f} GB payload), pack+unpack, {dt:.1f} s",
+            "single_thread_value": round(out["single"][0], 3),
+            "single_thread_seconds": round(out["single"][2], 2),
+            "host_cores_available": cores}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOADS))
+    ap.add_argument("--skip-host-link", action="store_true", help="leave out the pinned-host legs")
+    ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU-oracle baseline")
+    ap.add_argument("--stream-layers", type=int, default=0, help="layers of the streamed leg (0: all 61)")
+    ap.add_argument("--cpu-sample-requests", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 "
+              "(the load path shards by request across GPUs without any collective)", file=sys.stderr)
+        return 2
+
+    import torch
+    import kvl_workloads as W
+    import paper_2602_21548_amd as K
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    w = W.config(args.config)
+    L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
+    P = len(rows)
+    lay_src = K.make_layout(L, bs, rows, w.src.pool_blocks)
+    lay_dst = K.make_layout(L, bs, rows, w.dst.pool_blocks)
+
+    # resident-layer windows: layer l lives in slot l % 2 on both sides (layer-wise
+    # prefill keeps only a few layers' cache in HBM at a time)
+    WIN = min(2, L)
+    log(f"[bench] {WORKLOADS[args.config]}")
+    t0 = time.perf_counter()
+    src = []
+    for s in range(WIN):
+        src.append([torch.from_numpy(p).to(dev) for p in W.fill_pool_fast(w, s, "src")])
+    dst = [[torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device=dev) for r in rows]
+           for _ in range(WIN)]
+    probe = K.kvl_plan(lay_src, w.hit, w.app, w.src.tables, K.KVL_GATHER | K.KVL_HOST_ONLY)
+    payload, T, n_units = probe.payload_bytes, probe.hit_tokens, probe.n_units
+    probe.destroy()
+    xfer = torch.empty(payload, dtype=torch.uint8, device=dev)
+    log(f"[bench] inputs resident after {time.perf_counter() - t0:.1f} s: payload/layer {payload / 1e9:.3f} GB, "
+        f"{T} hit tokens, {n_units} descriptors")
+
+    stream = torch.cuda.Stream()
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+
+    def step(record=None):
+        g = K.kvl_plan(lay_src, w.hit, w.app, w.src.tables, K.KVL_GATHER)
+        s = K.kvl_plan(lay_dst, w.hit, w.app, w.dst.tables, K.KVL_SCATTER)
+        for l in range(L):
+            if record is not None:
+                e0, e1, e2 = ev(), ev(), ev()
+                e0.record(stream)
+            K.kvl_pack_layer(g, src[l % WIN], xfer, stream=stream)
+            if record is not None:
+                e1.record(stream)
+            K.kvl_unpack_layer(s, xfer, dst[l % WIN], stream=stream)
+            if record is not None:
+                e2.record(stream)
+                record.append((e0, e1, e2))
+        stream.synchronize()
+        g.destroy()
+        s.destroy()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    per_kernel = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(per_kernel)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    pack_ms = np.array([a.elapsed_time(b) for a, b, _ in per_kernel])
+    unpack_ms = np.array([b.elapsed_time(c) for _, b, c in per_kernel])
+    value = L * payload / (ms_per_step * 1e-3) / 1e9
+
+    # plan cost on its own (host work + descriptor upload), outside the timed steps
+    t0 = time.perf_counter()
+    for _ in range(5):
+        K.kvl_plan(lay_src, w.hit, w.app, w.src.tables, K.KVL_GATHER).destroy()
+    plan_ms = (time.perf_counter() - t0) * 1e3 / 5
+
+    # every row's placement, checked against the oracle through 8-byte row tags
+    verified = verify_tags(w, src, dst, xfer, T, WIN, L)
+
+    def roof(name, ms):
+        avg = float(ms.mean())
+        achieved = 2.0 * payload / (avg * 1e-3) / 1e9          # algorithmic bytes: row read + row written
+        return {"kernel": name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": measured_traffic(args.config, name),
+                "algorithmic_bytes_per_launch": 2 * payload, "avg_launch_ms": round(avg, 4),
+                "min_launch_ms": round(float(ms.min()), 4), "launches": int(ms.size)}
+
+    roof_pack = roof("kvl_pack_tile_kernel", pack_ms)
+    roof_unpack = roof("kvl_unpack_tile_kernel", unpack_ms)
+    dominant, other = (roof_pack, roof_unpack) if pack_ms.sum() >= unpack_ms.sum() else (roof_unpack, roof_pack)
+
+    out = {
+        "metric": METRIC, "value": round(value, 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8",
+        "data": "synthetic",
+        "config": {"workload": WORKLOADS[args.config], "layers": L, "requests": w.n_requests,
+                   "hit_tokens": T, "payload_bytes_per_layer": payload, "descriptors": n_units,
+                   "step": f"kvl_plan x2 + {L} x (kvl_pack_layer + kvl_unpack_layer), inputs resident in HBM",
+                   "resident_layer_window": WIN},
+        "roofline": dominant, "roofline_other": other,
+        "pack_payload_gbps": round(payload / (pack_ms.mean() * 1e-3) / 1e9, 1),
+        "unpack_payload_gbps": round(payload / (unpack_ms.mean() * 1e-3) / 1e9, 1),
+        "tokens_layers_per_s": round(T * L / (ms_per_step * 1e-3), 1),
+        "plan_ms": round(plan_ms, 3), "verified_rows_vs_oracle": verified,
+    }
+    del src, dst, xfer
+    torch.cuda.empty_cache()
+
+    if not args.skip_host_link:
+        out["host_link"] = host_link_legs(args)
+    if not args.skip_cpu:
+        log("[bench] timing the CPU oracle on a sample ...")
+        out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_sample_requests)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def verify_tags(w, src, dst, xfer, T, WIN, L) -> int:
+    """The fast fill writes (layer, plane, physical row) into the first 8 bytes of
+    every pool row.  Packing and unpacking those tags with the CPU oracle says where
+    every row must have gone; compare with what the GPU path left behind."""
+    import torch
+    import oracle
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    last = L - 1
+    slot = last % WIN                      # the transfer buffer and this slot hold the last layer
+    tag_rows = tuple(8 for _ in rows)
+    tag_src = [p.view(-1, r)[:, :8].contiguous().cpu().numpy().reshape(-1) for p, r in zip(src[slot], rows)]
+    want_x = oracle.pack(bs, tag_rows, w.hit, w.src.tables, tag_src, threads=8)
+    want_dst = [np.full(w.dst.pool_blocks * bs * 8, 0xA5, dtype=np.uint8) for _ in rows]
+    oracle.unpack(bs, tag_rows, w.hit, w.dst.tables, want_x, want_dst, threads=8)
+    checked = 0
+    off = 0
+    for p, r in enumerate(rows):
+        got = xfer[off:off + T * r].view(T, r)[:, :8].contiguous().cpu().numpy().reshape(-1)
+        if got.tobytes() != want_x[p * T * 8:(p + 1) * T * 8].tobytes():
+            raise SystemExit(f"bench: transfer buffer plane {p} differs from the oracle")
+        gd = dst[slot][p].view(-1, r)[:, :8].contiguous().cpu().numpy().reshape(-1)
+        if gd.tobytes() != want_dst[p].tobytes():
+            raise SystemExit(f"bench: destination pool plane {p} differs from the oracle")
+        off += T * r
+        checked += T + w.dst.pool_blocks * bs
+    return checked
+
+
+def host_link_legs(args) -> dict:
+    """kvl_h2d_unpack_layer on one layer and kvl_stream_layers over all layers of
+    the streamed MLA workload, against the host-link rate measured here."""
+    import torch
+    import kvl_workloads as W
+    import paper_2602_21548_amd as K
+    dev = torch.device("cuda:0")
+    w = W.config(5)
+    L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
+    if args.stream_layers:
+        L = min(L, args.stream_layers)
+    lay = K.make_layout(w.layout.n_layers, bs, rows, w.dst.pool_blocks)
+    plan = K.kvl_plan(lay, w.hit, w.app, w.dst.tables, K.KVL_SCATTER)
+    payload = plan.payload_bytes
+    H, S = w.notes["host_slots"], w.notes["dev_slots"]
+    log(f"[bench] host-link legs: pinning {H} x {payload / 1e9:.2f} GB ...")
+    host = [torch.empty(payload, dtype=torch.uint8, pin_memory=True) for _ in range(H)]
+    rng = np.random.Generator(np.random.PCG64(W.BASE_SEED + 205))
+    tile = rng.integers(0, 256, size=1 << 24, dtype=np.uint8)
+    for h in host:
+        a = h.numpy()
+        for pos in range(0, payload, tile.size):
+            k = min(tile.size, payload - pos)
+            a[pos:pos + k] = tile[:k]
+    slots = [[torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device=dev) for r in rows]
+             for _ in range(S)]
+    chunk = 32 << 20
+    staging = torch.empty(4 * chunk, dtype=torch.uint8, device=dev)
+    cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    peak_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    peak = K.kvl_measure_h2d_peak(host[0][:1 << 30], peak_buf, reps=5, stream=cs)
+    del peak_buf
+
+    # one layer through the host-buffer path
+    times = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        K.kvl_h2d_unpack_layer(plan, host[0], staging, chunk, slots[0], cs, ks)
+        ks.synchronize()
+        cs.synchronize()
+        times.append(time.perf_counter() - t0)
+    h2d_gbps = payload / min(times) / 1e9
+
+    st = K.kvl_stream_layers(plan, host, slots, staging, chunk, w.notes["compute_us"], cs, ks, ms, n_layers=L)
+    plan.destroy()
+    return {
+        "workload": "cfg5 streamed MLA: 61 layers x 1152 B rows, 128 req, pinned host buffer -> paged HBM, "
+                    "200 us synthetic compute per layer",
+        "h2d_peak_gbps": round(peak, 2), "chunk_bytes": chunk, "staging_slots": 4,
+        "h2d_unpack_layer_gbps": round(h2d_gbps, 2), "h2d_unpack_frac_of_link": round(h2d_gbps / peak, 4),
+        "stream_layers": L, "stream_total_ms": round(st["total_ms"], 2),
+        "stream_gbps": round(st["link_gbps"], 2), "stream_frac_of_link": round(st["link_gbps"] / peak, 4),
+        "stream_exposed_ms": round(st["exposed_ms"], 2),
+        "payload_bytes_per_layer": payload,
+    }
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -39,10 +39,11 @@ void set_hip_error(hipError_t e);
         }                                               \
     } while (0)
 
-constexpr uint32_t kDefaultUnitBytes = 64u << 10;
+constexpr uint32_t kDefaultUnitBytes = 128u << 10;
 constexpr uint32_t kDefaultBlockThreads = 256;
-constexpr uint32_t kDefaultVariant = 0;
-constexpr uint32_t kNumVariants = 16;
+constexpr uint32_t kNumVariants = 32;        // explicit variants are 1 .. kNumVariants
+constexpr uint32_t kDefaultPackCode = 2u | 8u;        // tile x1, nt stores
+constexpr uint32_t kDefaultUnpackCode = 2u | 8u;      // tile x1, nt stores
 
 bool valid_block_threads(uint32_t t);
 

@@ -60,7 +60,7 @@ static int resolve_tuning(const kvl_tuning_t *in, kvl_tuning_t *out) {
     if (t.unit_bytes == 0) t.unit_bytes = kDefaultUnitBytes;
     if (t.block_threads == 0) t.block_threads = kDefaultBlockThreads;
     if (!valid_block_threads(t.block_threads)) return KVL_EINVAL;
-    if (t.variant >= kNumVariants) return KVL_EINVAL;
+    if (t.variant > kNumVariants) return KVL_EINVAL;
     if (t.unit_bytes > (1u << 30)) t.unit_bytes = 1u << 30;
     t.reserved = 0;
     *out = t;
@@ -218,7 +218,7 @@ int kvl_plan_set_tuning(kvl_plan_t *plan, const kvl_tuning_t *tuning) {
         if (!kvl::valid_block_threads(tuning->block_threads)) return KVL_EINVAL;
         t.block_threads = tuning->block_threads;
     }
-    if (tuning->variant >= kvl::kNumVariants) return KVL_EINVAL;
+    if (tuning->variant > kvl::kNumVariants) return KVL_EINVAL;
     t.variant = tuning->variant;
     plan->tuning = t;
     return KVL_OK;

@@ -64,7 +64,7 @@ def test_pack_unpack_default(name, make):
     run_hop(make())
 
 
-@pytest.mark.parametrize("variant", range(16))
+@pytest.mark.parametrize("variant", range(33))
 @pytest.mark.parametrize("threads", [64, 256, 1024])
 def test_every_variant(variant, threads):
     # units of 5 KiB against 64..1024 threads x 4..8 vectors: full steps, ragged tails and idle lanes
@@ -76,7 +76,9 @@ def test_every_variant(variant, threads):
 def test_unit_sizes(unit_bytes):
     w = W.tiny(207, 10, 64, (1152,), 400, 1500, kind="runs")
     run_hop(w, unit_bytes=unit_bytes)
-    run_hop(w, unit_bytes=unit_bytes, variant=1)
+    run_hop(w, unit_bytes=unit_bytes, variant=2)
+    run_hop(w, unit_bytes=unit_bytes, variant=3, block_threads=64)
+    run_hop(w, unit_bytes=unit_bytes, variant=4)
 
 
 def test_layers_are_independent_pools():

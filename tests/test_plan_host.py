@@ -82,7 +82,7 @@ def test_descriptors_tile_the_transfer_buffer():
         assert u[0, 1] == 0
         assert np.array_equal(u[1:, 1], u[:-1, 1] + u[:-1, 2])       # dense, in order
         assert u[-1, 1] + u[-1, 2] == p.hit_tokens
-        max_rows = max(1, (ub or (64 << 10)) // 64)
+        max_rows = max(1, (ub or (128 << 10)) // 64)
         assert u[:, 2].max() <= max_rows
         assert np.all(u[:, 0] + u[:, 2] <= w.src.pool_blocks * 16)
 
