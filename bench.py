@@ -69,7 +69,8 @@ def cpu_baseline(index: int, sample_requests: int) -> dict:
     first `sample_requests` requests, pack then unpack, on the host cores."""
     import kvl_workloads as W
     import oracle
-    w = W.config(index, n_requests=sample_requests)
+    w = W.config(index, n_requests=sample_requests or None)
+    sample_requests = w.n_requests
     bs, rows = w.layout.block_tokens, w.layout.row_bytes
     src = W.fill_pool_fast(w, 0, "src")
     dst = W.sentinel_pool(w, "dst")
@@ -101,7 +102,9 @@ def main() -> int:
     ap.add_argument("--skip-host-link", action="store_true", help="leave out the pinned-host legs")
     ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU-oracle baseline")
     ap.add_argument("--stream-layers", type=int, default=0, help="layers of the streamed leg (0: all 61)")
-    ap.add_argument("--cpu-sample-requests", type=int, default=8)
+    ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests in the CPU sample (0: the whole batch)")
+    ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
+                    help="also launch one plain copy kernel of this size (a known-traffic reference for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 "
@@ -162,6 +165,14 @@ def main() -> int:
         g.destroy()
         s.destroy()
 
+    if args.calibration_copy_gib > 0:
+        nb = int(args.calibration_copy_gib * (1 << 30)) // 16 * 16
+        ca = torch.full((nb,), 1, dtype=torch.uint8, device=dev)
+        cb = torch.empty_like(ca)
+        K.kvl_copy_linear(ca, cb, stream=stream)
+        stream.synchronize()
+        log(f"[bench] calibration copy: kvl_linear_kernel moved {nb} bytes (reads {nb}, writes {nb})")
+        del ca, cb
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -279,7 +290,7 @@ def host_link_legs(args) -> dict:
             a[pos:pos + k] = tile[:k]
     slots = [[torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device=dev) for r in rows]
              for _ in range(S)]
-    chunk = 32 << 20
+    chunk = 128 << 20
     staging = torch.empty(4 * chunk, dtype=torch.uint8, device=dev)
     cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     peak_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)

@@ -1,0 +1,145 @@
+"""Full-size parity: the configurations of the benchmark, in the launch
+configuration the benchmark times (default tuning), against the CPU oracle.
+
+Configs 2-4: one layer each, every byte of the transfer buffer and of the
+destination pool compared with the oracle's.  Config 5: all 61 layers streamed
+from pinned host memory; the oracle computes the first 16 bytes of every token
+row of every layer (a 16-byte-row instance of the same definition), which names
+the layer and the row and so pins both placement and layer ordering; the device
+path is compared on probes taken by each layer's compute kernel and on all rows
+of the slots left at the end.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import kvl_workloads as W
+import oracle
+import paper_2602_21548_amd as K
+from gpu_util import dev_plan, same_bytes, to_host
+
+pytestmark = pytest.mark.gpu
+
+THREADS = 16
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4])
+def test_full_size_layer(idx):
+    t0 = time.perf_counter()
+    w = W.config(idx)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    layer = idx                                   # any layer: each has its own pool contents
+    src = W.fill_pool_fast(w, layer, "src")
+    want_x = oracle.pack(bs, rows, w.hit, w.src.tables, src, threads=THREADS)
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    n = g.payload_bytes
+    assert n == want_x.size
+    d_src = [torch.from_numpy(p).cuda() for p in src]
+    guard = 1 << 16
+    d_x = torch.full((n + guard,), 0x3C, dtype=torch.uint8, device="cuda")
+    K.kvl_pack_layer(g, d_src, d_x)
+    d_dst = [torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device="cuda") for r in rows]
+    K.kvl_unpack_layer(s, d_x, d_dst)
+    torch.cuda.synchronize()
+    print(f"[cfg{idx}] inputs + oracle pack + gpu: {time.perf_counter() - t0:.1f} s", flush=True)
+    got = to_host(d_x)
+    assert np.array_equal(got[:n], want_x), "pack differs from the oracle"
+    assert np.all(got[n:] == 0x3C), "pack wrote past the payload"
+    del got, d_x, d_src
+    for p, r in enumerate(rows):
+        # the oracle, one plane at a time (planes are independent problems laid out back to back)
+        T = g.hit_tokens
+        base = sum(T * q for q in rows[:p])
+        want = np.full(w.dst.pool_blocks * bs * r, 0xA5, dtype=np.uint8)
+        oracle.unpack(bs, (r,), w.hit, w.dst.tables, want_x[base:base + T * r], [want], threads=THREADS)
+        assert np.array_equal(to_host(d_dst[p]), want), f"unpack differs from the oracle in plane {p}"
+        del want
+    print(f"[cfg{idx}] done after {time.perf_counter() - t0:.1f} s", flush=True)
+    g.destroy()
+    s.destroy()
+
+
+def test_full_size_streamed_layers():
+    t0 = time.perf_counter()
+    w = W.config(5)
+    L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
+    row = rows[0]
+    H, S = w.notes["host_slots"], w.notes["dev_slots"]
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    n, T = s.payload_bytes, s.hit_tokens
+    pool_rows = w.dst.pool_blocks * bs
+
+    # host buffers: a random tile repeated; the first 16 bytes of row g of layer l are (l, g)
+    rng = np.random.Generator(np.random.PCG64(W.BASE_SEED + 205))
+    tile = rng.integers(0, 256, size=1 << 24, dtype=np.uint8)
+    host = [torch.empty(n, dtype=torch.uint8, pin_memory=True) for _ in range(H)]
+    for h in host:
+        a = h.numpy()
+        for pos in range(0, n, tile.size):
+            k = min(tile.size, n - pos)
+            a[pos:pos + k] = tile[:k]
+    g_idx = np.arange(T, dtype=np.uint64)
+
+    def tags_of(layer):
+        t = np.empty((T, 2), dtype=np.uint64)
+        t[:, 0] = layer
+        t[:, 1] = g_idx
+        return t
+
+    def fill(layer, slot):
+        host[slot].numpy().reshape(T, row)[:, :16] = tags_of(layer).view(np.uint8).reshape(T, 16)
+
+    # oracle on 16-byte rows: what the head of every pool row must be when layer l is computed
+    o_slots = [[np.full(pool_rows * 16, 0xA5, dtype=np.uint8)] for _ in range(S)]
+    o_host = [np.zeros(T * 16, dtype=np.uint8) for _ in range(H)]
+    rs = np.random.Generator(np.random.PCG64(W.BASE_SEED + 305))
+    probe_rows = np.sort(rs.choice(pool_rows, size=512, replace=False))
+    probes = [(0, int(r) * row) for r in probe_rows]
+    want_probe = np.zeros((L, len(probes), 16), dtype=np.uint8)
+    gen = oracle.stream_layers(bs, (16,), w.hit, w.dst.tables, o_host, L, o_slots)
+    want_final = {}
+    for l in range(L):
+        o_host[l % H][:] = tags_of(l).view(np.uint8).reshape(-1)
+        _, sl, planes = next(gen)
+        want_probe[l] = planes[0].reshape(pool_rows, 16)[probe_rows]
+        if l >= L - S:
+            want_final[sl] = planes[0].copy()
+    print(f"[cfg5] oracle done after {time.perf_counter() - t0:.1f} s", flush=True)
+
+    slots = [[torch.full((pool_rows * row,), 0xA5, dtype=torch.uint8, device="cuda")] for _ in range(S)]
+    chunk = 128 << 20
+    staging = torch.empty(4 * chunk, dtype=torch.uint8, device="cuda")
+    probe_out = torch.zeros(L * len(probes) * 16, dtype=torch.uint8, device="cuda")
+    cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    st = K.kvl_stream_layers(s, host, slots, staging, chunk, w.notes["compute_us"], cs, ks, ms,
+                             probes=probes, probe_out=probe_out, host_fill=fill, per_layer_times=True)
+    print(f"[cfg5] streamed {L} layers in {st['total_ms']:.0f} ms ({st['link_gbps']:.1f} GB/s) "
+          f"after {time.perf_counter() - t0:.1f} s", flush=True)
+    got = to_host(probe_out).reshape(L, len(probes), 16)
+    for l in range(L):
+        assert got[l].tobytes() == want_probe[l].tobytes(), f"compute of layer {l} saw the wrong cache"
+    for sl, want in want_final.items():
+        head = slots[sl][0].view(pool_rows, row)[:, :16].contiguous()
+        assert same_bytes(to_host(head).reshape(-1), want), f"slot {sl} differs from the oracle at the end"
+    # beyond the 16-byte heads: the rest of every hit row is the host buffer's bytes, and rows
+    # without a hit token still hold the sentinel -- checked on a sample of whole rows
+    last_slot = (L - 1) % S
+    pool = slots[last_slot][0].view(pool_rows, row)
+    hb = host[(L - 1) % H].numpy().reshape(T, row)
+    heads = want_final[last_slot].reshape(pool_rows, 16)
+    for r in probe_rows[:128]:
+        got_row = to_host(pool[int(r)])
+        if np.all(heads[r] == 0xA5):
+            assert np.all(got_row == 0xA5)
+        else:
+            gi = int(heads[r].view(np.uint64)[1])
+            assert got_row.tobytes() == hb[gi].tobytes()
+    tl, tb, te = st["t_loaded"], st["t_compute_begin"], st["t_compute_end"]
+    assert np.all(tb >= tl - 1e-3) and np.all(te - tb >= 0.18) and np.all(np.diff(tb) > 0)
+    # load of layer l + S does not finish before compute of layer l has ended
+    assert np.all(tl[S:] >= te[:-S] - 1e-3)
+    s.destroy()
