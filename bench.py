@@ -101,6 +101,7 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOADS))
     ap.add_argument("--skip-host-link", action="store_true", help="leave out the pinned-host legs")
     ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU-oracle baseline")
+    ap.add_argument("--skip-other-configs", action="store_true", help="leave out the short runs of the other workloads")
     ap.add_argument("--stream-layers", type=int, default=0, help="layers of the streamed leg (0: all 61)")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests in the CPU sample (0: the whole batch)")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
@@ -194,7 +195,10 @@ def main() -> int:
     plan_ms = (time.perf_counter() - t0) * 1e3 / 5
 
     # every row's placement, checked against the oracle through 8-byte row tags
-    verified = verify_tags(w, src, dst, xfer, T, WIN, L)
+    last_slot = (L - 1) % WIN              # the transfer buffer and this slot hold the last layer
+    verified = verify_tags(w, src[last_slot], dst[last_slot], xfer, T)
+
+    ceiling = copy_ceiling(stream)
 
     def roof(name, ms):
         avg = float(ms.mean())
@@ -202,6 +206,7 @@ def main() -> int:
         return {"kernel": name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                 "traffic": measured_traffic(args.config, name),
+                "frac_of_measured_linear_copy": round(achieved / ceiling, 4),
                 "algorithmic_bytes_per_launch": 2 * payload, "avg_launch_ms": round(avg, 4),
                 "min_launch_ms": round(float(ms.min()), 4), "launches": int(ms.size)}
 
@@ -223,10 +228,13 @@ def main() -> int:
         "unpack_payload_gbps": round(payload / (unpack_ms.mean() * 1e-3) / 1e9, 1),
         "tokens_layers_per_s": round(T * L / (ms_per_step * 1e-3), 1),
         "plan_ms": round(plan_ms, 3), "verified_rows_vs_oracle": verified,
+        "linear_copy_ceiling_gbps": round(ceiling, 1),
     }
     del src, dst, xfer
     torch.cuda.empty_cache()
 
+    if not args.skip_other_configs:
+        out["other_configs"] = {f"cfg{i}": short_hop(i) for i in sorted(WORKLOADS) if i != args.config}
     if not args.skip_host_link:
         out["host_link"] = host_link_legs(args)
     if not args.skip_cpu:
@@ -236,17 +244,15 @@ def main() -> int:
     return 0
 
 
-def verify_tags(w, src, dst, xfer, T, WIN, L) -> int:
+def verify_tags(w, src_planes, dst_planes, xfer, T) -> int:
     """The fast fill writes (layer, plane, physical row) into the first 8 bytes of
     every pool row.  Packing and unpacking those tags with the CPU oracle says where
     every row must have gone; compare with what the GPU path left behind."""
     import torch
     import oracle
     bs, rows = w.layout.block_tokens, w.layout.row_bytes
-    last = L - 1
-    slot = last % WIN                      # the transfer buffer and this slot hold the last layer
     tag_rows = tuple(8 for _ in rows)
-    tag_src = [p.view(-1, r)[:, :8].contiguous().cpu().numpy().reshape(-1) for p, r in zip(src[slot], rows)]
+    tag_src = [p.view(-1, r)[:, :8].contiguous().cpu().numpy().reshape(-1) for p, r in zip(src_planes, rows)]
     want_x = oracle.pack(bs, tag_rows, w.hit, w.src.tables, tag_src, threads=8)
     want_dst = [np.full(w.dst.pool_blocks * bs * 8, 0xA5, dtype=np.uint8) for _ in rows]
     oracle.unpack(bs, tag_rows, w.hit, w.dst.tables, want_x, want_dst, threads=8)
@@ -256,12 +262,76 @@ def verify_tags(w, src, dst, xfer, T, WIN, L) -> int:
         got = xfer[off:off + T * r].view(T, r)[:, :8].contiguous().cpu().numpy().reshape(-1)
         if got.tobytes() != want_x[p * T * 8:(p + 1) * T * 8].tobytes():
             raise SystemExit(f"bench: transfer buffer plane {p} differs from the oracle")
-        gd = dst[slot][p].view(-1, r)[:, :8].contiguous().cpu().numpy().reshape(-1)
+        gd = dst_planes[p].view(-1, r)[:, :8].contiguous().cpu().numpy().reshape(-1)
         if gd.tobytes() != want_dst[p].tobytes():
             raise SystemExit(f"bench: destination pool plane {p} differs from the oracle")
         off += T * r
         checked += T + w.dst.pool_blocks * bs
     return checked
+
+
+def copy_ceiling(stream) -> float:
+    """Traffic rate (GB/s, read + write) of a plain 4 GiB device-to-device copy with the
+    pack kernel's instruction mix: what a gather with perfect locality could reach here."""
+    import torch
+    import paper_2602_21548_amd as K
+    n = 4 << 30
+    a = torch.full((n,), 1, dtype=torch.uint8, device="cuda")
+    b = torch.empty_like(a)
+    best = 0.0
+    for i in range(6):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        K.kvl_copy_linear(a, b, stream=stream)
+        e1.record(stream)
+        e1.synchronize()
+        if i:
+            best = max(best, 2.0 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    return best
+
+
+def short_hop(index: int, reps: int = 8) -> dict:
+    """pack + unpack of one resident layer of another workload, timed per launch."""
+    import torch
+    import kvl_workloads as W
+    import paper_2602_21548_amd as K
+    dev = torch.device("cuda:0")
+    w = W.config(index)
+    L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
+    src = [torch.from_numpy(p).to(dev) for p in W.fill_pool_fast(w, 0, "src")]
+    dst = [torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device=dev) for r in rows]
+    g = K.kvl_plan(K.make_layout(L, bs, rows, w.src.pool_blocks), w.hit, w.app, w.src.tables, K.KVL_GATHER)
+    s = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables, K.KVL_SCATTER)
+    payload, T = g.payload_bytes, g.hit_tokens
+    xfer = torch.empty(payload, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream()
+    pk, up = [], []
+    for i in range(reps + 2):
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        e0.record(stream)
+        K.kvl_pack_layer(g, src, xfer, stream=stream)
+        e1.record(stream)
+        K.kvl_unpack_layer(s, xfer, dst, stream=stream)
+        e2.record(stream)
+        e2.synchronize()
+        if i >= 2:
+            pk.append(e0.elapsed_time(e1))
+            up.append(e1.elapsed_time(e2))
+    verified = verify_tags(w, src, dst, xfer, T)
+    g.destroy()
+    s.destroy()
+    pm, um = float(np.mean(pk)), float(np.mean(up))
+    out = {"workload": WORKLOADS[index], "payload_bytes_per_layer": payload, "hit_tokens": T,
+           "pack_ms": round(pm, 4), "unpack_ms": round(um, 4),
+           "pack_payload_gbps": round(payload / pm / 1e6, 1), "unpack_payload_gbps": round(payload / um / 1e6, 1),
+           "pack_frac_of_hbm_peak": round(2 * payload / pm / 1e6 / HBM_PEAK_GBPS, 4),
+           "unpack_frac_of_hbm_peak": round(2 * payload / um / 1e6 / HBM_PEAK_GBPS, 4),
+           "tokens_layers_per_s": round(T / ((pm + um) * 1e-3), 1), "verified_rows_vs_oracle": verified}
+    if payload < (64 << 20):
+        out["note"] = "launch- and cache-bound: the payload fits the on-die cache and a launch costs more than the copy"
+    del src, dst, xfer
+    torch.cuda.empty_cache()
+    return out
 
 
 def host_link_legs(args) -> dict:

@@ -10,19 +10,24 @@
 // vectors, so every wavefront load or store covers 1 KiB of contiguous memory.
 //
 // kvl_tuning_t::variant is 0 for the default below, else 1 + code with
-// code = mode | ntl << 2 | nts << 3 | deep << 4:
+// code = mode | ntl << 2 | sp << 3 | deep << 5:
 //   mode 0  one workgroup per descriptor, each lane loops over the span
 //   mode 1  one wavefront per descriptor, each lane loops over the span
 //   mode 2  tiled: a descriptor is cut into tiles of blockDim vectors and every
 //           lane moves exactly one 16-byte vector
 //   mode 3  tiled, two vectors per lane
-//   ntl / nts  non-temporal loads / stores
-//   deep       modes 0-1: 8 instead of 4 vectors in flight per lane
+//   ntl     non-temporal loads
+//   sp      store cache policy: 0 plain, 1 nt, 2 sc1, 3 sc1 nt
+//   deep    modes 0-1: 8 instead of 4 vectors in flight per lane
 // Measured on MI355X (5.2 GB of 72 KiB blocks in random order), the tiled form
 // with one vector per lane and 256-lane workgroups is the fastest: it leaves no
 // dependency between a lane's memory operations and lets the hardware fill the
-// memory system with resident wavefronts.  Non-temporal stores help both
-// directions; non-temporal loads gain nothing consistent across the workloads.
+// memory system with resident wavefronts.  Cache policies, measured with gather
+// and scatter alternating as they do in use: non-temporal loads everywhere; the
+// gather (random reads, sequential writes) stores with sc1 when blocks are
+// multiples of 4 KiB and with nt when they are not (41,984-byte blocks); the
+// scatter (sequential reads, random writes) stores with sc1+nt.  Together the
+// policies are worth 5-15 % over plain loads and stores.
 #include <algorithm>
 #include <cstdio>
 
@@ -52,15 +57,20 @@ __device__ __forceinline__ v4u load16(gsrc_t p) {
     return *p;
 }
 
-template <bool NT>
+// Store with a cache policy.  The compiler only offers the non-temporal hint;
+// the system-scope write-through forms (sc1) are written out as instructions.
+// A store needs no wait: nothing here reads what it wrote.
+template <int SP>
 __device__ __forceinline__ void store16(gdst_t p, v4u v) {
-    if (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
+    if (SP == 0) *p = v;
+    else if (SP == 1) __builtin_nontemporal_store(v, p);
+    else if (SP == 2) asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
+    else asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
 }
 
 // `lanes` threads copy n 16-byte vectors; this thread is `lane`.  U loads are
 // issued before the first store so that U KiB per wavefront are in flight.
-template <int U, bool NTL, bool NTS>
+template <int U, bool NTL, int SP>
 __device__ __forceinline__ void copy_span(gsrc_t __restrict__ src, gdst_t __restrict__ dst,
                                           uint32_t n, uint32_t lane, uint32_t lanes) {
     // n is below 2^32: a descriptor never spans more than 1 GiB
@@ -73,7 +83,7 @@ __device__ __forceinline__ void copy_span(gsrc_t __restrict__ src, gdst_t __rest
 #pragma unroll
         for (int k = 0; k < U; ++k) v[k] = load16<NTL>(src + i + k * lanes);
 #pragma unroll
-        for (int k = 0; k < U; ++k) store16<NTS>(dst + i + k * lanes, v[k]);
+        for (int k = 0; k < U; ++k) store16<SP>(dst + i + k * lanes, v[k]);
     }
     // ragged tail: this lane has at most U-1 vectors left
     v4u v[U];
@@ -85,11 +95,11 @@ __device__ __forceinline__ void copy_span(gsrc_t __restrict__ src, gdst_t __rest
 #pragma unroll
     for (int k = 0; k < U - 1; ++k) {
         const uint64_t j = (uint64_t)i + (uint64_t)k * lanes;
-        if (j < n) store16<NTS>(dst + j, v[k]);
+        if (j < n) store16<SP>(dst + j, v[k]);
     }
 }
 
-template <bool PACK, bool WAVE, int U, bool NTL, bool NTS>
+template <bool PACK, bool WAVE, int U, bool NTL, int SP>
 __device__ __forceinline__ void units_body(const CopyArgs &a) {
     uint32_t u_idx, lane, lanes;
     if (WAVE) {
@@ -109,20 +119,20 @@ __device__ __forceinline__ void units_body(const CopyArgs &a) {
     const uintptr_t pool = a.pool[p] + (uint64_t)u.pool_row * row * 16u;
     const uintptr_t xfer = a.xfer[p] + (uint64_t)u.xfer_row * row * 16u;
     const uint32_t n = u.n_rows * (uint32_t)row;
-    if (PACK) copy_span<U, NTL, NTS>((gsrc_t)pool, (gdst_t)xfer, n, lane, lanes);
-    else copy_span<U, NTL, NTS>((gsrc_t)xfer, (gdst_t)pool, n, lane, lanes);
+    if (PACK) copy_span<U, NTL, SP>((gsrc_t)pool, (gdst_t)xfer, n, lane, lanes);
+    else copy_span<U, NTL, SP>((gsrc_t)xfer, (gdst_t)pool, n, lane, lanes);
 }
 
 // gather: paged pool -> transfer buffer
-template <bool WAVE, int U, bool NTL, bool NTS>
+template <bool WAVE, int U, bool NTL, int SP>
 __global__ void __launch_bounds__(1024) kvl_pack_kernel(const CopyArgs a) {
-    units_body<true, WAVE, U, NTL, NTS>(a);
+    units_body<true, WAVE, U, NTL, SP>(a);
 }
 
 // scatter: transfer buffer -> paged pool
-template <bool WAVE, int U, bool NTL, bool NTS>
+template <bool WAVE, int U, bool NTL, int SP>
 __global__ void __launch_bounds__(1024) kvl_unpack_kernel(const CopyArgs a) {
-    units_body<false, WAVE, U, NTL, NTS>(a);
+    units_body<false, WAVE, U, NTL, SP>(a);
 }
 
 // Tiled form: the grid is (descriptors x tiles_per_unit, planes); a workgroup
@@ -130,7 +140,7 @@ __global__ void __launch_bounds__(1024) kvl_unpack_kernel(const CopyArgs a) {
 // vector per lane there is no loop and no dependency between a lane's memory
 // operations: the hardware keeps the memory system busy by the sheer number of
 // resident wavefronts rather than by unrolling.
-template <bool PACK, int VPT, bool NTL, bool NTS>
+template <bool PACK, int VPT, bool NTL, int SP>
 __device__ __forceinline__ void tile_body(const CopyArgs &a, uint32_t tiles_per_unit) {
     const uint32_t u_idx = blockIdx.x / tiles_per_unit;
     const uint32_t tile = blockIdx.x - u_idx * tiles_per_unit;
@@ -153,18 +163,18 @@ __device__ __forceinline__ void tile_body(const CopyArgs &a, uint32_t tiles_per_
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
         const uint32_t i = first + k * blockDim.x + threadIdx.x;
-        if (i < n) store16<NTS>(dst + i, v[k]);
+        if (i < n) store16<SP>(dst + i, v[k]);
     }
 }
 
-template <int VPT, bool NTL, bool NTS>
+template <int VPT, bool NTL, int SP>
 __global__ void __launch_bounds__(1024) kvl_pack_tile_kernel(const CopyArgs a, uint32_t tiles_per_unit) {
-    tile_body<true, VPT, NTL, NTS>(a, tiles_per_unit);
+    tile_body<true, VPT, NTL, SP>(a, tiles_per_unit);
 }
 
-template <int VPT, bool NTL, bool NTS>
+template <int VPT, bool NTL, int SP>
 __global__ void __launch_bounds__(1024) kvl_unpack_tile_kernel(const CopyArgs a, uint32_t tiles_per_unit) {
-    tile_body<false, VPT, NTL, NTS>(a, tiles_per_unit);
+    tile_body<false, VPT, NTL, SP>(a, tiles_per_unit);
 }
 
 // Fallback for row sizes or addresses that are not multiples of 16 bytes: one
@@ -186,27 +196,34 @@ __global__ void __launch_bounds__(1024) kvl_bytes_kernel(const CopyArgs a) {
 // Straight copy, one vector per lane: the tiled kernel without descriptors.
 __global__ void __launch_bounds__(256) kvl_linear_kernel(const v4u *src, v4u *dst, uint64_t n) {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) store16<true>((gdst_t)dst + i, load16<false>((gsrc_t)src + i));
+    if (i < n) store16<kLinearStorePolicy>((gdst_t)dst + i, load16<kLinearNtLoad>((gsrc_t)src + i));
 }
 
-template <bool PACK, bool WAVE, int U, bool NTL, bool NTS>
+template <bool PACK, bool WAVE, int U, bool NTL, int SP>
 static void launch_one(dim3 grid, dim3 block, hipStream_t s, const CopyArgs &a) {
-    if (PACK) hipLaunchKernelGGL((kvl_pack_kernel<WAVE, U, NTL, NTS>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((kvl_unpack_kernel<WAVE, U, NTL, NTS>), grid, block, 0, s, a);
+    if (PACK) hipLaunchKernelGGL((kvl_pack_kernel<WAVE, U, NTL, SP>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((kvl_unpack_kernel<WAVE, U, NTL, SP>), grid, block, 0, s, a);
+}
+
+template <bool PACK, bool WAVE, int U, bool NTL>
+static void launch_sp(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a) {
+    switch ((v >> 3) & 3u) {
+        case 0: launch_one<PACK, WAVE, U, NTL, 0>(g, b, s, a); break;
+        case 1: launch_one<PACK, WAVE, U, NTL, 1>(g, b, s, a); break;
+        case 2: launch_one<PACK, WAVE, U, NTL, 2>(g, b, s, a); break;
+        default: launch_one<PACK, WAVE, U, NTL, 3>(g, b, s, a); break;
+    }
 }
 
 template <bool PACK, bool WAVE, int U>
 static void launch_nt(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a) {
-    const bool ntl = v & 4u, nts = v & 8u;
-    if (ntl && nts) launch_one<PACK, WAVE, U, true, true>(g, b, s, a);
-    else if (ntl) launch_one<PACK, WAVE, U, true, false>(g, b, s, a);
-    else if (nts) launch_one<PACK, WAVE, U, false, true>(g, b, s, a);
-    else launch_one<PACK, WAVE, U, false, false>(g, b, s, a);
+    if (v & 4u) launch_sp<PACK, WAVE, U, true>(v, g, b, s, a);
+    else launch_sp<PACK, WAVE, U, false>(v, g, b, s, a);
 }
 
 template <bool PACK>
 static void launch_span_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a) {
-    const bool wave = (v & 3u) == 1u, deep = (v & 16u) != 0;
+    const bool wave = (v & 3u) == 1u, deep = (v & 32u) != 0;
     if (wave) {
         if (deep) launch_nt<PACK, true, 8>(v, g, b, s, a);
         else launch_nt<PACK, true, 4>(v, g, b, s, a);
@@ -216,19 +233,26 @@ static void launch_span_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const
     }
 }
 
-template <bool PACK, int VPT, bool NTL, bool NTS>
+template <bool PACK, int VPT, bool NTL, int SP>
 static void launch_tile_one(dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu) {
-    if (PACK) hipLaunchKernelGGL((kvl_pack_tile_kernel<VPT, NTL, NTS>), g, b, 0, s, a, tpu);
-    else hipLaunchKernelGGL((kvl_unpack_tile_kernel<VPT, NTL, NTS>), g, b, 0, s, a, tpu);
+    if (PACK) hipLaunchKernelGGL((kvl_pack_tile_kernel<VPT, NTL, SP>), g, b, 0, s, a, tpu);
+    else hipLaunchKernelGGL((kvl_unpack_tile_kernel<VPT, NTL, SP>), g, b, 0, s, a, tpu);
+}
+
+template <bool PACK, int VPT, bool NTL>
+static void launch_tile_sp(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu) {
+    switch ((v >> 3) & 3u) {
+        case 0: launch_tile_one<PACK, VPT, NTL, 0>(g, b, s, a, tpu); break;
+        case 1: launch_tile_one<PACK, VPT, NTL, 1>(g, b, s, a, tpu); break;
+        case 2: launch_tile_one<PACK, VPT, NTL, 2>(g, b, s, a, tpu); break;
+        default: launch_tile_one<PACK, VPT, NTL, 3>(g, b, s, a, tpu); break;
+    }
 }
 
 template <bool PACK, int VPT>
 static void launch_tile_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu) {
-    const bool ntl = v & 4u, nts = v & 8u;
-    if (ntl && nts) launch_tile_one<PACK, VPT, true, true>(g, b, s, a, tpu);
-    else if (ntl) launch_tile_one<PACK, VPT, true, false>(g, b, s, a, tpu);
-    else if (nts) launch_tile_one<PACK, VPT, false, true>(g, b, s, a, tpu);
-    else launch_tile_one<PACK, VPT, false, false>(g, b, s, a, tpu);
+    if (v & 4u) launch_tile_sp<PACK, VPT, true>(v, g, b, s, a, tpu);
+    else launch_tile_sp<PACK, VPT, false>(v, g, b, s, a, tpu);
 }
 
 int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_t unit_end,
@@ -253,8 +277,18 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
         a.row_elems[p] = vec ? plan->layout.row_bytes[p] / 16 : plan->layout.row_bytes[p];
 
     const uint32_t threads = plan->tuning.block_threads;
-    // default: tiled, one vector per lane, non-temporal stores
-    const uint32_t v = plan->tuning.variant ? plan->tuning.variant - 1 : (pack ? kDefaultPackCode : kDefaultUnpackCode);
+    // default: tiled, one vector per lane; cache policies as measured (see the top of this file)
+    uint32_t v;
+    if (plan->tuning.variant) {
+        v = plan->tuning.variant - 1;
+    } else if (!pack) {
+        v = kDefaultUnpackCode;
+    } else {
+        bool blocks_4k = true;
+        for (uint32_t p = plane_begin; p < plane_end; ++p)
+            blocks_4k = blocks_4k && ((uint64_t)plan->layout.block_tokens * plan->layout.row_bytes[p]) % 4096 == 0;
+        v = blocks_4k ? kDefaultPackCode : kDefaultPackCodeOddBlocks;
+    }
     dim3 block(threads);
     if (!vec) {
         dim3 grid(a.n_units, plane_end - plane_begin);
@@ -338,8 +372,9 @@ const char *kvl_variant_name(uint32_t v) {
     if (v > kvl::kNumVariants) return nullptr;
     v -= 1;
     static const char *modes[4] = {"wg/unit", "wave/unit", "tile x1", "tile x2"};
-    std::snprintf(name, sizeof name, "%s%s%s%s", modes[v & 3u], (v & 4u) ? " ntl" : "",
-                  (v & 8u) ? " nts" : "", (v & 16u) ? " deep" : "");
+    static const char *sp[4] = {"", " st:nt", " st:sc1", " st:sc1+nt"};
+    std::snprintf(name, sizeof name, "%s%s%s%s", modes[v & 3u], (v & 4u) ? " ld:nt" : "",
+                  sp[(v >> 3) & 3u], (v & 32u) ? " deep" : "");
     return name;
 }
 

@@ -64,7 +64,7 @@ def test_pack_unpack_default(name, make):
     run_hop(make())
 
 
-@pytest.mark.parametrize("variant", range(33))
+@pytest.mark.parametrize("variant", range(65))
 @pytest.mark.parametrize("threads", [64, 256, 1024])
 def test_every_variant(variant, threads):
     # units of 5 KiB against 64..1024 threads x 4..8 vectors: full steps, ragged tails and idle lanes
