@@ -1,5 +1,6 @@
 """CPU oracle (test infrastructure only): see kvl_oracle.c for what it defines."""
 from .kvl_oracle import (  # noqa: F401
     build, payload_bytes, total_hit_tokens, check, pack, unpack, stream_layers,
+    pack_range, unpack_range, check_range_scatter,
     OK, E_ARG, E_TABLE, E_BLOCK, E_DUP,
 )

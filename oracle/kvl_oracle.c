@@ -33,7 +33,11 @@
  * conservation, an independent per-byte brute force in Python on tiny pools
  * (exhaustive over permutations of up to 5 blocks), memcpy and numpy.take
  * special cases, permutation algebra across two tables, and a closed-form
- * self-describing fill.  The paper prints no worked example for this path.
+ * self-describing fill; for token ranges (below) an independent brute force,
+ * the reduction to the prefix case, and the merge identity "hit rows scattered,
+ * then tail rows scattered = whole prompt scattered".  A last test plants
+ * mistakes in copies of this file and demands that the pins notice each.  The
+ * paper prints no worked example for this path.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -92,6 +96,109 @@ int kvo_check(uint32_t bs, uint64_t pool_blocks, uint32_t n_req,
                 if (seen[id]) { rc = KVO_E_DUP; break; }
                 seen[id] = 1;
             }
+        }
+    }
+    free(seen);
+    return rc;
+}
+
+/*
+ * Token ranges.  The prefix case above is first_r = 0, count_r = hit_r.  The
+ * tail a prefill engine computes (the "miss" tokens of Section 4.1, sent on
+ * after a layer's computation and merged with the hit tokens' cache on the
+ * decode side) is first_r = hit_r, count_r = append_r; the whole prompt is
+ * first_r = 0, count_r = hit_r + append_r.  The transfer buffer is laid out as
+ * before with count_r in the place of hit_r, and token k of the range is token
+ * t = first_r + k of the request:
+ *
+ *   pack  : xfer[off_r,p + k*row_p + j] = pool_p[(tbl_r[t/bs]*bs + t%bs)*row_p + j]
+ *   unpack: the same assignment read right to left.
+ *
+ * first == NULL means all zeros.
+ */
+static uint64_t sum_u32(uint32_t n, const uint32_t *v)
+{
+    uint64_t s = 0;
+    for (uint32_t i = 0; i < n; ++i) s += v[i];
+    return s;
+}
+
+int kvo_pack_range(uint32_t bs, uint32_t n_planes, const uint32_t *row_bytes,
+                   uint32_t n_req, const uint32_t *first, const uint32_t *count,
+                   const int32_t *const *tables,
+                   const uint8_t *const *pool_planes, uint8_t *xfer,
+                   uint32_t r_begin, uint32_t r_end)
+{
+    if (!row_bytes || !count || !tables || !pool_planes || !xfer || bs == 0) return KVO_E_ARG;
+    uint64_t T = sum_u32(n_req, count);
+    uint64_t base = 0;
+    for (uint32_t p = 0; p < n_planes; ++p) {
+        uint64_t row = row_bytes[p];
+        const uint8_t *pool = pool_planes[p];
+        uint64_t off = base;
+        for (uint32_t r = 0; r < n_req; ++r) {
+            if (r >= r_begin && r < r_end) {
+                for (uint64_t k = 0; k < count[r]; ++k) {
+                    uint64_t t = (first ? first[r] : 0) + k;
+                    uint64_t phys_row = (uint64_t)tables[r][t / bs] * bs + t % bs;
+                    for (uint64_t j = 0; j < row; ++j)
+                        xfer[off + k * row + j] = pool[phys_row * row + j];
+                }
+            }
+            off += (uint64_t)count[r] * row;
+        }
+        base += T * row;
+    }
+    return KVO_OK;
+}
+
+int kvo_unpack_range(uint32_t bs, uint32_t n_planes, const uint32_t *row_bytes,
+                     uint32_t n_req, const uint32_t *first, const uint32_t *count,
+                     const int32_t *const *tables,
+                     const uint8_t *xfer, uint8_t *const *pool_planes,
+                     uint32_t r_begin, uint32_t r_end)
+{
+    if (!row_bytes || !count || !tables || !pool_planes || !xfer || bs == 0) return KVO_E_ARG;
+    uint64_t T = sum_u32(n_req, count);
+    uint64_t base = 0;
+    for (uint32_t p = 0; p < n_planes; ++p) {
+        uint64_t row = row_bytes[p];
+        uint8_t *pool = pool_planes[p];
+        uint64_t off = base;
+        for (uint32_t r = 0; r < n_req; ++r) {
+            if (r >= r_begin && r < r_end) {
+                for (uint64_t k = 0; k < count[r]; ++k) {
+                    uint64_t t = (first ? first[r] : 0) + k;
+                    uint64_t phys_row = (uint64_t)tables[r][t / bs] * bs + t % bs;
+                    for (uint64_t j = 0; j < row; ++j)
+                        pool[phys_row * row + j] = xfer[off + k * row + j];
+                }
+            }
+            off += (uint64_t)count[r] * row;
+        }
+        base += T * row;
+    }
+    return KVO_OK;
+}
+
+/* Destination blocks of a scatter over token ranges must be distinct
+ * (0 or KVO_E_DUP); table length and block ids are checked by kvo_check. */
+int kvo_check_range_scatter(uint32_t bs, uint64_t pool_blocks, uint32_t n_req,
+                            const uint32_t *first, const uint32_t *count,
+                            const int32_t *const *tables)
+{
+    if (!count || !tables || bs == 0) return KVO_E_ARG;
+    uint8_t *seen = (uint8_t *)calloc(pool_blocks ? pool_blocks : 1, 1);
+    if (!seen) return KVO_E_ARG;
+    int rc = KVO_OK;
+    for (uint32_t r = 0; r < n_req && rc == KVO_OK; ++r) {
+        if (count[r] == 0) continue;
+        uint64_t t0 = first ? first[r] : 0, t1 = t0 + count[r];
+        for (uint64_t b = t0 / bs; b <= (t1 - 1) / bs; ++b) {
+            int64_t id = tables[r][b];
+            if (id < 0 || (uint64_t)id >= pool_blocks) { rc = KVO_E_BLOCK; break; }
+            if (seen[id]) { rc = KVO_E_DUP; break; }
+            seen[id] = 1;
         }
     }
     free(seen);

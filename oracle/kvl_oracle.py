@@ -48,6 +48,15 @@ def _bind(path: str):
     lib.kvo_unpack.restype = C.c_int
     lib.kvo_unpack.argtypes = [C.c_uint32, C.c_uint32, u32p, C.c_uint32, u32p, i32pp,
                                C.c_void_p, u8pp, C.c_uint32, C.c_uint32]
+    u32p_n = C.POINTER(C.c_uint32)
+    lib.kvo_pack_range.restype = C.c_int
+    lib.kvo_pack_range.argtypes = [C.c_uint32, C.c_uint32, u32p, C.c_uint32, u32p_n, u32p, i32pp,
+                                   u8pp, C.c_void_p, C.c_uint32, C.c_uint32]
+    lib.kvo_unpack_range.restype = C.c_int
+    lib.kvo_unpack_range.argtypes = [C.c_uint32, C.c_uint32, u32p, C.c_uint32, u32p_n, u32p, i32pp,
+                                     C.c_void_p, u8pp, C.c_uint32, C.c_uint32]
+    lib.kvo_check_range_scatter.restype = C.c_int
+    lib.kvo_check_range_scatter.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, u32p_n, u32p, i32pp]
     return lib
 
 
@@ -181,6 +190,70 @@ def unpack(block_tokens: int, row_bytes, hit, tables, xfer: np.ndarray,
     else:
         with ThreadPoolExecutor(len(ranges)) as ex:
             list(ex.map(run, ranges))
+
+
+def pack_range(block_tokens: int, row_bytes, first, count, tables, pool_planes: Sequence[np.ndarray],
+               xfer: Optional[np.ndarray] = None, threads: int = 1) -> np.ndarray:
+    """Gather token rows [first_r, first_r + count_r) of every request (first=None: zeros)."""
+    lib = _load()
+    c, cp = _u32(count)
+    f, fp = _u32(first) if first is not None else (None, None)
+    rb, rbp = _u32(row_bytes)
+    keep, tp = _tables(tables)
+    pp = _planes(pool_planes, writable=False)
+    n = payload_bytes(c, rb)
+    if xfer is None:
+        xfer = np.empty(n, dtype=np.uint8)
+    if xfer.dtype != np.uint8 or xfer.size < n or not xfer.flags["C_CONTIGUOUS"]:
+        raise ValueError("transfer buffer too small or not contiguous uint8")
+
+    def run(rng):
+        rc = lib.kvo_pack_range(block_tokens, rb.size, rbp, c.size, fp, cp, tp, pp,
+                                xfer.ctypes.data, rng[0], rng[1])
+        if rc != OK:
+            raise RuntimeError(f"kvo_pack_range failed: {rc}")
+
+    ranges = _ranges(c.size, threads) if c.size else []
+    if len(ranges) <= 1:
+        run((0, c.size))
+    else:
+        with ThreadPoolExecutor(len(ranges)) as ex:
+            list(ex.map(run, ranges))
+    return xfer
+
+
+def unpack_range(block_tokens: int, row_bytes, first, count, tables, xfer: np.ndarray,
+                 pool_planes: Sequence[np.ndarray], threads: int = 1) -> None:
+    """Scatter a transfer buffer into token rows [first_r, first_r + count_r), in place."""
+    lib = _load()
+    c, cp = _u32(count)
+    f, fp = _u32(first) if first is not None else (None, None)
+    rb, rbp = _u32(row_bytes)
+    keep, tp = _tables(tables)
+    pp = _planes(pool_planes, writable=True)
+    n = payload_bytes(c, rb)
+    if xfer.dtype != np.uint8 or xfer.size < n or not xfer.flags["C_CONTIGUOUS"]:
+        raise ValueError("transfer buffer too small or not contiguous uint8")
+
+    def run(rng):
+        rc = lib.kvo_unpack_range(block_tokens, rb.size, rbp, c.size, fp, cp, tp,
+                                  xfer.ctypes.data, pp, rng[0], rng[1])
+        if rc != OK:
+            raise RuntimeError(f"kvo_unpack_range failed: {rc}")
+
+    ranges = _ranges(c.size, threads) if c.size else []
+    if len(ranges) <= 1:
+        run((0, c.size))
+    else:
+        with ThreadPoolExecutor(len(ranges)) as ex:
+            list(ex.map(run, ranges))
+
+
+def check_range_scatter(block_tokens: int, pool_blocks: int, first, count, tables) -> int:
+    c, cp = _u32(count)
+    f, fp = _u32(first) if first is not None else (None, None)
+    keep, tp = _tables(tables)
+    return int(_load().kvo_check_range_scatter(block_tokens, pool_blocks, c.size, fp, cp, tp))
 
 
 def stream_layers(block_tokens: int, row_bytes, hit, tables, host_layers: Sequence[np.ndarray],

@@ -247,7 +247,68 @@ def pin_threads_agree():
         assert u.tobytes() == v.tobytes()
 
 
-PINS = [pin_brute_force, pin_exhaustive_permutations, pin_round_trip, pin_byte_conservation,
+def brute_pack_range(bs, row_bytes, first, count, tables, pools):
+    out = bytearray()
+    for p, row in enumerate(row_bytes):
+        for r in range(len(count)):
+            for t in range(int(first[r]), int(first[r]) + int(count[r])):
+                blk, within = divmod(t, bs)
+                start = (int(tables[r][blk]) * bs + within) * row
+                out += bytes(pools[p][start:start + row])
+    return np.frombuffer(bytes(out), dtype=np.uint8)
+
+
+def pin_ranges():
+    """Token ranges (the appended tail, the whole prompt): brute force, reduction to the
+    prefix case, and the merge property of Section 4.1 (hit cache + miss cache = prompt cache)."""
+    for kw in TINY:
+        w = W.tiny(**kw)
+        bs, rows = w.layout.block_tokens, w.layout.row_bytes
+        src = W.fill_pool(w, 0, "src")
+        zero = np.zeros_like(w.hit)
+        # reduction: first = 0, count = hit is the prefix definition
+        assert oracle.pack_range(bs, rows, zero, w.hit, w.src.tables, src).tobytes() == _o_pack(w, src).tobytes()
+        assert oracle.pack_range(bs, rows, None, w.hit, w.src.tables, src).tobytes() == _o_pack(w, src).tobytes()
+        # brute force on the tail and on an arbitrary inner range
+        tail = oracle.pack_range(bs, rows, w.hit, w.app, w.src.tables, src)
+        assert tail.tobytes() == brute_pack_range(bs, rows, w.hit, w.app, w.src.tables, src).tobytes(), kw
+        tot = w.hit + w.app
+        f2 = tot // 3
+        c2 = tot - f2 - tot // 4
+        inner = oracle.pack_range(bs, rows, f2, c2, w.src.tables, src)
+        assert inner.tobytes() == brute_pack_range(bs, rows, f2, c2, w.src.tables, src).tobytes(), kw
+        # merge: scattering the hit part and then the tail equals scattering the whole prompt
+        whole = oracle.pack_range(bs, rows, zero, tot, w.src.tables, src)
+        hitp = _o_pack(w, src)
+        a = W.sentinel_pool(w, "dst")
+        b = W.sentinel_pool(w, "dst")
+        oracle.unpack_range(bs, rows, zero, tot, w.dst.tables, whole, a)
+        oracle.unpack(bs, rows, w.hit, w.dst.tables, hitp, b)
+        oracle.unpack_range(bs, rows, w.hit, w.app, w.dst.tables, tail, b)
+        for u, v in zip(a, b):
+            assert u.tobytes() == v.tobytes(), kw
+        # the whole-prompt buffer is, per plane and request, the hit rows followed by the tail rows
+        T_h, T_a, T_w = int(w.hit.sum()), int(w.app.sum()), int(tot.sum())
+        ph = pa = pw = 0
+        for p, row in enumerate(rows):
+            ph, pa, pw = sum(T_h * q for q in rows[:p]), sum(T_a * q for q in rows[:p]), sum(T_w * q for q in rows[:p])
+            for r in range(len(tot)):
+                nh, na = int(w.hit[r]) * row, int(w.app[r]) * row
+                assert whole[pw:pw + nh].tobytes() == hitp[ph:ph + nh].tobytes()
+                assert whole[pw + nh:pw + nh + na].tobytes() == tail[pa:pa + na].tobytes()
+                ph, pa, pw = ph + nh, pa + na, pw + nh + na
+        # threads agree
+        assert oracle.pack_range(bs, rows, w.hit, w.app, w.src.tables, src, threads=3).tobytes() == tail.tobytes()
+    # range scatter preconditions: a shared boundary block between two requests' ranges is an alias
+    tabs = [np.array([1, 2], np.int32), np.array([2, 3], np.int32)]
+    assert oracle.check_range_scatter(4, 8, [0, 0], [5, 3], tabs) == oracle.E_DUP    # both touch block 2
+    assert oracle.check_range_scatter(4, 8, [0, 0], [4, 3], tabs) == oracle.OK      # first stops inside block 1
+    assert oracle.check_range_scatter(4, 8, [0, 4], [5, 3], tabs) == oracle.OK      # second starts in block 3
+    assert oracle.check_range_scatter(4, 8, [0, 0], [0, 0], tabs) == oracle.OK
+    assert oracle.check_range_scatter(4, 3, [0, 4], [4, 3], tabs) == oracle.E_BLOCK
+
+
+PINS = [pin_ranges, pin_brute_force, pin_exhaustive_permutations, pin_round_trip, pin_byte_conservation,
         pin_memcpy_and_take, pin_permutation_algebra, pin_closed_form_fill, pin_threads_agree]
 
 
@@ -329,6 +390,13 @@ MUTANTS = [
     ("row loop one short", r"j < row; \+\+j", "j + 1 < row; ++j"),
     ("xfer index transposed", r"xfer\[off \+ t \* row \+ j\]", "xfer[off + j * hit[r] + t]"),
     ("payload counts one plane", r"bytes \+= T \* \(uint64_t\)row_bytes\[p\];", "bytes = T * (uint64_t)row_bytes[p];"),
+    ("range: first token dropped", r"uint64_t t = \(first \? first\[r\] : 0\) \+ k;", "uint64_t t = k;"),
+    ("range: buffer indexed by request token", r"xfer\[off \+ k \* row \+ j\]", "xfer[off + t * row + j]"),
+    ("range: request offset counts skipped tokens", r"off \+= \(uint64_t\)count\[r\] \* row;",
+     "off += ((uint64_t)count[r] + (first ? first[r] : 0)) * row;"),
+    ("range: plane base from the wrong total", r"uint64_t T = sum_u32\(n_req, count\);",
+     "uint64_t T = sum_u32(n_req, first ? first : count);"),
+    ("range: loop one short", r"k < count\[r\]; \+\+k", "k + 1 < count[r]; ++k"),
 ]
 
 
