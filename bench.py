@@ -210,6 +210,8 @@ def main() -> int:
                 "algorithmic_bytes_per_launch": 2 * payload, "avg_launch_ms": round(avg, 4),
                 "min_launch_ms": round(float(ms.min()), 4), "launches": int(ms.size)}
 
+    tail = tail_return_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN)
+
     roof_pack = roof("kvl_pack_tile_kernel", pack_ms)
     roof_unpack = roof("kvl_unpack_tile_kernel", unpack_ms)
     dominant, other = (roof_pack, roof_unpack) if pack_ms.sum() >= unpack_ms.sum() else (roof_unpack, roof_pack)
@@ -229,6 +231,7 @@ def main() -> int:
         "tokens_layers_per_s": round(T * L / (ms_per_step * 1e-3), 1),
         "plan_ms": round(plan_ms, 3), "verified_rows_vs_oracle": verified,
         "linear_copy_ceiling_gbps": round(ceiling, 1),
+        "tail_return": tail,
     }
     del src, dst, xfer
     torch.cuda.empty_cache()
@@ -268,6 +271,35 @@ def verify_tags(w, src_planes, dst_planes, xfer, T) -> int:
         off += T * r
         checked += T + w.dst.pool_blocks * bs
     return checked
+
+
+def tail_return_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN) -> dict:
+    """The hop after each layer's compute on the decode-engine read path: only the appended
+    (miss) tokens' cache goes back, prefill pool -> transfer buffer -> decode pool.  A few
+    hundred tokens per request, so launches, not bandwidth, set the time."""
+    import torch
+    import paper_2602_21548_amd as K
+    g = K.kvl_plan(lay_dst, w.hit, w.app, w.dst.tables, K.KVL_GATHER | K.KVL_TOKENS_APPEND)
+    s = K.kvl_plan(lay_src, w.hit, w.app, w.src.tables, K.KVL_SCATTER | K.KVL_TOKENS_APPEND)
+    n, T = g.payload_bytes, g.hit_tokens
+    x = torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
+    ms = []
+    for rep in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for l in range(L):
+            K.kvl_pack_layer(g, dst[l % WIN], x, stream=stream)
+            K.kvl_unpack_layer(s, x, src[l % WIN], stream=stream)
+        e1.record(stream)
+        e1.synchronize()
+        if rep:
+            ms.append(e0.elapsed_time(e1) / L)
+    g.destroy()
+    s.destroy()
+    per_layer = float(np.mean(ms))
+    return {"what": "appended-tail return hop (pack + unpack per layer), same workload",
+            "tokens": T, "payload_bytes_per_layer": n, "us_per_layer": round(per_layer * 1e3, 2),
+            "payload_gbps": round(n / (per_layer * 1e-3) / 1e9, 1) if n else 0.0}
 
 
 def copy_ceiling(stream) -> float:

@@ -21,7 +21,9 @@
  *                         memory (the prefill engine's host buffer)
  *   kvl_stream_layers     all layers: load of layer l+1 under compute of layer l
  *
- * Transfer-buffer layout (one layer), with T = sum of hit tokens of the batch:
+ * Transfer-buffer layout (one layer), with T = sum of hit tokens of the batch
+ * (for a plan over another token range, KVL_TOKENS_*: read "tokens of the range"
+ * for "hit tokens" throughout):
  *   plane p starts at byte  sum_{q<p} T * row_bytes[q];
  *   inside plane p request r starts at  sum_{s<r} hit_s * row_bytes[p];
  *   token t of request r follows at t * row_bytes[p].  Dense, no padding.
@@ -72,6 +74,13 @@ extern "C" {
 #define KVL_HOST_ONLY  4u  /* make descriptors on the host only (no device is touched);
                               such a plan can be inspected but not executed */
 #define KVL_NO_MERGE   8u  /* do not merge physically adjacent blocks into one run */
+/* Which token rows of each request the plan moves.  Default: the hit prefix
+ * [0, hit).  The other two serve the step after a layer's computation
+ * (Section 4.1): the decode-engine read path sends on only the miss tokens'
+ * cache, which is merged with the hit tokens' cache already there; the
+ * prefill-engine read path sends on hit and miss tokens together. */
+#define KVL_TOKENS_APPEND 16u  /* the appended tail [hit, hit + append) */
+#define KVL_TOKENS_ALL    32u  /* the whole prompt [0, hit + append) */
 
 typedef struct kvl_plan_s kvl_plan_t;   /* opaque, library-owned */
 
@@ -113,8 +122,8 @@ typedef struct {
 
 /* Build a plan.  Validates the batch (KVL_ERANGE: a block id outside
  * [0, pool_blocks), a table shorter than the request needs, or more than 2^32-1
- * pool rows or hit tokens; KVL_EALIAS: with KVL_SCATTER, a block that receives
- * hit rows is named twice), lays out the transfer buffer, merges physically
+ * pool rows or moved tokens; KVL_EALIAS: with KVL_SCATTER, a block that receives
+ * rows is named twice), lays out the transfer buffer, merges physically
  * adjacent blocks of a request into runs, splits runs into descriptors and,
  * unless KVL_HOST_ONLY, uploads them to the current device.
  * requests: host array of n_req entries (n_req may be 0).  *out receives the
@@ -131,7 +140,7 @@ int kvl_plan_set_tuning(kvl_plan_t *plan, const kvl_tuning_t *tuning);
 
 /* Plan inspection (host side, valid for any plan). */
 int kvl_plan_payload_bytes(const kvl_plan_t *plan, uint64_t *bytes_per_layer); /* all planes */
-int kvl_plan_hit_tokens(const kvl_plan_t *plan, uint64_t *tokens);             /* T */
+int kvl_plan_hit_tokens(const kvl_plan_t *plan, uint64_t *tokens);             /* T: tokens the plan moves */
 int kvl_plan_n_units(const kvl_plan_t *plan, uint64_t *n_units);
 /* Copy up to capacity descriptors into out (host array); *n_units gets the total. */
 int kvl_plan_get_units(const kvl_plan_t *plan, kvl_unit_t *out, uint64_t capacity, uint64_t *n_units);

@@ -21,6 +21,7 @@ from . import build as _build
 KVL_MAX_PLANES = 4
 KVL_OK, KVL_EINVAL, KVL_ERANGE, KVL_EALIAS, KVL_ESPACE, KVL_EHIP, KVL_ENOMEM = 0, -1, -2, -3, -4, -5, -6
 KVL_GATHER, KVL_SCATTER, KVL_HOST_ONLY, KVL_NO_MERGE = 1, 2, 4, 8
+KVL_TOKENS_APPEND, KVL_TOKENS_ALL = 16, 32
 
 
 class KvlError(RuntimeError):

@@ -72,7 +72,9 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
     if (!layout || !out || (n_req && !req)) return KVL_EINVAL;
     *out = nullptr;
     if (!(flags & (KVL_GATHER | KVL_SCATTER))) return KVL_EINVAL;
-    if (flags & ~(KVL_GATHER | KVL_SCATTER | KVL_HOST_ONLY | KVL_NO_MERGE)) return KVL_EINVAL;
+    if (flags & ~(KVL_GATHER | KVL_SCATTER | KVL_HOST_ONLY | KVL_NO_MERGE | KVL_TOKENS_APPEND | KVL_TOKENS_ALL))
+        return KVL_EINVAL;
+    if ((flags & KVL_TOKENS_APPEND) && (flags & KVL_TOKENS_ALL)) return KVL_EINVAL;
     if (layout->block_tokens == 0 || layout->n_planes == 0 || layout->n_planes > KVL_MAX_PLANES)
         return KVL_EINVAL;
     const uint64_t bs = layout->block_tokens;
@@ -104,8 +106,25 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
         std::vector<uint8_t> taken;
         if (scatter) taken.assign(layout->pool_blocks ? layout->pool_blocks : 1, 0);
 
+        // token range of request q that this plan moves
+        auto range = [flags](const kvl_request_t &q, uint64_t *t0, uint64_t *t1) {
+            if (flags & KVL_TOKENS_APPEND) {
+                *t0 = q.hit_tokens;
+                *t1 = (uint64_t)q.hit_tokens + q.append_tokens;
+            } else if (flags & KVL_TOKENS_ALL) {
+                *t0 = 0;
+                *t1 = (uint64_t)q.hit_tokens + q.append_tokens;
+            } else {
+                *t0 = 0;
+                *t1 = q.hit_tokens;
+            }
+        };
         uint64_t T = 0;
-        for (uint32_t r = 0; r < n_req; ++r) T += req[r].hit_tokens;
+        for (uint32_t r = 0; r < n_req; ++r) {
+            uint64_t t0, t1;
+            range(req[r], &t0, &t1);
+            T += t1 - t0;
+        }
         if (T > UINT32_MAX) { delete plan; return KVL_ERANGE; }
         plan->hit_tokens = T;
 
@@ -121,30 +140,36 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
                 const int64_t id = q.block_table[b];
                 if (id < 0 || (uint64_t)id >= layout->pool_blocks) { delete plan; return KVL_ERANGE; }
             }
-            const uint64_t hit_blocks = ((uint64_t)q.hit_tokens + bs - 1) / bs;
+            uint64_t t0, t1;
+            range(q, &t0, &t1);
+            if (t1 == t0) continue;
+            const uint64_t b_first = t0 / bs, b_end = (t1 + bs - 1) / bs;   // blocks [b_first, b_end) are touched
             if (scatter) {
-                for (uint64_t b = 0; b < hit_blocks; ++b) {
+                for (uint64_t b = b_first; b < b_end; ++b) {
                     uint8_t &t = taken[(size_t)q.block_table[b]];
                     if (t) { delete plan; return KVL_EALIAS; }
                     t = 1;
                 }
             }
-            // walk the hit blocks, growing a run while the next block is the
-            // physical successor of a full block
-            uint64_t b = 0;
-            while (b < hit_blocks) {
+            // rows of block b that lie in the range: [lo, hi) in request tokens
+            auto lo_of = [&](uint64_t b) { return std::max<uint64_t>(t0, b * bs); };
+            auto hi_of = [&](uint64_t b) { return std::min<uint64_t>(t1, (b + 1) * bs); };
+            // walk the touched blocks, growing a run while it ends on a block
+            // boundary and the next block is the physical successor
+            uint64_t b = b_first;
+            while (b < b_end) {
                 const uint64_t first = (uint64_t)q.block_table[b];
-                uint64_t rows = std::min<uint64_t>(bs, q.hit_tokens - b * bs);
+                uint64_t pool_row = first * bs + (lo_of(b) - b * bs);
+                uint64_t rows = hi_of(b) - lo_of(b);
                 uint64_t e = b + 1;
-                while (merge && e < hit_blocks && rows == (e - b) * bs &&
+                while (merge && e < b_end && hi_of(e - 1) == e * bs &&
                        (uint64_t)q.block_table[e] == first + (e - b)) {
-                    rows += std::min<uint64_t>(bs, q.hit_tokens - e * bs);
+                    rows += hi_of(e) - lo_of(e);
                     ++e;
                 }
                 // split the run evenly into pieces of at most max_rows rows
                 const uint64_t pieces = (rows + max_rows - 1) / max_rows;
                 const uint64_t base = rows / pieces, extra = rows % pieces;
-                uint64_t pool_row = first * bs;
                 for (uint64_t k = 0; k < pieces; ++k) {
                     const uint64_t n = base + (k < extra ? 1 : 0);
                     kvl_unit_t u{(uint32_t)pool_row, (uint32_t)xfer_row, (uint32_t)n, 0};

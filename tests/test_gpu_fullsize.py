@@ -62,6 +62,41 @@ def test_full_size_layer(idx):
     s.destroy()
 
 
+@pytest.mark.parametrize("idx,flag", [(2, "append"), (3, "all"), (4, "append")])
+def test_full_size_token_ranges(idx, flag):
+    """The hop after a layer's compute at full size: the appended tail (a few hundred tokens
+    per request: the launch-bound regime) or the whole prompt, prefill pool -> decode pool."""
+    t0 = time.perf_counter()
+    w = W.config(idx)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    kflag = K.KVL_TOKENS_APPEND if flag == "append" else K.KVL_TOKENS_ALL
+    zero = np.zeros_like(w.hit)
+    first, count = (w.hit, w.app) if flag == "append" else (zero, w.hit + w.app)
+    pe = W.fill_pool_fast(w, 1, "dst")
+    de = W.fill_pool_fast(w, 2, "src")
+    want_x = oracle.pack_range(bs, rows, first, count, w.dst.tables, pe, threads=THREADS)
+    g = K.kvl_plan(K.make_layout(w.layout.n_layers, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables,
+                   K.KVL_GATHER | kflag)
+    s = K.kvl_plan(K.make_layout(w.layout.n_layers, bs, rows, w.src.pool_blocks), w.hit, w.app, w.src.tables,
+                   K.KVL_SCATTER | kflag)
+    n = g.payload_bytes
+    assert n == want_x.size
+    d_pe = [torch.from_numpy(p).cuda() for p in pe]
+    d_de = [torch.from_numpy(p).cuda() for p in de]
+    d_x = torch.full((n + 4096,), 0x3C, dtype=torch.uint8, device="cuda")
+    K.kvl_pack_layer(g, d_pe, d_x)
+    K.kvl_unpack_layer(s, d_x, d_de)
+    torch.cuda.synchronize()
+    got = to_host(d_x)
+    assert np.array_equal(got[:n], want_x) and np.all(got[n:] == 0x3C)
+    oracle.unpack_range(bs, rows, first, count, w.src.tables, want_x, de, threads=THREADS)   # de becomes the expectation
+    for p in range(len(rows)):
+        assert np.array_equal(to_host(d_de[p]), de[p]), f"merged decode-side pool differs in plane {p}"
+    print(f"[cfg{idx} {flag}] {n / 1e6:.1f} MB payload, done after {time.perf_counter() - t0:.1f} s", flush=True)
+    g.destroy()
+    s.destroy()
+
+
 def test_full_size_streamed_layers():
     t0 = time.perf_counter()
     w = W.config(5)

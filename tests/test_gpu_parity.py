@@ -64,6 +64,47 @@ def test_pack_unpack_default(name, make):
     run_hop(make())
 
 
+def run_range_hop(w, flag, layer=0, **tuning):
+    """The step after a layer's compute: gather a token range from the prefill-side pool,
+    merge it into the decode-side pool that already holds other rows."""
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    zero = np.zeros_like(w.hit)
+    first, count = (w.hit, w.app) if flag == K.KVL_TOKENS_APPEND else (zero, w.hit + w.app)
+    pe = W.fill_pool(w, layer, "dst")               # prefill engine's pool (source of this hop)
+    de = W.fill_pool(w, layer, "src")               # decode engine's pool: must keep every other row
+    want_x = oracle.pack_range(bs, rows, first, count, w.dst.tables, pe, threads=8)
+    want_de = [p.copy() for p in de]
+    oracle.unpack_range(bs, rows, first, count, w.src.tables, want_x, want_de, threads=8)
+    s_lay = K.make_layout(w.layout.n_layers, bs, rows, w.dst.pool_blocks)
+    d_lay = K.make_layout(w.layout.n_layers, bs, rows, w.src.pool_blocks)
+    g = K.kvl_plan(s_lay, w.hit, w.app, w.dst.tables, K.KVL_GATHER | flag, **tuning)
+    s = K.kvl_plan(d_lay, w.hit, w.app, w.src.tables, K.KVL_SCATTER | flag, **tuning)
+    n = g.payload_bytes
+    assert n == want_x.size == s.payload_bytes
+    d_pe, d_de = planes_to_dev(pe), planes_to_dev(de)
+    d_x = torch.full((n + GUARD,), 0x3C, dtype=torch.uint8, device="cuda")
+    K.kvl_pack_layer(g, d_pe, d_x)
+    K.kvl_unpack_layer(s, d_x, d_de)
+    torch.cuda.synchronize()
+    got = to_host(d_x)
+    assert same_bytes(got[:n], want_x) and np.all(got[n:] == 0x3C)
+    for a, b in zip(d_de, want_de):
+        assert same_bytes(to_host(a), b)
+    g.destroy()
+    s.destroy()
+
+
+@pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("flag", [K.KVL_TOKENS_APPEND, K.KVL_TOKENS_ALL], ids=["append", "all"])
+def test_token_ranges(name, make, flag):
+    w = make()
+    if name == "cfg1":
+        w.app[:] = [7, 16, 0, 25]                   # cfg1 has no tail of its own; 4 x 63 blocks cover 1008 tokens
+        w.hit[:] = [1000, 992, 1001, 983]
+    run_range_hop(w, flag)
+    run_range_hop(w, flag, unit_bytes=2048, variant=2)
+
+
 @pytest.mark.parametrize("variant", range(65))
 @pytest.mark.parametrize("threads", [64, 256, 1024])
 def test_every_variant(variant, threads):

@@ -188,3 +188,70 @@ def test_h2d_chunks_cover_the_payload():
     with pytest.raises(K.KvlError) as e:
         p.chunks(1024)                      # smaller than one descriptor
     assert e.value.code == K.KVL_ESPACE
+
+
+# --------------------------------------------------------------------------
+# token ranges: the appended tail and the whole prompt
+# --------------------------------------------------------------------------
+
+def _range_of(w, flag):
+    zero = np.zeros_like(w.hit)
+    if flag == K.KVL_TOKENS_APPEND:
+        return w.hit, w.app
+    if flag == K.KVL_TOKENS_ALL:
+        return zero, w.hit + w.app
+    return zero, w.hit
+
+
+@pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("flag", [K.KVL_TOKENS_APPEND, K.KVL_TOKENS_ALL], ids=["append", "all"])
+def test_range_descriptors_reproduce_the_oracle(name, make, flag):
+    w = make()
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    first, count = _range_of(w, flag)
+    for ub in (0, 2048):
+        g = host_plan(w, "src", K.KVL_GATHER | flag, unit_bytes=ub)
+        assert g.hit_tokens == int(count.astype(np.int64).sum())
+        assert g.payload_bytes == oracle.payload_bytes(count, rows)
+        src = W.fill_pool(w, 0, "src")
+        want = oracle.pack_range(bs, rows, first, count, w.src.tables, src)
+        assert replay_pack(g, rows, src).tobytes() == want.tobytes()
+        s = host_plan(w, "dst", K.KVL_SCATTER | flag, unit_bytes=ub)
+        got, ref = W.sentinel_pool(w, "dst"), W.sentinel_pool(w, "dst")
+        replay_unpack(s, rows, want, got)
+        oracle.unpack_range(bs, rows, first, count, w.dst.tables, want, ref)
+        for a, b in zip(got, ref):
+            assert a.tobytes() == b.tobytes()
+
+
+def test_range_merging_and_flags():
+    bs, row = 16, 32
+    lay = K.make_layout(1, bs, (row,), 64)
+    tbl = [np.arange(10, 30, dtype=np.int32)]
+    # tail starts mid-block and runs over 3 physically consecutive blocks: one run
+    p = K.kvl_plan(lay, [5 * bs + 3], [2 * bs + 4], tbl, K.KVL_GATHER | K.KVL_HOST_ONLY | K.KVL_TOKENS_APPEND,
+                   unit_bytes=1 << 20)
+    assert p.units()[:, :3].tolist() == [[15 * bs + 3, 0, 2 * bs + 4]]
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_plan(lay, [5], [4], tbl, K.KVL_GATHER | K.KVL_HOST_ONLY | K.KVL_TOKENS_APPEND | K.KVL_TOKENS_ALL)
+    assert e.value.code == K.KVL_EINVAL
+
+
+@pytest.mark.parametrize("case", [
+    dict(hit=[0, 0], app=[5, 3], tables=[[1, 2], [2, 3]]),     # both tails touch block 2
+    dict(hit=[0, 0], app=[4, 3], tables=[[1, 2], [2, 3]]),
+    dict(hit=[0, 4], app=[5, 3], tables=[[1, 2], [2, 3]]),     # second tail starts in block 3
+    dict(hit=[3, 4], app=[0, 0], tables=[[1], [1]]),           # hit blocks alias, tails are empty
+])
+def test_range_validation_agrees_with_the_oracle(case):
+    bs, pool = 4, 8
+    lay = K.make_layout(1, bs, (16,), pool)
+    tabs = [np.array(t, dtype=np.int32) for t in case["tables"]]
+    hit, app = np.array(case["hit"], np.uint32), np.array(case["app"], np.uint32)
+    want = ERR[oracle.check_range_scatter(bs, pool, hit, app, tabs)]
+    try:
+        K.kvl_plan(lay, hit, app, tabs, K.KVL_SCATTER | K.KVL_HOST_ONLY | K.KVL_TOKENS_APPEND)
+        got = K.KVL_OK
+    except K.KvlError as e:
+        got = e.code
+    assert got == want, case
