@@ -191,6 +191,15 @@ int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
                          void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
                          void *const *pool_planes, void *copy_stream, void *kernel_stream);
 
+/* The same result with one hipMemcpyAsync per descriptor and plane, straight from
+ * the pinned host buffer into the paged pool: no staging, no kernel.  This is the
+ * many-small-copies pattern whose per-copy submission cost Section 5.2 measures
+ * (5-7 us per copy on its hardware); it exists to measure that cost here and is
+ * not the fast path.  *n_copies (may be NULL) receives the number of copies
+ * enqueued on stream. */
+int kvl_h2d_blockwise_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
+                            void *const *pool_planes, void *stream, uint64_t *n_copies);
+
 /* A 16-byte sample of what the compute of a layer sees. */
 typedef struct {
     uint32_t plane;

@@ -103,6 +103,8 @@ _SIGNATURES = {
     "kvl_unpack_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_void_p]),
     "kvl_h2d_unpack_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                        C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p]),
+    "kvl_h2d_blockwise_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
+                                          C.POINTER(C.c_uint64)]),
     "kvl_stream_layers": (C.c_int, [_PLAN_P, C.POINTER(kvl_stream_cfg_t), C.POINTER(kvl_stream_stats_t)]),
     "kvl_measure_h2d_peak": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p,
                                        C.POINTER(C.c_double)]),
@@ -287,8 +289,13 @@ def kvl_pack_layer(plan: Plan, pool_planes: Sequence[torch.Tensor], xfer: torch.
 
 
 def kvl_unpack_layer(plan: Plan, xfer: torch.Tensor, pool_planes: Sequence[torch.Tensor], stream=None) -> None:
+    """xfer: a device tensor, or a pinned host tensor (the kernel then reads it over the host link)."""
     arr = _plane_ptrs(plan, pool_planes, "kvl_unpack_layer pool")
-    _check(_lib.kvl_unpack_layer(plan.handle, _dev(xfer, "xfer"), _nbytes(xfer), arr, _stream_handle(stream)),
+    if isinstance(xfer, torch.Tensor) and not xfer.is_cuda:
+        ptr = _pinned(xfer, "xfer", 0)
+    else:
+        ptr = _dev(xfer, "xfer")
+    _check(_lib.kvl_unpack_layer(plan.handle, ptr, _nbytes(xfer), arr, _stream_handle(stream)),
            "kvl_unpack_layer")
 
 
@@ -308,6 +315,17 @@ def kvl_h2d_unpack_layer(plan: Plan, pinned_host_xfer: torch.Tensor, dev_staging
     _check(_lib.kvl_h2d_unpack_layer(plan.handle, host, _dev(dev_staging, "staging"), _nbytes(dev_staging),
                                      chunk_bytes, arr, _stream_handle(copy_stream),
                                      _stream_handle(kernel_stream)), "kvl_h2d_unpack_layer")
+
+
+def kvl_h2d_blockwise_layer(plan: Plan, pinned_host_xfer: torch.Tensor, pool_planes: Sequence[torch.Tensor],
+                            stream=None) -> int:
+    """One hipMemcpyAsync per descriptor and plane (a measurement aid); returns the number of copies."""
+    arr = _plane_ptrs(plan, pool_planes, "kvl_h2d_blockwise_layer pool")
+    host = _pinned(pinned_host_xfer, "pinned_host_xfer", plan.payload_bytes)
+    n = C.c_uint64()
+    _check(_lib.kvl_h2d_blockwise_layer(plan.handle, host, arr, _stream_handle(stream), C.byref(n)),
+           "kvl_h2d_blockwise_layer")
+    return int(n.value)
 
 
 def kvl_stream_layers(plan: Plan, host_layers: Sequence[torch.Tensor],

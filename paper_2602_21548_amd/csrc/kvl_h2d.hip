@@ -90,6 +90,30 @@ int kvl_h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xfer,
                                   pool_planes, cs, ks, nullptr, &ring_pos);
 }
 
+int kvl_h2d_blockwise_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
+                            void *const *pool_planes, void *stream, uint64_t *n_copies) {
+    if (!plan || !pool_planes) return KVL_EINVAL;
+    if (!(plan->flags & KVL_SCATTER) || (plan->flags & KVL_HOST_ONLY)) return KVL_EINVAL;
+    if (n_copies) *n_copies = 0;
+    if (plan->units.empty()) return KVL_OK;
+    if (!pinned_host_xfer) return KVL_EINVAL;
+    const char *host = static_cast<const char *>(pinned_host_xfer);
+    uint64_t copies = 0;
+    for (uint32_t p = 0; p < plan->layout.n_planes; ++p) {
+        if (!pool_planes[p]) return KVL_EINVAL;
+        const uint64_t row = plan->layout.row_bytes[p];
+        char *pool = static_cast<char *>(pool_planes[p]);
+        for (const kvl_unit_t &u : plan->units) {
+            KVL_HIP(hipMemcpyAsync(pool + (uint64_t)u.pool_row * row,
+                                   host + plan->plane_base[p] + (uint64_t)u.xfer_row * row,
+                                   (uint64_t)u.n_rows * row, hipMemcpyHostToDevice, (hipStream_t)stream));
+            ++copies;
+        }
+    }
+    if (n_copies) *n_copies = copies;
+    return KVL_OK;
+}
+
 int kvl_measure_h2d_peak(const void *pinned_host, void *dev, uint64_t bytes, uint32_t reps,
                          void *stream, double *gbps) {
     if (!pinned_host || !dev || !gbps || bytes == 0 || reps == 0) return KVL_EINVAL;

@@ -251,6 +251,30 @@ def test_h2d_unpack(name, make, chunk_kb, slots):
         assert same_bytes(to_host(a), b)
 
 
+@pytest.mark.parametrize("name,make", [CASES[1], CASES[3], CASES[7]], ids=[CASES[i][0] for i in (1, 3, 7)])
+def test_h2d_zero_copy_and_blockwise(name, make):
+    """Two other ways from the pinned host buffer into the pool: the scatter kernel reading
+    host memory itself, and one copy-engine copy per descriptor."""
+    w = make()
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    n = oracle.payload_bytes(w.hit, rows)
+    x = W.random_payload(w, 3, n)
+    want = W.sentinel_pool(w, "dst")
+    oracle.unpack(bs, rows, w.hit, w.dst.tables, x, want)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    host = pinned_from(x)
+    a = planes_to_dev(W.sentinel_pool(w, "dst"))
+    b = planes_to_dev(W.sentinel_pool(w, "dst"))
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    K.kvl_unpack_layer(s, host, a, stream=st)
+    copies = K.kvl_h2d_blockwise_layer(s, host, b, stream=st)
+    st.synchronize()
+    assert copies == s.n_units * len(rows)
+    for got_a, got_b, ref in zip(a, b, want):
+        assert same_bytes(to_host(got_a), ref) and same_bytes(to_host(got_b), ref)
+
+
 def test_h2d_errors():
     w = W.tiny(211, 3, 16, (32,), 32, 60, allow_zero_hit=False)
     s = dev_plan(w, "dst", K.KVL_SCATTER)
