@@ -35,7 +35,9 @@
  * special cases, permutation algebra across two tables, and a closed-form
  * self-describing fill; for token ranges (below) an independent brute force,
  * the reduction to the prefix case, and the merge identity "hit rows scattered,
- * then tail rows scattered = whole prompt scattered".  A last test plants
+ * then tail rows scattered = whole prompt scattered"; for the Full-Block storage
+ * layout (bottom of this file) NumPy reshapes of its defining sentence, a
+ * per-byte brute force and agreement with the Layer-Block path.  A last test plants
  * mistakes in copies of this file and demands that the pins notice each.  The
  * paper prints no worked example for this path.
  */
@@ -259,4 +261,100 @@ int kvo_unpack(uint32_t bs, uint32_t n_planes, const uint32_t *row_bytes,
         base += T * row;
     }
     return KVO_OK;
+}
+
+/*
+ * Storage layout.  Appendix A.5: a Full Block is a byte tensor
+ * [layer, tokens, bytes], the concatenation of one block's Layer Blocks, and all
+ * traffic with storage uses Full Blocks while the per-layer loads use Layer
+ * Blocks (Section 4.1, "Different Block Layouts").  With several planes a Layer
+ * Block is its planes' spans one after the other, so
+ *
+ *   LB = bs * sum_p row_p               bytes of one Layer Block
+ *   FB = n_layers * LB                  bytes of one Full Block
+ *   byte (l, p, w, j) of a Full Block   at  l*LB + bs*sum_{q<p} row_q + w*row_p + j
+ *
+ * The buffer holds the Full Blocks that the token ranges touch, request after
+ * request, each request's blocks in table order: request r contributes blocks
+ * first_r/bs .. (first_r+count_r-1)/bs (none if count_r = 0).  Loading layer l
+ * from it into a paged pool moves, for every token t = first_r + k of a range,
+ * its row from Full Block f = F_r + (t/bs - first_r/bs), row w = t % bs; storing
+ * is the same assignment the other way.  Bytes of the buffer outside the ranges'
+ * rows of layer l are not touched.
+ */
+uint64_t kvo_fullblock_bytes(uint32_t bs, uint32_t n_layers, uint32_t n_planes,
+                             const uint32_t *row_bytes)
+{
+    uint64_t lb = 0;
+    for (uint32_t p = 0; p < n_planes; ++p) lb += (uint64_t)bs * row_bytes[p];
+    return lb * n_layers;
+}
+
+uint64_t kvo_fullblock_count(uint32_t bs, uint32_t n_req, const uint32_t *first,
+                             const uint32_t *count)
+{
+    uint64_t n = 0;
+    for (uint32_t r = 0; r < n_req; ++r) {
+        if (count[r] == 0) continue;
+        uint64_t t0 = first ? first[r] : 0, t1 = t0 + count[r];
+        n += (t1 - 1) / bs - t0 / bs + 1;
+    }
+    return n;
+}
+
+static int fullblocks_move(int to_pool, uint32_t bs, uint32_t n_layers, uint32_t n_planes,
+                           const uint32_t *row_bytes, uint32_t n_req,
+                           const uint32_t *first, const uint32_t *count,
+                           const int32_t *const *tables, uint32_t layer,
+                           uint8_t *blocks, uint8_t *const *pool_planes)
+{
+    if (!row_bytes || !count || !tables || !blocks || !pool_planes || bs == 0) return KVO_E_ARG;
+    if (layer >= n_layers) return KVO_E_ARG;
+    uint64_t lb = 0;
+    for (uint32_t p = 0; p < n_planes; ++p) lb += (uint64_t)bs * row_bytes[p];
+    uint64_t fb = lb * n_layers;
+    uint64_t plane_off = 0;
+    for (uint32_t p = 0; p < n_planes; ++p) {
+        uint64_t row = row_bytes[p];
+        uint8_t *pool = pool_planes[p];
+        uint64_t f_base = 0;                     /* Full Blocks of the requests before r */
+        for (uint32_t r = 0; r < n_req; ++r) {
+            if (count[r] == 0) continue;
+            uint64_t t0 = first ? first[r] : 0;
+            for (uint64_t k = 0; k < count[r]; ++k) {
+                uint64_t t = t0 + k;
+                uint64_t f = f_base + (t / bs - t0 / bs);
+                uint64_t w = t % bs;
+                uint64_t in_blocks = f * fb + (uint64_t)layer * lb + plane_off + w * row;
+                uint64_t in_pool = ((uint64_t)tables[r][t / bs] * bs + w) * row;
+                for (uint64_t j = 0; j < row; ++j) {
+                    if (to_pool) pool[in_pool + j] = blocks[in_blocks + j];
+                    else blocks[in_blocks + j] = pool[in_pool + j];
+                }
+            }
+            f_base += (t0 + count[r] - 1) / bs - t0 / bs + 1;
+        }
+        plane_off += (uint64_t)bs * row;
+    }
+    return KVO_OK;
+}
+
+int kvo_fullblocks_to_pool(uint32_t bs, uint32_t n_layers, uint32_t n_planes,
+                           const uint32_t *row_bytes, uint32_t n_req,
+                           const uint32_t *first, const uint32_t *count,
+                           const int32_t *const *tables, uint32_t layer,
+                           const uint8_t *blocks, uint8_t *const *pool_planes)
+{
+    return fullblocks_move(1, bs, n_layers, n_planes, row_bytes, n_req, first, count, tables,
+                           layer, (uint8_t *)blocks, pool_planes);
+}
+
+int kvo_pool_to_fullblocks(uint32_t bs, uint32_t n_layers, uint32_t n_planes,
+                           const uint32_t *row_bytes, uint32_t n_req,
+                           const uint32_t *first, const uint32_t *count,
+                           const int32_t *const *tables, uint32_t layer,
+                           const uint8_t *const *pool_planes, uint8_t *blocks)
+{
+    return fullblocks_move(0, bs, n_layers, n_planes, row_bytes, n_req, first, count, tables,
+                           layer, blocks, (uint8_t *const *)pool_planes);
 }

@@ -57,6 +57,16 @@ def _bind(path: str):
                                      C.c_void_p, u8pp, C.c_uint32, C.c_uint32]
     lib.kvo_check_range_scatter.restype = C.c_int
     lib.kvo_check_range_scatter.argtypes = [C.c_uint32, C.c_uint64, C.c_uint32, u32p_n, u32p, i32pp]
+    lib.kvo_fullblock_bytes.restype = C.c_uint64
+    lib.kvo_fullblock_bytes.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, u32p]
+    lib.kvo_fullblock_count.restype = C.c_uint64
+    lib.kvo_fullblock_count.argtypes = [C.c_uint32, C.c_uint32, u32p_n, u32p]
+    for fn in (lib.kvo_fullblocks_to_pool, lib.kvo_pool_to_fullblocks):
+        fn.restype = C.c_int
+    lib.kvo_fullblocks_to_pool.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, u32p, C.c_uint32, u32p_n, u32p,
+                                           i32pp, C.c_uint32, C.c_void_p, u8pp]
+    lib.kvo_pool_to_fullblocks.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, u32p, C.c_uint32, u32p_n, u32p,
+                                           i32pp, C.c_uint32, u8pp, C.c_void_p]
     return lib
 
 
@@ -254,6 +264,52 @@ def check_range_scatter(block_tokens: int, pool_blocks: int, first, count, table
     f, fp = _u32(first) if first is not None else (None, None)
     keep, tp = _tables(tables)
     return int(_load().kvo_check_range_scatter(block_tokens, pool_blocks, c.size, fp, cp, tp))
+
+
+def fullblock_bytes(block_tokens: int, n_layers: int, row_bytes) -> int:
+    rb, rbp = _u32(row_bytes)
+    return int(_load().kvo_fullblock_bytes(block_tokens, n_layers, rb.size, rbp))
+
+
+def fullblock_count(block_tokens: int, first, count) -> int:
+    c, cp = _u32(count)
+    f, fp = _u32(first) if first is not None else (None, None)
+    return int(_load().kvo_fullblock_count(block_tokens, c.size, fp, cp))
+
+
+def fullblocks_to_pool(block_tokens: int, n_layers: int, row_bytes, first, count, tables, layer: int,
+                       blocks: np.ndarray, pool_planes: Sequence[np.ndarray]) -> None:
+    """Load layer `layer` of the ranges' rows from a buffer of Full Blocks into a paged pool."""
+    c, cp = _u32(count)
+    f, fp = _u32(first) if first is not None else (None, None)
+    rb, rbp = _u32(row_bytes)
+    keep, tp = _tables(tables)
+    pp = _planes(pool_planes, writable=True)
+    need = fullblock_count(block_tokens, first, count) * fullblock_bytes(block_tokens, n_layers, rb)
+    if blocks.dtype != np.uint8 or blocks.size < need or not blocks.flags["C_CONTIGUOUS"]:
+        raise ValueError("Full-Block buffer too small or not contiguous uint8")
+    rc = _load().kvo_fullblocks_to_pool(block_tokens, n_layers, rb.size, rbp, c.size, fp, cp, tp, layer,
+                                        blocks.ctypes.data, pp)
+    if rc != OK:
+        raise RuntimeError(f"kvo_fullblocks_to_pool failed: {rc}")
+
+
+def pool_to_fullblocks(block_tokens: int, n_layers: int, row_bytes, first, count, tables, layer: int,
+                       pool_planes: Sequence[np.ndarray], blocks: np.ndarray) -> None:
+    """Store layer `layer` of the ranges' rows from a paged pool into a buffer of Full Blocks."""
+    c, cp = _u32(count)
+    f, fp = _u32(first) if first is not None else (None, None)
+    rb, rbp = _u32(row_bytes)
+    keep, tp = _tables(tables)
+    pp = _planes(pool_planes, writable=False)
+    need = fullblock_count(block_tokens, first, count) * fullblock_bytes(block_tokens, n_layers, rb)
+    if blocks.dtype != np.uint8 or blocks.size < need or not blocks.flags["C_CONTIGUOUS"] \
+            or not blocks.flags["WRITEABLE"]:
+        raise ValueError("Full-Block buffer too small, read-only or not contiguous uint8")
+    rc = _load().kvo_pool_to_fullblocks(block_tokens, n_layers, rb.size, rbp, c.size, fp, cp, tp, layer,
+                                        pp, blocks.ctypes.data)
+    if rc != OK:
+        raise RuntimeError(f"kvo_pool_to_fullblocks failed: {rc}")
 
 
 def stream_layers(block_tokens: int, row_bytes, hit, tables, host_layers: Sequence[np.ndarray],

@@ -308,7 +308,80 @@ def pin_ranges():
     assert oracle.check_range_scatter(4, 3, [0, 4], [4, 3], tabs) == oracle.E_BLOCK
 
 
-PINS = [pin_ranges, pin_brute_force, pin_exhaustive_permutations, pin_round_trip, pin_byte_conservation,
+def pin_full_blocks():
+    """Storage layout (Appendix A.5): a Full Block is the concatenation of a block's Layer
+    Blocks.  Checked against NumPy reshapes of that sentence, a per-byte brute force, the
+    Layer-Block path, and a store/load round trip."""
+    # (1) one plane, whole blocks: the buffer is the array [block, layer, bs*row]
+    rng = np.random.Generator(np.random.PCG64(77))
+    bs, row, L, nblk = 4, 16, 3, 12
+    pools = [rng.integers(0, 256, size=nblk * bs * row, dtype=np.uint8) for _ in range(L)]
+    tabs = [np.array([7, 2, 9], np.int32), np.array([0, 11], np.int32)]
+    count = [3 * bs, 2 * bs]
+    nfb = oracle.fullblock_count(bs, None, count)
+    fb = oracle.fullblock_bytes(bs, L, (row,))
+    assert nfb == 5 and fb == L * bs * row
+    buf = np.full(nfb * fb, 0x77, dtype=np.uint8)
+    for l in range(L):
+        oracle.pool_to_fullblocks(bs, L, (row,), None, count, tabs, l, [pools[l]], buf)
+    flat = np.concatenate(tabs)
+    want = np.stack([np.stack([pools[l].reshape(nblk, bs * row)[flat[f]] for l in range(L)]) for f in range(nfb)])
+    assert buf.tobytes() == want.tobytes()
+    # and layer l of that buffer, taken block by block, is exactly the dense transfer buffer of layer l
+    for l in range(L):
+        dense = buf.reshape(nfb, L, bs * row)[:, l, :].reshape(-1)
+        assert dense.tobytes() == oracle.pack(bs, (row,), count, tabs, [pools[l]]).tobytes()
+        a = np.zeros(nblk * bs * row, np.uint8)
+        b = np.zeros(nblk * bs * row, np.uint8)
+        oracle.fullblocks_to_pool(bs, L, (row,), None, count, tabs, l, buf, [a])
+        oracle.unpack(bs, (row,), count, tabs, dense, [b])
+        assert a.tobytes() == b.tobytes()
+    # (2) ragged ranges, several planes: per-byte brute force, sentinel outside the ranges
+    for kw in TINY:
+        w = W.tiny(**dict(kw, n_layers=3))
+        bs, rows, L = w.layout.block_tokens, w.layout.row_bytes, 3
+        for first, count in ((np.zeros_like(w.hit), w.hit), (w.hit, w.app), (np.zeros_like(w.hit), w.hit + w.app)):
+            nfb = oracle.fullblock_count(bs, first, count)
+            fb = oracle.fullblock_bytes(bs, L, rows)
+            lb = fb // L
+            assert lb == bs * sum(rows)
+            pools = [W.fill_pool(w, l, "src") for l in range(L)]
+            buf = np.full(nfb * fb + 8, 0x5A, dtype=np.uint8)
+            for l in range(L):
+                oracle.pool_to_fullblocks(bs, L, rows, first, count, w.src.tables, l, pools[l], buf)
+            ref = np.full(nfb * fb + 8, 0x5A, dtype=np.uint8)
+            f = 0
+            for r in range(len(count)):
+                if int(count[r]) == 0:
+                    continue
+                b0, b1 = int(first[r]) // bs, (int(first[r]) + int(count[r]) - 1) // bs
+                for b in range(b0, b1 + 1):
+                    for wi in range(bs):
+                        t = b * bs + wi
+                        if not (int(first[r]) <= t < int(first[r]) + int(count[r])):
+                            continue
+                        for l in range(L):
+                            po = 0
+                            for p, row in enumerate(rows):
+                                src_off = (int(w.src.tables[r][b]) * bs + wi) * row
+                                dst_off = f * fb + l * lb + po + wi * row
+                                ref[dst_off:dst_off + row] = pools[l][p][src_off:src_off + row]
+                                po += bs * row
+                    f += 1
+            assert f == nfb
+            assert buf.tobytes() == ref.tobytes(), kw
+            # (3) load it back into other tables: equals the Layer-Block scatter of the same rows
+            for l in range(L):
+                got = W.sentinel_pool(w, "dst")
+                oracle.fullblocks_to_pool(bs, L, rows, first, count, w.dst.tables, l, buf, got)
+                x = oracle.pack_range(bs, rows, first, count, w.src.tables, pools[l])
+                exp = W.sentinel_pool(w, "dst")
+                oracle.unpack_range(bs, rows, first, count, w.dst.tables, x, exp)
+                for u, v in zip(got, exp):
+                    assert u.tobytes() == v.tobytes(), kw
+
+
+PINS = [pin_full_blocks, pin_ranges, pin_brute_force, pin_exhaustive_permutations, pin_round_trip, pin_byte_conservation,
         pin_memcpy_and_take, pin_permutation_algebra, pin_closed_form_fill, pin_threads_agree]
 
 
@@ -397,6 +470,12 @@ MUTANTS = [
     ("range: plane base from the wrong total", r"uint64_t T = sum_u32\(n_req, count\);",
      "uint64_t T = sum_u32(n_req, first ? first : count);"),
     ("range: loop one short", r"k < count\[r\]; \+\+k", "k + 1 < count[r]; ++k"),
+    ("full block: layer stride is the full block", r"\(uint64_t\)layer \* lb \+ plane_off", "(uint64_t)layer * fb + plane_off"),
+    ("full block: plane offset forgets block size", r"plane_off \+= \(uint64_t\)bs \* row;", "plane_off += row;"),
+    ("full block: block index not rebased", r"f_base \+ \(t / bs - t0 / bs\)", "f_base + t / bs"),
+    ("full block: request base counts tokens", r"f_base \+= \(t0 \+ count\[r\] - 1\) / bs - t0 / bs \+ 1;", "f_base += (count[r] + bs - 1) / bs;"),
+    ("full block: row in block dropped", r"plane_off \+ w \* row;", "plane_off + k * row;"),
+    ("full block: size counts one plane", r"lb \+= \(uint64_t\)bs \* row_bytes\[p\];\n    return", "lb = (uint64_t)bs * row_bytes[p];\n    return"),
 ]
 
 
