@@ -412,7 +412,11 @@ def host_link_legs(args) -> dict:
 
     st = K.kvl_stream_layers(plan, host, slots, staging, chunk, w.notes["compute_us"], cs, ks, ms, n_layers=L)
     plan.destroy()
+    del slots, staging
+    torch.cuda.empty_cache()
+    fullblocks = full_block_leg(host[0], peak)
     return {
+        "full_blocks": fullblocks,
         "workload": "cfg5 streamed MLA: 61 layers x 1152 B rows, 128 req, pinned host buffer -> paged HBM, "
                     "200 us synthetic compute per layer",
         "h2d_peak_gbps": round(peak, 2), "chunk_bytes": chunk, "staging_slots": 4,
@@ -422,6 +426,50 @@ def host_link_legs(args) -> dict:
         "stream_exposed_ms": round(st["exposed_ms"], 2),
         "payload_bytes_per_layer": payload,
     }
+
+
+def full_block_leg(pinned: "torch.Tensor", h2d_peak: float) -> dict:
+    """Storage layout: 61-layer Full Blocks in pinned host memory (4 requests of the MLA
+    workload); every layer loaded into a paged pool, and stored back, by one kernel per layer
+    that converts the layout while it crosses the host link."""
+    import torch
+    import kvl_workloads as W
+    import paper_2602_21548_amd as K
+    dev = torch.device("cuda:0")
+    w = W.config(3, n_requests=4)
+    L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
+    s = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables,
+                   K.KVL_SCATTER | K.KVL_GATHER | K.KVL_NO_MERGE)
+    fb, nfb = s.fullblock_geometry()
+    need = fb * nfb
+    while need > pinned.numel():                       # fit the pinned buffer the caller already has
+        w = W.config(3, n_requests=w.n_requests - 1)
+        s.destroy()
+        s = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables,
+                       K.KVL_SCATTER | K.KVL_GATHER | K.KVL_NO_MERGE)
+        fb, nfb = s.fullblock_geometry()
+        need = fb * nfb
+    buf = pinned[:need]
+    pool = [torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device=dev) for r in rows]
+    st = torch.cuda.Stream()
+    per_layer = s.payload_bytes
+    out = {"workload": f"{w.n_requests} requests of cfg3, {nfb} Full Blocks of {fb} bytes ({L} layers x {bs} x {rows[0]} B)",
+           "bytes_per_layer": per_layer}
+    for name, fn in (("h2d", lambda l: K.kvl_fullblocks_to_pool_layer(s, buf, l, pool, stream=st)),
+                     ("d2h", lambda l: K.kvl_pool_to_fullblocks_layer(s, pool, l, buf, stream=st))):
+        best = 0.0
+        for rep in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            for l in range(L):
+                fn(l)
+            e1.record(st)
+            e1.synchronize()
+            best = max(best, per_layer * L / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        out[f"{name}_gbps"] = round(best, 2)
+    out["h2d_frac_of_link"] = round(out["h2d_gbps"] / h2d_peak, 4)
+    s.destroy()
+    return out
 
 
 if __name__ == "__main__":

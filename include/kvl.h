@@ -109,7 +109,7 @@ typedef struct {
     uint32_t pool_row;
     uint32_t xfer_row;
     uint32_t n_rows;
-    uint32_t reserved;
+    uint32_t block_index;   /* block of the first row, counted over the blocks the plan touches, in request order */
 } kvl_unit_t;
 
 /* Optional tuning; a zero field means "library default". */
@@ -190,6 +190,31 @@ int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_byt
 int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
                          void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
                          void *const *pool_planes, void *copy_stream, void *kernel_stream);
+
+/* Storage layout (Section 4.1 "Different Block Layouts", Appendix A.5).  All
+ * traffic with storage uses Full Blocks, byte tensors [layer, tokens, bytes] that
+ * are the concatenation of one block's Layer Blocks; with several planes a Layer
+ * Block is its planes' spans one after the other:
+ *   LB = block_tokens * sum_p row_bytes[p],  FB = n_layers * LB,
+ *   byte (layer l, plane p, row w, j) of a Full Block at
+ *       l*LB + block_tokens * sum_{q<p} row_bytes[q] + w*row_bytes[p] + j.
+ * A Full-Block buffer holds the blocks the plan's token ranges touch, request
+ * after request, each request's blocks in table order (kvl_unit_t::block_index
+ * counts them).  The two calls below move ONE layer's rows between such a buffer
+ * and a paged pool with a single kernel that does the layout conversion on the
+ * fly; the buffer may be device memory or pinned host memory mapped into the
+ * device (then the kernel crosses the host link itself and nothing is staged).
+ * Both need a plan made with KVL_NO_MERGE (descriptors must not span blocks);
+ * KVL_EINVAL otherwise or if layer >= n_layers; KVL_ESPACE if the buffer is
+ * smaller than n_full_blocks * full_block_bytes. */
+int kvl_plan_fullblock_geometry(const kvl_plan_t *plan, uint64_t *full_block_bytes, uint64_t *n_full_blocks);
+/* storage read -> prefill pool, layer by layer (KVL_SCATTER plan) */
+int kvl_fullblocks_to_pool_layer(const kvl_plan_t *plan, const void *full_blocks, uint64_t full_blocks_bytes,
+                                 uint32_t layer, void *const *pool_planes, void *stream);
+/* decode pool -> Full Blocks to persist (KVL_GATHER plan); bytes of the buffer that
+ * belong to other layers or to rows outside the ranges are left as they are */
+int kvl_pool_to_fullblocks_layer(const kvl_plan_t *plan, const void *const *pool_planes, uint32_t layer,
+                                 void *full_blocks, uint64_t full_blocks_bytes, void *stream);
 
 /* The same result with one hipMemcpyAsync per descriptor and plane, straight from
  * the pinned host buffer into the paged pool: no staging, no kernel.  This is the

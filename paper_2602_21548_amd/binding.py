@@ -45,7 +45,7 @@ class kvl_request_t(C.Structure):
 
 class kvl_unit_t(C.Structure):
     _fields_ = [("pool_row", C.c_uint32), ("xfer_row", C.c_uint32), ("n_rows", C.c_uint32),
-                ("reserved", C.c_uint32)]
+                ("block_index", C.c_uint32)]
 
 
 class kvl_tuning_t(C.Structure):
@@ -103,6 +103,11 @@ _SIGNATURES = {
     "kvl_unpack_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_void_p]),
     "kvl_h2d_unpack_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                        C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p]),
+    "kvl_plan_fullblock_geometry": (C.c_int, [_PLAN_P, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
+    "kvl_fullblocks_to_pool_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.c_uint64, C.c_uint32,
+                                               C.POINTER(C.c_void_p), C.c_void_p]),
+    "kvl_pool_to_fullblocks_layer": (C.c_int, [_PLAN_P, C.POINTER(C.c_void_p), C.c_uint32, C.c_void_p,
+                                               C.c_uint64, C.c_void_p]),
     "kvl_h2d_blockwise_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
                                           C.POINTER(C.c_uint64)]),
     "kvl_stream_layers": (C.c_int, [_PLAN_P, C.POINTER(kvl_stream_cfg_t), C.POINTER(kvl_stream_stats_t)]),
@@ -214,7 +219,7 @@ class Plan:
         return int(v.value)
 
     def units(self) -> np.ndarray:
-        """Descriptors as an (n, 4) uint32 array: pool_row, xfer_row, n_rows, reserved."""
+        """Descriptors as an (n, 4) uint32 array: pool_row, xfer_row, n_rows, block_index."""
         n = self.n_units
         out = np.zeros((n, 4), dtype=np.uint32)
         got = C.c_uint64()
@@ -230,6 +235,12 @@ class Plan:
                "kvl_plan_get_chunks")
         return [dict(plane=c.plane, unit_begin=c.unit_begin, unit_end=c.unit_end,
                      host_offset=c.host_offset, bytes=c.bytes) for c in arr[:n.value]]
+
+    def fullblock_geometry(self):
+        """(bytes of one Full Block, Full Blocks a buffer of this plan's ranges holds)."""
+        a, b = C.c_uint64(), C.c_uint64()
+        _check(_lib.kvl_plan_fullblock_geometry(self.handle, C.byref(a), C.byref(b)), "kvl_plan_fullblock_geometry")
+        return int(a.value), int(b.value)
 
     def set_tuning(self, block_threads: int = 0, variant: int = 0) -> None:
         t = kvl_tuning_t(0, block_threads, variant, 0)
@@ -315,6 +326,29 @@ def kvl_h2d_unpack_layer(plan: Plan, pinned_host_xfer: torch.Tensor, dev_staging
     _check(_lib.kvl_h2d_unpack_layer(plan.handle, host, _dev(dev_staging, "staging"), _nbytes(dev_staging),
                                      chunk_bytes, arr, _stream_handle(copy_stream),
                                      _stream_handle(kernel_stream)), "kvl_h2d_unpack_layer")
+
+
+def _dev_or_pinned(t: torch.Tensor, what: str) -> int:
+    if isinstance(t, torch.Tensor) and not t.is_cuda:
+        return _pinned(t, what, 0)
+    return _dev(t, what)
+
+
+def kvl_fullblocks_to_pool_layer(plan: Plan, full_blocks: torch.Tensor, layer: int,
+                                 pool_planes: Sequence[torch.Tensor], stream=None) -> None:
+    """full_blocks: a device tensor or a pinned host tensor holding the plan's Full Blocks."""
+    arr = _plane_ptrs(plan, pool_planes, "kvl_fullblocks_to_pool_layer pool")
+    _check(_lib.kvl_fullblocks_to_pool_layer(plan.handle, _dev_or_pinned(full_blocks, "full_blocks"),
+                                             _nbytes(full_blocks), layer, arr, _stream_handle(stream)),
+           "kvl_fullblocks_to_pool_layer")
+
+
+def kvl_pool_to_fullblocks_layer(plan: Plan, pool_planes: Sequence[torch.Tensor], layer: int,
+                                 full_blocks: torch.Tensor, stream=None) -> None:
+    arr = _plane_ptrs(plan, pool_planes, "kvl_pool_to_fullblocks_layer pool")
+    _check(_lib.kvl_pool_to_fullblocks_layer(plan.handle, arr, layer, _dev_or_pinned(full_blocks, "full_blocks"),
+                                             _nbytes(full_blocks), _stream_handle(stream)),
+           "kvl_pool_to_fullblocks_layer")
 
 
 def kvl_h2d_blockwise_layer(plan: Plan, pinned_host_xfer: torch.Tensor, pool_planes: Sequence[torch.Tensor],

@@ -16,6 +16,7 @@ struct kvl_plan_s {
     uint64_t payload_bytes = 0;                  // all planes
     uint64_t plane_base[KVL_MAX_PLANES] = {};    // byte offset of each plane in the transfer buffer
     uint32_t max_unit_rows = 0;
+    uint64_t blocks_touched = 0;                 // Full Blocks a buffer of this plan's ranges holds
     bool vec16 = false;                          // every row size is a multiple of 16 bytes
     std::vector<kvl_unit_t> units;               // host copy of the descriptors
     kvl_unit_t *d_units = nullptr;               // device copy (absent for KVL_HOST_ONLY)

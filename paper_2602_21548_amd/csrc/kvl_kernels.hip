@@ -193,6 +193,47 @@ __global__ void __launch_bounds__(1024) kvl_bytes_kernel(const CopyArgs a) {
     }
 }
 
+// Storage layout <-> paged pool for one layer.  Same tiling as above; the far
+// side is a buffer of Full Blocks ([layer, tokens, bytes] per block), so a
+// descriptor (which never spans blocks here) lands at
+//   block_index * FB + (layer, plane) offset + row-in-block * row.
+// The buffer may be pinned host memory: then these accesses cross the host link.
+struct FullBlockArgs {
+    const kvl_unit_t *units;
+    uint32_t n_units;
+    uint32_t block_tokens;
+    uint32_t row_elems[KVL_MAX_PLANES];       // 16-byte vectors (VEC) or bytes per row
+    uintptr_t pool[KVL_MAX_PLANES];
+    uintptr_t blocks;                          // base of the Full-Block buffer
+    uint64_t fb_elems;                         // elements per Full Block
+    uint64_t layer_plane_off[KVL_MAX_PLANES];  // element offset of (layer, plane) inside a Full Block
+};
+
+template <bool TO_POOL, bool VEC>
+__global__ void __launch_bounds__(256) kvl_fullblock_kernel(const FullBlockArgs a, uint32_t tiles_per_unit) {
+    const uint32_t u_idx = blockIdx.x / tiles_per_unit;
+    const uint32_t tile = blockIdx.x - u_idx * tiles_per_unit;
+    const kvl_unit_t u = a.units[u_idx];
+    const uint32_t p = blockIdx.y;
+    const uint32_t row = a.row_elems[p];
+    const uint32_t n = u.n_rows * row;
+    const uint32_t i = tile * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t within = u.pool_row % a.block_tokens;
+    const uint64_t in_pool = (uint64_t)u.pool_row * row + i;
+    const uint64_t in_blocks = (uint64_t)u.block_index * a.fb_elems + a.layer_plane_off[p] +
+                               (uint64_t)within * row + i;
+    if (VEC) {
+        if (TO_POOL) store16<3>((gdst_t)a.pool[p] + in_pool, load16<false>((gsrc_t)a.blocks + in_blocks));
+        else store16<0>((gdst_t)a.blocks + in_blocks, load16<true>((gsrc_t)a.pool[p] + in_pool));
+    } else {
+        uint8_t *pool = reinterpret_cast<uint8_t *>(a.pool[p]);
+        uint8_t *blocks = reinterpret_cast<uint8_t *>(a.blocks);
+        if (TO_POOL) pool[in_pool] = blocks[in_blocks];
+        else blocks[in_blocks] = pool[in_pool];
+    }
+}
+
 // Straight copy, one vector per lane: the tiled kernel without descriptors.
 __global__ void __launch_bounds__(256) kvl_linear_kernel(const v4u *src, v4u *dst, uint64_t n) {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -320,9 +361,72 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
     return KVL_OK;
 }
 
+static int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint64_t blocks_bytes,
+                           uint32_t layer, void *const *pool_planes, hipStream_t stream) {
+    if (!plan || !pool_planes) return KVL_EINVAL;
+    if ((plan->flags & KVL_HOST_ONLY) || !(plan->flags & KVL_NO_MERGE)) return KVL_EINVAL;
+    if (!(plan->flags & (to_pool ? KVL_SCATTER : KVL_GATHER))) return KVL_EINVAL;
+    if (layer >= plan->layout.n_layers) return KVL_EINVAL;
+    const uint32_t P = plan->layout.n_planes;
+    const uint64_t bs = plan->layout.block_tokens;
+    uint64_t lb = 0;
+    for (uint32_t p = 0; p < P; ++p) lb += bs * plan->layout.row_bytes[p];
+    const uint64_t fb = lb * plan->layout.n_layers;
+    if (blocks_bytes < plan->blocks_touched * fb) return KVL_ESPACE;
+    if (plan->units.empty()) return KVL_OK;
+    if (!blocks) return KVL_EINVAL;
+    bool vec = plan->vec16 && blocks % 16 == 0;
+    for (uint32_t p = 0; p < P; ++p) {
+        if (!pool_planes[p]) return KVL_EINVAL;
+        vec = vec && reinterpret_cast<uintptr_t>(pool_planes[p]) % 16 == 0;
+    }
+    const uint64_t e = vec ? 16 : 1;          // element size
+    FullBlockArgs a{};
+    a.units = plan->d_units;
+    a.n_units = (uint32_t)plan->units.size();
+    a.block_tokens = plan->layout.block_tokens;
+    a.blocks = blocks;
+    a.fb_elems = fb / e;
+    uint64_t plane_off = 0;
+    uint32_t max_row = 0;
+    for (uint32_t p = 0; p < P; ++p) {
+        a.row_elems[p] = (uint32_t)(plan->layout.row_bytes[p] / e);
+        a.pool[p] = reinterpret_cast<uintptr_t>(pool_planes[p]);
+        a.layer_plane_off[p] = ((uint64_t)layer * lb + plane_off) / e;
+        plane_off += bs * plan->layout.row_bytes[p];
+        max_row = std::max(max_row, a.row_elems[p]);
+    }
+    const uint32_t threads = 256;
+    const uint64_t tpu = ((uint64_t)plan->max_unit_rows * max_row + threads - 1) / threads;
+    const uint64_t wgs = (uint64_t)a.n_units * tpu;
+    if (tpu == 0 || wgs > (uint64_t)INT32_MAX) return KVL_ERANGE;
+    dim3 grid((uint32_t)wgs, P), block(threads);
+    if (to_pool) {
+        if (vec) hipLaunchKernelGGL((kvl_fullblock_kernel<true, true>), grid, block, 0, stream, a, (uint32_t)tpu);
+        else hipLaunchKernelGGL((kvl_fullblock_kernel<true, false>), grid, block, 0, stream, a, (uint32_t)tpu);
+    } else {
+        if (vec) hipLaunchKernelGGL((kvl_fullblock_kernel<false, true>), grid, block, 0, stream, a, (uint32_t)tpu);
+        else hipLaunchKernelGGL((kvl_fullblock_kernel<false, false>), grid, block, 0, stream, a, (uint32_t)tpu);
+    }
+    KVL_HIP(hipGetLastError());
+    return KVL_OK;
+}
+
 }  // namespace kvl
 
 extern "C" {
+
+int kvl_fullblocks_to_pool_layer(const kvl_plan_t *plan, const void *full_blocks, uint64_t full_blocks_bytes,
+                                 uint32_t layer, void *const *pool_planes, void *stream) {
+    return kvl::fullblock_layer(plan, true, reinterpret_cast<uintptr_t>(full_blocks), full_blocks_bytes, layer,
+                                pool_planes, (hipStream_t)stream);
+}
+
+int kvl_pool_to_fullblocks_layer(const kvl_plan_t *plan, const void *const *pool_planes, uint32_t layer,
+                                 void *full_blocks, uint64_t full_blocks_bytes, void *stream) {
+    return kvl::fullblock_layer(plan, false, reinterpret_cast<uintptr_t>(full_blocks), full_blocks_bytes, layer,
+                                const_cast<void *const *>(pool_planes), (hipStream_t)stream);
+}
 
 int kvl_pack_layer(const kvl_plan_t *plan, const void *const *pool_planes, void *xfer,
                    uint64_t xfer_capacity, void *stream) {

@@ -129,6 +129,7 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
         plan->hit_tokens = T;
 
         uint64_t xfer_row = 0;
+        uint64_t block_base = 0;          // touched blocks of the requests before r
         uint32_t longest = 0;
         for (uint32_t r = 0; r < n_req; ++r) {
             const kvl_request_t &q = req[r];
@@ -160,6 +161,7 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
             while (b < b_end) {
                 const uint64_t first = (uint64_t)q.block_table[b];
                 uint64_t pool_row = first * bs + (lo_of(b) - b * bs);
+                uint64_t token = lo_of(b);            // request token of the next piece's first row
                 uint64_t rows = hi_of(b) - lo_of(b);
                 uint64_t e = b + 1;
                 while (merge && e < b_end && hi_of(e - 1) == e * bs &&
@@ -172,15 +174,19 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
                 const uint64_t base = rows / pieces, extra = rows % pieces;
                 for (uint64_t k = 0; k < pieces; ++k) {
                     const uint64_t n = base + (k < extra ? 1 : 0);
-                    kvl_unit_t u{(uint32_t)pool_row, (uint32_t)xfer_row, (uint32_t)n, 0};
+                    kvl_unit_t u{(uint32_t)pool_row, (uint32_t)xfer_row, (uint32_t)n,
+                                 (uint32_t)(block_base + (token / bs - b_first))};
                     plan->units.push_back(u);
                     longest = std::max<uint32_t>(longest, (uint32_t)n);
                     pool_row += n;
                     xfer_row += n;
+                    token += n;
                 }
                 b = e;
             }
+            block_base += b_end - b_first;
         }
+        plan->blocks_touched = block_base;
         if (plan->units.size() > (size_t)INT32_MAX) { delete plan; return KVL_ERANGE; }
         plan->max_unit_rows = longest;
     } catch (const std::bad_alloc &) {
@@ -258,6 +264,16 @@ int kvl_plan_payload_bytes(const kvl_plan_t *plan, uint64_t *bytes) {
 int kvl_plan_hit_tokens(const kvl_plan_t *plan, uint64_t *tokens) {
     if (!plan || !tokens) return KVL_EINVAL;
     *tokens = plan->hit_tokens;
+    return KVL_OK;
+}
+
+int kvl_plan_fullblock_geometry(const kvl_plan_t *plan, uint64_t *full_block_bytes, uint64_t *n_full_blocks) {
+    if (!plan || !full_block_bytes || !n_full_blocks) return KVL_EINVAL;
+    uint64_t lb = 0;
+    for (uint32_t p = 0; p < plan->layout.n_planes; ++p)
+        lb += (uint64_t)plan->layout.block_tokens * plan->layout.row_bytes[p];
+    *full_block_bytes = lb * plan->layout.n_layers;
+    *n_full_blocks = plan->blocks_touched;
     return KVL_OK;
 }
 

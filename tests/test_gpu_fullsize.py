@@ -97,6 +97,51 @@ def test_full_size_token_ranges(idx, flag):
     s.destroy()
 
 
+def test_full_size_full_blocks_from_pinned_host():
+    """Storage layout at its real shape: 61-layer Full Blocks of 64 x 1152 bytes per layer in
+    pinned host memory; every layer loaded into the paged pool by one kernel reading the host
+    buffer, compared with the oracle on two layers in full and on the row heads of all layers."""
+    t0 = time.perf_counter()
+    w = W.config(3, n_requests=3)
+    L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
+    row = rows[0]
+    s = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables,
+                   K.KVL_SCATTER | K.KVL_NO_MERGE)
+    fb, nfb = s.fullblock_geometry()
+    assert fb == L * bs * row
+    host = torch.empty(fb * nfb, dtype=torch.uint8, pin_memory=True)
+    a = host.numpy()
+    rng = np.random.Generator(np.random.PCG64(W.BASE_SEED + 405))
+    tile = rng.integers(0, 256, size=1 << 24, dtype=np.uint8)
+    for pos in range(0, a.size, tile.size):
+        k = min(tile.size, a.size - pos)
+        a[pos:pos + k] = tile[:k]
+    # head of every row of every block and layer: (block, layer, row) -- names where it must land
+    heads = a.reshape(nfb, L, bs, row)[:, :, :, :8].view(np.uint64).reshape(nfb, L, bs)
+    heads[:] = (np.arange(nfb, dtype=np.uint64)[:, None, None] << np.uint64(32)) \
+        | (np.arange(L, dtype=np.uint64)[None, :, None] << np.uint64(16)) | np.arange(bs, dtype=np.uint64)[None, None, :]
+    print(f"[fullblocks] {nfb} Full Blocks x {fb} B = {a.size / 1e9:.2f} GB pinned after {time.perf_counter() - t0:.1f} s", flush=True)
+    pool = [torch.full((w.dst.pool_blocks * bs * row,), 0xA5, dtype=torch.uint8, device="cuda")]
+    st = torch.cuda.Stream()
+    zero = np.zeros_like(w.hit)
+    # 8-byte-row instance of the same definition for the row heads of every layer
+    head_buf = np.ascontiguousarray(a.reshape(nfb, L, bs, row)[:, :, :, :8]).reshape(-1)
+    for l in range(L):
+        torch.cuda.synchronize()
+        K.kvl_fullblocks_to_pool_layer(s, host, l, pool, stream=st)
+        st.synchronize()
+        want_h = [np.full(w.dst.pool_blocks * bs * 8, 0xA5, dtype=np.uint8)]
+        oracle.fullblocks_to_pool(bs, L, (8,), zero, w.hit, w.dst.tables, l, head_buf, want_h)
+        got_h = pool[0].view(-1, row)[:, :8].contiguous()
+        assert same_bytes(to_host(got_h).reshape(-1), want_h[0]), f"layer {l}: rows landed in the wrong place"
+        if l in (0, L - 1):
+            want = [np.full(w.dst.pool_blocks * bs * row, 0xA5, dtype=np.uint8)]
+            oracle.fullblocks_to_pool(bs, L, rows, zero, w.hit, w.dst.tables, l, a, want)
+            assert np.array_equal(to_host(pool[0]), want[0]), f"layer {l} differs from the oracle"
+    print(f"[fullblocks] done after {time.perf_counter() - t0:.1f} s", flush=True)
+    s.destroy()
+
+
 def test_full_size_streamed_layers():
     t0 = time.perf_counter()
     w = W.config(5)

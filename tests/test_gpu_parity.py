@@ -275,6 +275,68 @@ def test_h2d_zero_copy_and_blockwise(name, make):
         assert same_bytes(to_host(got_a), ref) and same_bytes(to_host(got_b), ref)
 
 
+FB_CASES = [CASES[0], CASES[1], CASES[3], CASES[5], CASES[7], CASES[9]]
+
+
+@pytest.mark.parametrize("name,make", FB_CASES, ids=[c[0] for c in FB_CASES])
+@pytest.mark.parametrize("where", ["device", "pinned"])
+@pytest.mark.parametrize("flag", [0, K.KVL_TOKENS_ALL], ids=["hit", "all"])
+def test_full_block_layout(name, make, where, flag):
+    """Decode pool -> Full Blocks (persist), then Full Blocks -> prefill pool (load), layer by
+    layer, against the oracle's storage-layout functions."""
+    w = make()
+    L = 3
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    zero = np.zeros_like(w.hit)
+    first, count = (zero, w.hit) if flag == 0 else (zero, w.hit + w.app)
+    g = K.kvl_plan(K.make_layout(L, bs, rows, w.src.pool_blocks), w.hit, w.app, w.src.tables,
+                   K.KVL_GATHER | K.KVL_NO_MERGE | flag)
+    s = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables,
+                   K.KVL_SCATTER | K.KVL_NO_MERGE | flag, unit_bytes=8192)
+    fb, nfb = g.fullblock_geometry()
+    assert (fb, nfb) == s.fullblock_geometry()
+    nbytes = max(16, fb * nfb)
+    want_buf = np.full(nbytes + 64, 0x5A, dtype=np.uint8)
+    if where == "device":
+        buf = torch.full((nbytes + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+    else:
+        buf = torch.full((nbytes + 64,), 0x5A, dtype=torch.uint8).pin_memory()
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    srcs = []
+    for l in range(L):
+        pools = W.fill_pool(w, l, "src")
+        oracle.pool_to_fullblocks(bs, L, rows, first, count, w.src.tables, l, pools, want_buf)
+        srcs.append(planes_to_dev(pools))
+        torch.cuda.synchronize()
+        K.kvl_pool_to_fullblocks_layer(g, srcs[l], l, buf, stream=st)
+    st.synchronize()
+    got_buf = to_host(buf) if where == "device" else buf.numpy()
+    assert same_bytes(got_buf, want_buf), "Full-Block buffer differs from the oracle"
+    for l in (L - 1, 0):
+        want = W.sentinel_pool(w, "dst")
+        oracle.fullblocks_to_pool(bs, L, rows, first, count, w.dst.tables, l, want_buf, want)
+        got = planes_to_dev(W.sentinel_pool(w, "dst"))
+        torch.cuda.synchronize()
+        K.kvl_fullblocks_to_pool_layer(s, buf, l, got, stream=st)
+        st.synchronize()
+        for a, b in zip(got, want):
+            assert same_bytes(to_host(a), b), f"layer {l} loaded from Full Blocks differs from the oracle"
+    # errors: merged plan, short buffer, layer out of range
+    merged = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables, K.KVL_SCATTER | flag)
+    pool = planes_to_dev(W.sentinel_pool(w, "dst"))
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_fullblocks_to_pool_layer(merged, buf, 0, pool)
+    assert e.value.code == K.KVL_EINVAL
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_fullblocks_to_pool_layer(s, buf, L, pool)
+    assert e.value.code == K.KVL_EINVAL
+    if fb * nfb > 64:
+        with pytest.raises(K.KvlError) as e:
+            K.kvl_fullblocks_to_pool_layer(s, buf[:fb * nfb - 16], 0, pool)
+        assert e.value.code == K.KVL_ESPACE
+
+
 def test_h2d_errors():
     w = W.tiny(211, 3, 16, (32,), 32, 60, allow_zero_hit=False)
     s = dev_plan(w, "dst", K.KVL_SCATTER)

@@ -255,3 +255,47 @@ def test_range_validation_agrees_with_the_oracle(case):
     except K.KvlError as e:
         got = e.code
     assert got == want, case
+
+
+# --------------------------------------------------------------------------
+# storage layout: descriptors carry the Full-Block index
+# --------------------------------------------------------------------------
+
+def replay_to_fullblocks(plan, lay, layer, pools, buf):
+    """What a descriptor means for the storage layout, spelt out with NumPy slices."""
+    bs, rows, L = lay.block_tokens, lay.row_bytes, lay.n_layers
+    fb, nfb = plan.fullblock_geometry()
+    lb = fb // L
+    po = 0
+    for p, row in enumerate(rows):
+        for pool_row, _, n, bi in plan.units():
+            w = int(pool_row) % bs
+            dst = int(bi) * fb + layer * lb + po + w * row
+            src = int(pool_row) * row
+            buf[dst:dst + int(n) * row] = pools[p][src:src + int(n) * row]
+        po += bs * row
+
+
+@pytest.mark.parametrize("name,make", CASES[:4] + CASES[5:6], ids=[c[0] for c in CASES[:4] + CASES[5:6]])
+@pytest.mark.parametrize("flag", [0, K.KVL_TOKENS_APPEND, K.KVL_TOKENS_ALL], ids=["hit", "append", "all"])
+def test_fullblock_descriptors_reproduce_the_oracle(name, make, flag):
+    w = make()
+    L = 3
+    lay = W.Layout(L, w.layout.block_tokens, w.layout.row_bytes)
+    bs, rows = lay.block_tokens, lay.row_bytes
+    first, count = _range_of(w, flag)
+    klay = K.make_layout(L, bs, rows, w.src.pool_blocks)
+    plan = K.kvl_plan(klay, w.hit, w.app, w.src.tables, K.KVL_GATHER | K.KVL_HOST_ONLY | K.KVL_NO_MERGE | flag,
+                      unit_bytes=4096)
+    fb, nfb = plan.fullblock_geometry()
+    assert fb == oracle.fullblock_bytes(bs, L, rows) and nfb == oracle.fullblock_count(bs, first, count)
+    got = np.full(nfb * fb, 0x5A, dtype=np.uint8)
+    want = np.full(nfb * fb, 0x5A, dtype=np.uint8)
+    for l in range(L):
+        pools = W.fill_pool(w, l, "src")
+        replay_to_fullblocks(plan, lay, l, pools, got)
+        oracle.pool_to_fullblocks(bs, L, rows, first, count, w.src.tables, l, pools, want)
+    assert got.tobytes() == want.tobytes()
+    # descriptors of an unmerged plan never span blocks
+    u = plan.units().astype(np.int64)
+    assert np.all(u[:, 0] % bs + u[:, 2] <= bs)
