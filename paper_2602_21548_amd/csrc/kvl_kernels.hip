@@ -10,7 +10,7 @@
 // vectors, so every wavefront load or store covers 1 KiB of contiguous memory.
 //
 // kvl_tuning_t::variant is 0 for the default below, else 1 + code with
-// code = mode | ntl << 2 | sp << 3 | deep << 5:
+// code = mode | ntl << 2 | sp << 3 | deep << 5 | noalign << 6:
 //   mode 0  one workgroup per descriptor, each lane loops over the span
 //   mode 1  one wavefront per descriptor, each lane loops over the span
 //   mode 2  tiled: a descriptor is cut into tiles of blockDim vectors and every
@@ -19,15 +19,20 @@
 //   ntl     non-temporal loads
 //   sp      store cache policy: 0 plain, 1 nt, 2 sc1, 3 sc1 nt
 //   deep    modes 0-1: 8 instead of 4 vectors in flight per lane
+//   noalign modes 2-3: do not line tiles up with the destination's 128-byte lines
+//           (they are lined up by default whenever the rows are not multiples of 128 bytes)
 // Measured on MI355X (5.2 GB of 72 KiB blocks in random order), the tiled form
 // with one vector per lane and 256-lane workgroups is the fastest: it leaves no
 // dependency between a lane's memory operations and lets the hardware fill the
 // memory system with resident wavefronts.  Cache policies, measured with gather
-// and scatter alternating as they do in use: non-temporal loads everywhere; the
-// gather (random reads, sequential writes) stores with sc1 when blocks are
-// multiples of 4 KiB and with nt when they are not (41,984-byte blocks); the
-// scatter (sequential reads, random writes) stores with sc1+nt.  Together the
-// policies are worth 5-15 % over plain loads and stores.
+// and scatter alternating as they do in use: the gather (random reads,
+// sequential writes) runs best with non-temporal loads and sc1 stores; the
+// scatter (sequential reads, random writes) with sc1+nt stores, and with
+// non-temporal loads only if the rows are multiples of 128 bytes (otherwise
+// neighbouring wavefronts share source lines, and a non-temporal load fetches
+// the shared line twice).  Together the policies are worth 5-15 % over plain
+// loads and stores.  With rows that are not multiples of 128 bytes the tiles are
+// also lined up with the destination's cache lines (worth 5-9 % on 656-byte rows).
 #include <algorithm>
 #include <cstdio>
 
@@ -141,40 +146,48 @@ __global__ void __launch_bounds__(1024) kvl_unpack_kernel(const CopyArgs a) {
 // operations: the hardware keeps the memory system busy by the sheer number of
 // resident wavefronts rather than by unrolling.
 template <bool PACK, int VPT, bool NTL, int SP>
-__device__ __forceinline__ void tile_body(const CopyArgs &a, uint32_t tiles_per_unit) {
+__device__ __forceinline__ void tile_body(const CopyArgs &a, uint32_t tiles_per_unit, uint32_t align_dst) {
     const uint32_t u_idx = blockIdx.x / tiles_per_unit;
     const uint32_t tile = blockIdx.x - u_idx * tiles_per_unit;
     const kvl_unit_t u = a.units[a.unit_begin + u_idx];
     const uint32_t p = a.plane_begin + blockIdx.y;
     const uint32_t row = a.row_elems[p];
     const uint32_t n = u.n_rows * row;
-    const uint32_t first = tile * (blockDim.x * VPT);
-    if (first >= n) return;
     const uintptr_t pool = a.pool[p] + (uint64_t)u.pool_row * row * 16u;
     const uintptr_t xfer = a.xfer[p] + (uint64_t)u.xfer_row * row * 16u;
     gsrc_t src = (gsrc_t)(PACK ? pool : xfer);
     gdst_t dst = (gdst_t)(PACK ? xfer : pool);
+    // With rows that are not multiples of 128 bytes a span starts anywhere in a
+    // cache line.  Tiles are then laid from the 128-byte boundary below the
+    // span's first destination byte, so that every wavefront's store covers
+    // whole lines (its load may straddle them, which costs far less): the first
+    // `lead` lanes of the first tile idle.
+    const uint32_t lead = align_dst ? ((uint32_t)((PACK ? xfer : pool) >> 4) & 7u) : 0u;
+    const uint32_t first = tile * (blockDim.x * VPT);
+    if (first >= n + lead) return;
     v4u v[VPT];
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
-        const uint32_t i = first + k * blockDim.x + threadIdx.x;
-        if (i < n) v[k] = load16<NTL>(src + i);
+        const uint32_t pos = first + k * blockDim.x + threadIdx.x;
+        if (pos >= lead && pos - lead < n) v[k] = load16<NTL>(src + (pos - lead));
     }
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
-        const uint32_t i = first + k * blockDim.x + threadIdx.x;
-        if (i < n) store16<SP>(dst + i, v[k]);
+        const uint32_t pos = first + k * blockDim.x + threadIdx.x;
+        if (pos >= lead && pos - lead < n) store16<SP>(dst + (pos - lead), v[k]);
     }
 }
 
 template <int VPT, bool NTL, int SP>
-__global__ void __launch_bounds__(1024) kvl_pack_tile_kernel(const CopyArgs a, uint32_t tiles_per_unit) {
-    tile_body<true, VPT, NTL, SP>(a, tiles_per_unit);
+__global__ void __launch_bounds__(1024) kvl_pack_tile_kernel(const CopyArgs a, uint32_t tiles_per_unit,
+                                                             uint32_t align_dst) {
+    tile_body<true, VPT, NTL, SP>(a, tiles_per_unit, align_dst);
 }
 
 template <int VPT, bool NTL, int SP>
-__global__ void __launch_bounds__(1024) kvl_unpack_tile_kernel(const CopyArgs a, uint32_t tiles_per_unit) {
-    tile_body<false, VPT, NTL, SP>(a, tiles_per_unit);
+__global__ void __launch_bounds__(1024) kvl_unpack_tile_kernel(const CopyArgs a, uint32_t tiles_per_unit,
+                                                               uint32_t align_dst) {
+    tile_body<false, VPT, NTL, SP>(a, tiles_per_unit, align_dst);
 }
 
 // Fallback for row sizes or addresses that are not multiples of 16 bytes: one
@@ -275,25 +288,27 @@ static void launch_span_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const
 }
 
 template <bool PACK, int VPT, bool NTL, int SP>
-static void launch_tile_one(dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu) {
-    if (PACK) hipLaunchKernelGGL((kvl_pack_tile_kernel<VPT, NTL, SP>), g, b, 0, s, a, tpu);
-    else hipLaunchKernelGGL((kvl_unpack_tile_kernel<VPT, NTL, SP>), g, b, 0, s, a, tpu);
+static void launch_tile_one(dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu, uint32_t al) {
+    if (PACK) hipLaunchKernelGGL((kvl_pack_tile_kernel<VPT, NTL, SP>), g, b, 0, s, a, tpu, al);
+    else hipLaunchKernelGGL((kvl_unpack_tile_kernel<VPT, NTL, SP>), g, b, 0, s, a, tpu, al);
 }
 
 template <bool PACK, int VPT, bool NTL>
-static void launch_tile_sp(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu) {
+static void launch_tile_sp(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu,
+                           uint32_t al) {
     switch ((v >> 3) & 3u) {
-        case 0: launch_tile_one<PACK, VPT, NTL, 0>(g, b, s, a, tpu); break;
-        case 1: launch_tile_one<PACK, VPT, NTL, 1>(g, b, s, a, tpu); break;
-        case 2: launch_tile_one<PACK, VPT, NTL, 2>(g, b, s, a, tpu); break;
-        default: launch_tile_one<PACK, VPT, NTL, 3>(g, b, s, a, tpu); break;
+        case 0: launch_tile_one<PACK, VPT, NTL, 0>(g, b, s, a, tpu, al); break;
+        case 1: launch_tile_one<PACK, VPT, NTL, 1>(g, b, s, a, tpu, al); break;
+        case 2: launch_tile_one<PACK, VPT, NTL, 2>(g, b, s, a, tpu, al); break;
+        default: launch_tile_one<PACK, VPT, NTL, 3>(g, b, s, a, tpu, al); break;
     }
 }
 
 template <bool PACK, int VPT>
-static void launch_tile_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu) {
-    if (v & 4u) launch_tile_sp<PACK, VPT, true>(v, g, b, s, a, tpu);
-    else launch_tile_sp<PACK, VPT, false>(v, g, b, s, a, tpu);
+static void launch_tile_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu,
+                                uint32_t al) {
+    if (v & 4u) launch_tile_sp<PACK, VPT, true>(v, g, b, s, a, tpu, al);
+    else launch_tile_sp<PACK, VPT, false>(v, g, b, s, a, tpu, al);
 }
 
 int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_t unit_end,
@@ -322,13 +337,12 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
     uint32_t v;
     if (plan->tuning.variant) {
         v = plan->tuning.variant - 1;
-    } else if (!pack) {
-        v = kDefaultUnpackCode;
     } else {
-        bool blocks_4k = true;
+        bool rows_128 = true;       // every span starts on a 128-byte line of the transfer buffer
         for (uint32_t p = plane_begin; p < plane_end; ++p)
-            blocks_4k = blocks_4k && ((uint64_t)plan->layout.block_tokens * plan->layout.row_bytes[p]) % 4096 == 0;
-        v = blocks_4k ? kDefaultPackCode : kDefaultPackCodeOddBlocks;
+            rows_128 = rows_128 && plan->layout.row_bytes[p] % 128 == 0;
+        if (pack) v = kDefaultPackCode;
+        else v = rows_128 ? kDefaultUnpackCode : kDefaultUnpackCodeOddRows;
     }
     dim3 block(threads);
     if (!vec) {
@@ -340,16 +354,22 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
         uint32_t max_row = 0;
         for (uint32_t p = plane_begin; p < plane_end; ++p) max_row = std::max(max_row, a.row_elems[p]);
         const uint64_t per_tile = (uint64_t)threads * vpt;
-        const uint64_t tpu = ((uint64_t)plan->max_unit_rows * max_row + per_tile - 1) / per_tile;
+        // destination spans start on 128-byte lines by themselves when the rows and the base do
+        bool dst_lines = true;
+        for (uint32_t p = plane_begin; p < plane_end; ++p)
+            dst_lines = dst_lines && plan->layout.row_bytes[p] % 128 == 0 &&
+                        (pack ? a.xfer[p] : a.pool[p]) % 128 == 0;
+        const uint32_t al = (dst_lines || (v & 64u)) ? 0u : 1u;
+        const uint64_t tpu = ((uint64_t)plan->max_unit_rows * max_row + (al ? 7 : 0) + per_tile - 1) / per_tile;
         const uint64_t blocks = (uint64_t)a.n_units * tpu;
         if (tpu == 0 || blocks > (uint64_t)INT32_MAX) return KVL_ERANGE;
         dim3 grid((uint32_t)blocks, plane_end - plane_begin);
         if (pack) {
-            if (vpt == 2) launch_tile_variant<true, 2>(v, grid, block, stream, a, (uint32_t)tpu);
-            else launch_tile_variant<true, 1>(v, grid, block, stream, a, (uint32_t)tpu);
+            if (vpt == 2) launch_tile_variant<true, 2>(v, grid, block, stream, a, (uint32_t)tpu, al);
+            else launch_tile_variant<true, 1>(v, grid, block, stream, a, (uint32_t)tpu, al);
         } else {
-            if (vpt == 2) launch_tile_variant<false, 2>(v, grid, block, stream, a, (uint32_t)tpu);
-            else launch_tile_variant<false, 1>(v, grid, block, stream, a, (uint32_t)tpu);
+            if (vpt == 2) launch_tile_variant<false, 2>(v, grid, block, stream, a, (uint32_t)tpu, al);
+            else launch_tile_variant<false, 1>(v, grid, block, stream, a, (uint32_t)tpu, al);
         }
     } else {
         const uint32_t per_wg = (v & 3u) == 1u ? threads / 64 : 1;
@@ -477,8 +497,8 @@ const char *kvl_variant_name(uint32_t v) {
     v -= 1;
     static const char *modes[4] = {"wg/unit", "wave/unit", "tile x1", "tile x2"};
     static const char *sp[4] = {"", " st:nt", " st:sc1", " st:sc1+nt"};
-    std::snprintf(name, sizeof name, "%s%s%s%s", modes[v & 3u], (v & 4u) ? " ld:nt" : "",
-                  sp[(v >> 3) & 3u], (v & 32u) ? " deep" : "");
+    std::snprintf(name, sizeof name, "%s%s%s%s%s", modes[v & 3u], (v & 4u) ? " ld:nt" : "",
+                  sp[(v >> 3) & 3u], (v & 32u) ? " deep" : "", (v & 64u) ? " noalign" : "");
     return name;
 }
 

@@ -105,7 +105,7 @@ def test_token_ranges(name, make, flag):
     run_range_hop(w, flag, unit_bytes=2048, variant=2)
 
 
-@pytest.mark.parametrize("variant", range(65))
+@pytest.mark.parametrize("variant", range(129))
 @pytest.mark.parametrize("threads", [64, 256, 1024])
 def test_every_variant(variant, threads):
     # units of 5 KiB against 64..1024 threads x 4..8 vectors: full steps, ragged tails and idle lanes
@@ -120,6 +120,25 @@ def test_unit_sizes(unit_bytes):
     run_hop(w, unit_bytes=unit_bytes, variant=2)
     run_hop(w, unit_bytes=unit_bytes, variant=3, block_threads=64)
     run_hop(w, unit_bytes=unit_bytes, variant=4)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_batches(seed):
+    """Random small batches: all table kinds, ragged hits, 1-3 planes, rows that take the vector
+    path with and without line alignment and rows that take the byte path."""
+    rng = np.random.Generator(np.random.PCG64(7000 + seed))
+    bs = int(rng.choice([1, 2, 3, 8, 16, 64]))
+    planes = int(rng.integers(1, 4))
+    rows = tuple(int(rng.choice([5, 16, 36, 48, 656, 1152])) for _ in range(planes))
+    kind = ["random", "fragmented", "contiguous", "runs"][seed % 4]
+    R = int(rng.integers(1, 9))
+    max_tokens = int(rng.integers(1, 40 * bs + 2))
+    pool_blocks = R * (max_tokens // bs + 4) + 3
+    w = W.tiny(7000 + seed, R, bs, rows, pool_blocks, max_tokens, kind=kind)
+    ub = int(rng.choice([0, 700, 5000, 1 << 16]))
+    run_hop(w, unit_bytes=ub)
+    run_range_hop(w, K.KVL_TOKENS_APPEND, unit_bytes=ub)
+    run_range_hop(w, K.KVL_TOKENS_ALL, unit_bytes=ub, block_threads=64)
 
 
 def test_layers_are_independent_pools():

@@ -299,3 +299,31 @@ def test_fullblock_descriptors_reproduce_the_oracle(name, make, flag):
     # descriptors of an unmerged plan never span blocks
     u = plan.units().astype(np.int64)
     assert np.all(u[:, 0] % bs + u[:, 2] <= bs)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_batches_all_ranges(seed):
+    """Random small batches (all table kinds, ragged hits, 1-3 planes, odd rows): descriptors
+    replayed on the host equal the oracle for the hit prefix, the tail and the whole prompt."""
+    rng = np.random.Generator(np.random.PCG64(9000 + seed))
+    bs = int(rng.choice([1, 2, 3, 8, 16, 64]))
+    planes = int(rng.integers(1, 4))
+    rows = tuple(int(rng.choice([5, 16, 36, 48, 656, 1152])) for _ in range(planes))
+    kind = ["random", "fragmented", "contiguous", "runs"][seed % 4]
+    R = int(rng.integers(1, 9))
+    max_tokens = int(rng.integers(1, 6 * bs + 2))
+    pool_blocks = R * (max_tokens // bs + 4) + 3
+    w = W.tiny(9000 + seed, R, bs, rows, pool_blocks, max_tokens, kind=kind)
+    ub = int(rng.choice([0, 64, 700, 5000]))
+    for flag in (0, K.KVL_TOKENS_APPEND, K.KVL_TOKENS_ALL):
+        first, count = _range_of(w, flag)
+        g = host_plan(w, "src", K.KVL_GATHER | flag, unit_bytes=ub)
+        src = W.fill_pool(w, 0, "src")
+        want = oracle.pack_range(bs, rows, first, count, w.src.tables, src)
+        assert replay_pack(g, rows, src).tobytes() == want.tobytes()
+        s = host_plan(w, "dst", K.KVL_SCATTER | flag, unit_bytes=ub)
+        got, ref = W.sentinel_pool(w, "dst"), W.sentinel_pool(w, "dst")
+        replay_unpack(s, rows, want, got)
+        oracle.unpack_range(bs, rows, first, count, w.dst.tables, want, ref)
+        for a, b in zip(got, ref):
+            assert a.tobytes() == b.tobytes()
