@@ -104,9 +104,13 @@ def main() -> int:
     ap.add_argument("--skip-other-configs", action="store_true", help="leave out the short runs of the other workloads")
     ap.add_argument("--stream-layers", type=int, default=0, help="layers of the streamed leg (0: all 61)")
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests in the CPU sample (0: the whole batch)")
+    ap.add_argument("--only-steps", action="store_true",
+                    help="time the steps only: no tail-return, other-config, host-link or CPU legs (for profiler runs)")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also launch one plain copy kernel of this size (a known-traffic reference for counter runs)")
     args = ap.parse_args()
+    if args.only_steps:
+        args.skip_host_link = args.skip_cpu = args.skip_other_configs = True
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 "
               "(the load path shards by request across GPUs without any collective)", file=sys.stderr)
@@ -198,7 +202,7 @@ def main() -> int:
     last_slot = (L - 1) % WIN              # the transfer buffer and this slot hold the last layer
     verified = verify_tags(w, src[last_slot], dst[last_slot], xfer, T)
 
-    ceiling = copy_ceiling(stream)
+    ceiling = copy_ceiling(stream, args.calibration_copy_gib or 4.0)
 
     def roof(name, ms):
         avg = float(ms.mean())
@@ -210,7 +214,7 @@ def main() -> int:
                 "algorithmic_bytes_per_launch": 2 * payload, "avg_launch_ms": round(avg, 4),
                 "min_launch_ms": round(float(ms.min()), 4), "launches": int(ms.size)}
 
-    tail = tail_return_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN)
+    tail = None if args.only_steps else tail_return_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN)
 
     roof_pack = roof("kvl_pack_tile_kernel", pack_ms)
     roof_unpack = roof("kvl_unpack_tile_kernel", unpack_ms)
@@ -302,12 +306,12 @@ def tail_return_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN) -> dict:
             "payload_gbps": round(n / (per_layer * 1e-3) / 1e9, 1) if n else 0.0}
 
 
-def copy_ceiling(stream) -> float:
+def copy_ceiling(stream, gib: float = 4.0) -> float:
     """Traffic rate (GB/s, read + write) of a plain 4 GiB device-to-device copy with the
     pack kernel's instruction mix: what a gather with perfect locality could reach here."""
     import torch
     import paper_2602_21548_amd as K
-    n = 4 << 30
+    n = int(gib * (1 << 30)) // 16 * 16
     a = torch.full((n,), 1, dtype=torch.uint8, device="cuda")
     b = torch.empty_like(a)
     best = 0.0
