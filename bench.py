@@ -106,6 +106,8 @@ def main() -> int:
     ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests in the CPU sample (0: the whole batch)")
     ap.add_argument("--only-steps", action="store_true",
                     help="time the steps only: no tail-return, other-config, host-link or CPU legs (for profiler runs)")
+    ap.add_argument("--only-host-link", action="store_true",
+                    help="run the pinned-host legs only and print their object (for profiler runs)")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also launch one plain copy kernel of this size (a known-traffic reference for counter runs)")
     args = ap.parse_args()
@@ -125,6 +127,9 @@ def main() -> int:
         return 3
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.only_host_link:
+        print(json.dumps({"host_link": host_link_legs(args)}), flush=True)
+        return 0
 
     w = W.config(args.config)
     L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
