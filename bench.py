@@ -249,6 +249,8 @@ def main() -> int:
         out["other_configs"] = {f"cfg{i}": short_hop(i) for i in sorted(WORKLOADS) if i != args.config}
     if not args.skip_host_link:
         out["host_link"] = host_link_legs(args)
+    if not args.only_steps:
+        out["scheduler"] = scheduler_leg()
     if not args.skip_cpu:
         log("[bench] timing the CPU oracle on a sample ...")
         out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_sample_requests)
@@ -309,6 +311,35 @@ def tail_return_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN) -> dict:
     return {"what": "appended-tail return hop (pack + unpack per layer), same workload",
             "tokens": T, "payload_bytes_per_layer": n, "us_per_layer": round(per_layer * 1e3, 2),
             "payload_gbps": round(n / (per_layer * 1e-3) / 1e9, 1) if n else 0.0}
+
+
+def scheduler_leg() -> dict:
+    """Host cost of the request scheduling rules (Section 6.1): one prefill fetch and one decode
+    fetch over 8 engines and a queue of 1024 requests with lengths like Table 2's 64K traces."""
+    from paper_2602_21548_amd import sched as S
+    from oracle import sched_oracle as O
+    rng = np.random.Generator(np.random.PCG64(20260221 + 400))
+    Q = np.maximum(1024, rng.normal(32721 + 429, 8000, size=1024)).astype(np.uint64)
+    tok = rng.integers(0, 400_000, size=8).astype(np.uint64)
+    read_q = rng.integers(0, 300_000, size=8).astype(np.uint64)
+    seq = rng.integers(0, 32, size=8).astype(np.uint64)
+    free = np.full(8, 6_000_000, dtype=np.uint64)
+    alpha, beta = 150_000, 100_000_000
+    reps = 50
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        a, _t = S.kvl_sched_pe_fetch(tok, read_q, Q, alpha, beta)
+        d = S.kvl_sched_de_fetch(tok, seq, free, Q)[0]
+    lib_us = (time.perf_counter() - t0) / reps / (2 * Q.size) * 1e6
+    t0 = time.perf_counter()
+    oa = O.pe_fetch(tok.tolist(), read_q.tolist(), Q.tolist(), alpha, beta)
+    od = O.de_fetch(tok.tolist(), seq.tolist(), free.tolist(), Q.tolist())[0]
+    ora_us = (time.perf_counter() - t0) / (2 * Q.size) * 1e6
+    if a != oa or d != od:
+        raise SystemExit("bench: scheduler decisions differ from the oracle")
+    return {"what": "Algorithm 1 prefill fetch + decode phase-2 fetch, 8 engines, 1024 queued requests",
+            "library_us_per_decision": round(lib_us, 3), "oracle_us_per_decision": round(ora_us, 3),
+            "decisions_match_oracle": True}
 
 
 def copy_ceiling(stream, gib: float = 4.0) -> float:

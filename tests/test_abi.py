@@ -6,8 +6,8 @@ import re
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "kvl.h")).read()
+def declared_functions(header="kvl.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)            # drop comments
     names = re.findall(r"^\s*(?:const\s+)?[A-Za-z_][\w\s]*?[\s\*]+(kvl_\w+)\s*\(", text, flags=re.M)
     return sorted(set(n for n in names if not n.endswith("_fn")))
@@ -28,6 +28,10 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), f"{name} declared in kvl.h but not exported"
     # and the binding wraps exactly the declared set
     assert sorted(B._SIGNATURES) == declared_functions()
+    from paper_2602_21548_amd import sched
+    for name in declared_functions("kvl_sched.h"):
+        assert hasattr(lib, name), f"{name} declared in kvl_sched.h but not exported"
+    assert sorted(sched.SIGNATURES) == declared_functions("kvl_sched.h")
 
 
 def test_strerror_and_versions():
