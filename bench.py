@@ -508,6 +508,12 @@ def full_block_leg(pinned: "torch.Tensor", h2d_peak: float) -> dict:
             best = max(best, per_layer * L / (e0.elapsed_time(e1) * 1e-3) / 1e9)
         out[f"{name}_gbps"] = round(best, 2)
     out["h2d_frac_of_link"] = round(out["h2d_gbps"] / h2d_peak, 4)
+    # the streamed load with the storage layout as its source: 61 layers under 200 us of compute each
+    slots = [pool, [torch.full_like(p, 0xA5) for p in pool]]
+    cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    stt = K.kvl_stream_layers(s, None, slots, None, 0, 200, cs, ks, ms, n_layers=L, full_blocks=buf)
+    out["stream_from_full_blocks_gbps"] = round(stt["link_gbps"], 2)
+    out["stream_from_full_blocks_ms"] = round(stt["total_ms"], 2)
     s.destroy()
     return out
 

@@ -44,7 +44,8 @@
  * array and a few events).  Stream arguments are hipStream_t passed as void*;
  * NULL means the default stream.  pack/unpack/h2d_unpack only enqueue work and
  * return; results are ready when the stream reaches that point.
- * A plan may be used by one thread at a time.
+ * A plan may be used by one thread at a time, and only while the device it was
+ * made on is the current one (KVL_EINVAL otherwise).
  */
 #ifndef KVL_H
 #define KVL_H
@@ -132,6 +133,8 @@ int kvl_plan(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t
              uint32_t flags, kvl_plan_t **out);
 int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t n_req,
                    uint32_t flags, const kvl_tuning_t *tuning, kvl_plan_t **out);
+/* Frees the plan and its device descriptors.  Work enqueued with the plan must
+ * have finished (synchronise the streams first). */
 void kvl_plan_destroy(kvl_plan_t *plan);
 
 /* Change launch tuning (block_threads, variant) of an existing plan;
@@ -258,6 +261,14 @@ typedef struct {
     void *copy_stream;                 /* three distinct non-default streams recommended */
     void *kernel_stream;
     void *compute_stream;
+    /* Optional storage-layout source.  When full_blocks is not NULL the layers are
+     * loaded from a buffer of the plan's Full Blocks (device memory, or pinned host
+     * memory mapped into the device) as kvl_fullblocks_to_pool_layer does: layer l
+     * by one converting kernel on kernel_stream.  host_layers, the staging area,
+     * chunk_bytes, copy_stream and host_fill are then unused.  Needs a plan made
+     * with KVL_NO_MERGE. */
+    const void *full_blocks;
+    uint64_t full_blocks_bytes;
 } kvl_stream_cfg_t;
 
 typedef struct {

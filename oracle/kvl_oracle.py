@@ -327,3 +327,15 @@ def stream_layers(block_tokens: int, row_bytes, hit, tables, host_layers: Sequen
         s = l % S
         unpack(block_tokens, row_bytes, hit, tables, host_layers[l % H], dev_slots[s])
         yield l, s, dev_slots[s]
+
+
+def stream_layers_fullblocks(block_tokens: int, n_layers: int, row_bytes, first, count, tables,
+                             blocks: np.ndarray, dev_slots: Sequence[Sequence[np.ndarray]], run_layers: int = 0
+                             ) -> Iterator[Tuple[int, int, Sequence[np.ndarray]]]:
+    """The same layer-wise load with the storage layout as its source: layer l is taken
+    from layer l of a buffer of Full Blocks into destination slot l mod S."""
+    S = len(dev_slots)
+    for l in range(run_layers or n_layers):
+        s = l % S
+        fullblocks_to_pool(block_tokens, n_layers, row_bytes, first, count, tables, l, blocks, dev_slots[s])
+        yield l, s, dev_slots[s]

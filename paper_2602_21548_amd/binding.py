@@ -75,7 +75,8 @@ class kvl_stream_cfg_t(C.Structure):
                 ("probes", C.POINTER(kvl_probe_t)), ("probe_out", C.c_void_p),
                 ("snapshot_planes", C.POINTER(C.c_void_p)),
                 ("host_fill", HOST_FILL_FN), ("host_fill_user", C.c_void_p),
-                ("copy_stream", C.c_void_p), ("kernel_stream", C.c_void_p), ("compute_stream", C.c_void_p)]
+                ("copy_stream", C.c_void_p), ("kernel_stream", C.c_void_p), ("compute_stream", C.c_void_p),
+                ("full_blocks", C.c_void_p), ("full_blocks_bytes", C.c_uint64)]
 
 
 class kvl_stream_stats_t(C.Structure):
@@ -368,19 +369,26 @@ def kvl_stream_layers(plan: Plan, host_layers: Sequence[torch.Tensor],
                       n_layers: int = 0, probes: Optional[Sequence[tuple]] = None,
                       probe_out: Optional[torch.Tensor] = None,
                       snapshots: Optional[Sequence[Sequence[torch.Tensor]]] = None,
-                      host_fill=None, per_layer_times: bool = False) -> dict:
+                      host_fill=None, per_layer_times: bool = False,
+                      full_blocks: Optional[torch.Tensor] = None) -> dict:
     """kvl_stream_layers; returns the stats as a dict.  host_fill(layer, slot_index) is an
-    optional Python callable run where the storage read of that layer would deliver."""
+    optional Python callable run where the storage read of that layer would deliver.
+    With full_blocks (device or pinned host tensor) the layers are loaded from the storage
+    layout instead; host_layers, dev_staging and chunk_bytes may then be None / 0."""
     L = n_layers or int(plan.layout.n_layers)
     P = plan.n_planes
     cfg = kvl_stream_cfg_t()
     cfg.n_layers = L
     need = plan.payload_bytes
+    host_layers = host_layers or []
     H = len(host_layers)
     hl = (C.c_void_p * max(1, H))()
     for i, t in enumerate(host_layers):
         hl[i] = _pinned(t, f"host_layers[{i}]", need)
     cfg.n_host_slots, cfg.host_layers = H, hl
+    if full_blocks is not None:
+        cfg.full_blocks = _dev_or_pinned(full_blocks, "full_blocks")
+        cfg.full_blocks_bytes = _nbytes(full_blocks)
     S = len(dev_slots)
     sp = (C.c_void_p * max(1, S * P))()
     for s, planes in enumerate(dev_slots):
@@ -388,8 +396,10 @@ def kvl_stream_layers(plan: Plan, host_layers: Sequence[torch.Tensor],
         for p in range(P):
             sp[s * P + p] = arr[p]
     cfg.n_dev_slots, cfg.dev_slot_planes = S, sp
-    cfg.dev_staging = _dev(dev_staging, "staging")
-    cfg.staging_bytes, cfg.chunk_bytes, cfg.compute_us = _nbytes(dev_staging), chunk_bytes, compute_us
+    if dev_staging is not None:
+        cfg.dev_staging = _dev(dev_staging, "staging")
+        cfg.staging_bytes = _nbytes(dev_staging)
+    cfg.chunk_bytes, cfg.compute_us = chunk_bytes, compute_us
     keep = []
     if probes:
         pa = (kvl_probe_t * len(probes))()

@@ -64,4 +64,8 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
 
 int ensure_ring_events(kvl_plan_t *plan, size_t slots);
 
+// Enqueue the move of one layer between a buffer of Full Blocks and a paged pool.
+int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint64_t blocks_bytes,
+                    uint32_t layer, void *const *pool_planes, hipStream_t stream);
+
 }  // namespace kvl

@@ -56,6 +56,13 @@ struct CopyArgs {
     uintptr_t xfer[KVL_MAX_PLANES];      // address of transfer row 0 of the plane
 };
 
+// The descriptors live on the device that was current when the plan was made.
+static int check_device(const kvl_plan_t *plan) {
+    int dev = -1;
+    KVL_HIP(hipGetDevice(&dev));
+    return dev == plan->device ? KVL_OK : KVL_EINVAL;
+}
+
 template <bool NT>
 __device__ __forceinline__ v4u load16(gsrc_t p) {
     if (NT) return __builtin_nontemporal_load(p);
@@ -317,6 +324,8 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
     if (unit_end <= unit_begin || plane_end <= plane_begin) return KVL_OK;
     if (!plan->d_units || unit_end > plan->units.size() || plane_end > plan->layout.n_planes)
         return KVL_EINVAL;
+    int rc_dev = check_device(plan);
+    if (rc_dev != KVL_OK) return rc_dev;
     CopyArgs a{};
     a.units = plan->d_units;
     a.unit_begin = unit_begin;
@@ -381,7 +390,7 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
     return KVL_OK;
 }
 
-static int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint64_t blocks_bytes,
+int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint64_t blocks_bytes,
                            uint32_t layer, void *const *pool_planes, hipStream_t stream) {
     if (!plan || !pool_planes) return KVL_EINVAL;
     if ((plan->flags & KVL_HOST_ONLY) || !(plan->flags & KVL_NO_MERGE)) return KVL_EINVAL;
@@ -395,6 +404,8 @@ static int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t block
     if (blocks_bytes < plan->blocks_touched * fb) return KVL_ESPACE;
     if (plan->units.empty()) return KVL_OK;
     if (!blocks) return KVL_EINVAL;
+    int rc_dev = check_device(plan);
+    if (rc_dev != KVL_OK) return rc_dev;
     bool vec = plan->vec16 && blocks % 16 == 0;
     for (uint32_t p = 0; p < P; ++p) {
         if (!pool_planes[p]) return KVL_EINVAL;

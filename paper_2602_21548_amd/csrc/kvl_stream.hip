@@ -75,15 +75,24 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
     if (!plan || !cfg) return KVL_EINVAL;
     const uint32_t L = cfg->n_layers ? cfg->n_layers : plan->layout.n_layers;
     const uint32_t H = cfg->n_host_slots, S = cfg->n_dev_slots, P = plan->layout.n_planes;
-    if (L == 0 || H == 0 || S == 0 || !cfg->host_layers || !cfg->dev_slot_planes) return KVL_EINVAL;
+    const bool from_blocks = cfg->full_blocks != nullptr;
+    if (L == 0 || S == 0 || !cfg->dev_slot_planes) return KVL_EINVAL;
+    if (!from_blocks && (H == 0 || !cfg->host_layers)) return KVL_EINVAL;
     if (cfg->compute_us > 1000000u) return KVL_EINVAL;
     if (cfg->n_probes && (!cfg->probes || !cfg->probe_out)) return KVL_EINVAL;
     size_t slots = 0;
-    int rc = check_h2d_args(plan, cfg->host_layers[0], cfg->dev_staging, cfg->staging_bytes,
+    int rc = KVL_OK;
+    if (from_blocks) {
+        if (!(plan->flags & KVL_SCATTER) || (plan->flags & KVL_HOST_ONLY) || !(plan->flags & KVL_NO_MERGE))
+            return KVL_EINVAL;
+        if (L > plan->layout.n_layers) return KVL_EINVAL;
+    } else {
+        rc = check_h2d_args(plan, cfg->host_layers[0], cfg->dev_staging, cfg->staging_bytes,
                             cfg->chunk_bytes, &slots);
-    if (rc != KVL_OK) return rc;
-    for (uint32_t h = 0; h < H; ++h)
-        if (!cfg->host_layers[h] && !plan->units.empty()) return KVL_EINVAL;
+        if (rc != KVL_OK) return rc;
+        for (uint32_t h = 0; h < H; ++h)
+            if (!cfg->host_layers[h] && !plan->units.empty()) return KVL_EINVAL;
+    }
     for (uint32_t i = 0; i < S * P; ++i)
         if (!cfg->dev_slot_planes[i]) return KVL_EINVAL;
     for (uint32_t i = 0; i < cfg->n_probes; ++i) {
@@ -94,13 +103,15 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
     }
 
     std::vector<kvl_chunk_t> chunks;
-    try {
-        rc = make_chunks(plan, cfg->chunk_bytes, chunks);
-    } catch (const std::bad_alloc &) {
-        return KVL_ENOMEM;
+    if (!from_blocks) {
+        try {
+            rc = make_chunks(plan, cfg->chunk_bytes, chunks);
+        } catch (const std::bad_alloc &) {
+            return KVL_ENOMEM;
+        }
+        if (rc != KVL_OK) return rc;
     }
-    if (rc != KVL_OK) return rc;
-    rc = ensure_ring_events(plan, slots);
+    rc = ensure_ring_events(plan, from_blocks ? 1 : slots);
     if (rc != KVL_OK) return rc;
 
     hipStream_t cs = (hipStream_t)cfg->copy_stream, ks = (hipStream_t)cfg->kernel_stream,
@@ -146,16 +157,23 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
 
     size_t ring_pos = 0;
     for (uint32_t l = 0; l < L; ++l) {
-        const uint32_t h = l % H, s = l % S;
-        void *host_slot = cfg->host_layers[h];
-        if (cfg->host_fill) {
-            if (l >= H) KVL_HIP(hipEventSynchronize(h2d_done[l - H]));
-            if (cfg->host_fill(cfg->host_fill_user, l, host_slot, plan->payload_bytes) != 0)
-                return KVL_EINVAL;
-        }
+        const uint32_t s = l % S;
         void *const *slot_planes = cfg->dev_slot_planes + (size_t)s * P;
-        rc = enqueue_h2d_layer(plan, chunks, host_slot, cfg->dev_staging, cfg->chunk_bytes, slots,
-                               slot_planes, cs, ks, l >= S ? cend[l - S] : nullptr, &ring_pos);
+        if (from_blocks) {
+            // the slot may be overwritten once the compute that read it has finished
+            if (l >= S) KVL_HIP(hipStreamWaitEvent(ks, cend[l - S], 0));
+            rc = fullblock_layer(plan, true, reinterpret_cast<uintptr_t>(cfg->full_blocks),
+                                 cfg->full_blocks_bytes, l, slot_planes, ks);
+        } else {
+            void *host_slot = cfg->host_layers[l % H];
+            if (cfg->host_fill) {
+                if (l >= H) KVL_HIP(hipEventSynchronize(h2d_done[l - H]));
+                if (cfg->host_fill(cfg->host_fill_user, l, host_slot, plan->payload_bytes) != 0)
+                    return KVL_EINVAL;
+            }
+            rc = enqueue_h2d_layer(plan, chunks, host_slot, cfg->dev_staging, cfg->chunk_bytes, slots,
+                                   slot_planes, cs, ks, l >= S ? cend[l - S] : nullptr, &ring_pos);
+        }
         if (rc != KVL_OK) return rc;
         KVL_HIP(hipEventRecord(h2d_done[l], cs));
         KVL_HIP(hipEventRecord(loaded[l], ks));

@@ -52,3 +52,21 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(B.kvl_chunk_t) == 32
     assert ctypes.sizeof(B.kvl_probe_t) == 16
     assert ctypes.sizeof(B.kvl_tuning_t) == 16
+
+
+def test_missing_library_fails_loudly():
+    """No fallback: if the shared library is absent and cannot be built, importing the binding raises."""
+    import subprocess
+    import sys
+    code = (
+        "import sys; sys.path.insert(0, %r)\n"
+        "import paper_2602_21548_amd.build as b\n"
+        "b.LIB = '/nonexistent/dir/libkvl.so'\n"
+        "b.hipcc = lambda: '/nonexistent/hipcc'\n"
+        "try:\n"
+        "    import paper_2602_21548_amd.binding\n"
+        "except Exception as e:\n"
+        "    print('raised', type(e).__name__); sys.exit(7)\n"
+        "sys.exit(0)\n" % ROOT)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True)
+    assert r.returncode == 7, r.stdout + r.stderr

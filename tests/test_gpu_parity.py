@@ -428,3 +428,37 @@ def test_stream_layers_observables(S, H):
     assert np.all(np.diff(tb) > 0)
     assert st["total_ms"] >= L * 0.05
     assert st["h2d_bytes"] == n * L
+
+
+@pytest.mark.parametrize("S", [1, 2])
+@pytest.mark.parametrize("where", ["device", "pinned"])
+def test_stream_layers_from_full_blocks(S, where):
+    """Layer-wise load straight from the storage layout: what each layer's compute sees."""
+    L = 5
+    w = W.tiny(213, 6, 16, (64, 32), 96, 200, n_layers=L)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    zero = np.zeros_like(w.hit)
+    nfb, fb = oracle.fullblock_count(bs, zero, w.hit), oracle.fullblock_bytes(bs, L, rows)
+    blocks = W.random_payload(w, 9, nfb * fb)
+    o_slots = [W.sentinel_pool(w, "dst", 0xEE) for _ in range(S)]
+    want = []
+    for _, _, planes in oracle.stream_layers_fullblocks(bs, L, rows, zero, w.hit, w.dst.tables, blocks, o_slots):
+        want.append([p.copy() for p in planes])
+    s = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables,
+                   K.KVL_SCATTER | K.KVL_NO_MERGE)
+    assert s.fullblock_geometry() == (fb, nfb)
+    buf = to_dev(blocks) if where == "device" else pinned_from(blocks)
+    slots = [planes_to_dev(W.sentinel_pool(w, "dst", 0xEE)) for _ in range(S)]
+    snaps = [[torch.zeros_like(pl) for pl in slots[0]] for _ in range(L)]
+    torch.cuda.synchronize()
+    cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    st = K.kvl_stream_layers(s, None, slots, None, 0, 50, cs, ks, ms, n_layers=L, snapshots=snaps,
+                             per_layer_times=True, full_blocks=buf)
+    for l in range(L):
+        for p in range(len(rows)):
+            assert same_bytes(to_host(snaps[l][p]), want[l][p]), f"layer {l} plane {p}"
+    assert np.all(st["t_compute_begin"] >= st["t_loaded"] - 1e-3)
+    merged = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables, K.KVL_SCATTER)
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_stream_layers(merged, None, slots, None, 0, 50, cs, ks, ms, n_layers=L, full_blocks=buf)
+    assert e.value.code == K.KVL_EINVAL
