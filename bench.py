@@ -217,6 +217,7 @@ def main() -> int:
                 "traffic": measured_traffic(args.config, name),
                 "frac_of_measured_linear_copy": round(achieved / ceiling, 4),
                 "algorithmic_bytes_per_launch": 2 * payload, "avg_launch_ms": round(avg, 4),
+                "median_launch_ms": round(float(np.median(ms)), 4),
                 "min_launch_ms": round(float(ms.min()), 4), "launches": int(ms.size)}
 
     tail = None if args.only_steps else tail_return_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN)
