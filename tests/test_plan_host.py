@@ -327,3 +327,14 @@ def test_random_batches_all_ranges(seed):
         oracle.unpack_range(bs, rows, first, count, w.dst.tables, want, ref)
         for a, b in zip(got, ref):
             assert a.tobytes() == b.tobytes()
+
+
+def test_hip_errors_are_surfaced_not_swallowed():
+    """Without a GPU a device plan must fail with KVL_EHIP and carry the HIP error text."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    lay = K.make_layout(1, 4, (16,), 4)
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_plan(lay, [1], [0], [np.array([0], np.int32)], K.KVL_GATHER)
+    assert e.value.code == K.KVL_EHIP and "hip" in str(e.value).lower()
