@@ -452,6 +452,8 @@ def host_link_legs(args) -> dict:
     h2d_gbps = payload / min(times) / 1e9
 
     st = K.kvl_stream_layers(plan, host, slots, staging, chunk, w.notes["compute_us"], cs, ks, ms, n_layers=L)
+    # the same 61 layers with the zero-copy form (scatter kernel reads the pinned buffers itself)
+    zc = K.kvl_stream_layers(plan, host, slots, None, 0, w.notes["compute_us"], cs, ks, ms, n_layers=L)
     plan.destroy()
     del slots, staging
     torch.cuda.empty_cache()
@@ -465,6 +467,8 @@ def host_link_legs(args) -> dict:
         "stream_layers": L, "stream_total_ms": round(st["total_ms"], 2),
         "stream_gbps": round(st["link_gbps"], 2), "stream_frac_of_link": round(st["link_gbps"] / peak, 4),
         "stream_exposed_ms": round(st["exposed_ms"], 2),
+        "stream_zero_copy_gbps": round(zc["link_gbps"], 2),
+        "stream_zero_copy_frac_of_link": round(zc["link_gbps"] / peak, 4),
         "payload_bytes_per_layer": payload,
     }
 

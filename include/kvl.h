@@ -189,7 +189,10 @@ int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_byt
  * next call at once.  The pool is complete when kernel_stream reaches the end
  * of the enqueued work.  KVL_ESPACE: staging smaller than one chunk, or a
  * chunk smaller than one descriptor.  copy_stream and kernel_stream should
- * differ for the copies to overlap the scatter. */
+ * differ for the copies to overlap the scatter.
+ * chunk_bytes == 0 selects the zero-copy form: no staging, no copies; one scatter
+ * kernel on kernel_stream reads the pinned buffer across the host link itself
+ * (dev_staging, staging_bytes and copy_stream are then unused). */
 int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
                          void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
                          void *const *pool_planes, void *copy_stream, void *kernel_stream);
@@ -247,7 +250,7 @@ typedef struct {
     void *const *host_layers;          /* [H] pinned host transfer buffers */
     uint32_t n_dev_slots;              /* S >= 1 resident destination layers */
     void *const *dev_slot_planes;      /* [S * n_planes] device plane bases, slot-major */
-    void *dev_staging;                 /* as in kvl_h2d_unpack_layer */
+    void *dev_staging;                 /* as in kvl_h2d_unpack_layer; chunk_bytes == 0: zero-copy loads */
     uint64_t staging_bytes;
     uint64_t chunk_bytes;
     uint32_t compute_us;               /* duration of the synthetic per-layer compute kernel */

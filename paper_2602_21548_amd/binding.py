@@ -324,7 +324,9 @@ def kvl_h2d_unpack_layer(plan: Plan, pinned_host_xfer: torch.Tensor, dev_staging
                          copy_stream, kernel_stream) -> None:
     arr = _plane_ptrs(plan, pool_planes, "kvl_h2d_unpack_layer pool")
     host = _pinned(pinned_host_xfer, "pinned_host_xfer", plan.payload_bytes)
-    _check(_lib.kvl_h2d_unpack_layer(plan.handle, host, _dev(dev_staging, "staging"), _nbytes(dev_staging),
+    stage = _dev(dev_staging, "staging") if dev_staging is not None else None
+    stage_bytes = _nbytes(dev_staging) if dev_staging is not None else 0
+    _check(_lib.kvl_h2d_unpack_layer(plan.handle, host, stage, stage_bytes,
                                      chunk_bytes, arr, _stream_handle(copy_stream),
                                      _stream_handle(kernel_stream)), "kvl_h2d_unpack_layer")
 

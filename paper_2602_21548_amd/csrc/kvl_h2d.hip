@@ -47,11 +47,26 @@ int enqueue_h2d_layer(kvl_plan_t *plan, const std::vector<kvl_chunk_t> &chunks,
     return KVL_OK;
 }
 
+// Zero-copy form (chunk_bytes == 0): the scatter kernel reads the pinned buffer itself.
+int enqueue_zero_copy_layer(const kvl_plan_t *plan, const void *host_xfer, void *const *pool_planes,
+                            hipStream_t kern_s, hipEvent_t wait_before_scatter) {
+    if (wait_before_scatter) KVL_HIP(hipStreamWaitEvent(kern_s, wait_before_scatter, 0));
+    uintptr_t xp[KVL_MAX_PLANES];
+    for (uint32_t p = 0; p < plan->layout.n_planes; ++p)
+        xp[p] = reinterpret_cast<uintptr_t>(host_xfer) + plan->plane_base[p];
+    return launch_units(plan, false, 0, (uint32_t)plan->units.size(), 0, plan->layout.n_planes,
+                        pool_planes, xp, kern_s);
+}
+
 int check_h2d_args(const kvl_plan_t *plan, const void *host, const void *staging,
                    uint64_t staging_bytes, uint64_t chunk_bytes, size_t *slots) {
     if (!plan) return KVL_EINVAL;
     if (!(plan->flags & KVL_SCATTER) || (plan->flags & KVL_HOST_ONLY)) return KVL_EINVAL;
-    if (chunk_bytes == 0 || chunk_bytes % 16) return KVL_EINVAL;
+    if (chunk_bytes == 0) {                 // zero copy: no staging area is needed
+        *slots = 0;
+        return (!plan->units.empty() && !host) ? KVL_EINVAL : KVL_OK;
+    }
+    if (chunk_bytes % 16) return KVL_EINVAL;
     if (staging_bytes < chunk_bytes) return KVL_ESPACE;
     if (!plan->units.empty() && (!host || !staging)) return KVL_EINVAL;
     if (reinterpret_cast<uintptr_t>(staging) % 16) return KVL_EINVAL;
@@ -72,6 +87,8 @@ int kvl_h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xfer,
     if (rc != KVL_OK) return rc;
     if (!pool_planes) return KVL_EINVAL;
     if (plan->units.empty()) return KVL_OK;
+    if (chunk_bytes == 0)
+        return kvl::enqueue_zero_copy_layer(plan, pinned_host_xfer, pool_planes, (hipStream_t)kernel_stream, nullptr);
     std::vector<kvl_chunk_t> chunks;
     try {
         rc = kvl::make_chunks(plan, chunk_bytes, chunks);

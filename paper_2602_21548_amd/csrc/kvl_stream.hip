@@ -23,6 +23,8 @@ int enqueue_h2d_layer(kvl_plan_t *plan, const std::vector<kvl_chunk_t> &chunks,
                       hipEvent_t wait_before_scatter, size_t *ring_pos);
 int check_h2d_args(const kvl_plan_t *plan, const void *host, const void *staging,
                    uint64_t staging_bytes, uint64_t chunk_bytes, size_t *slots);
+int enqueue_zero_copy_layer(const kvl_plan_t *plan, const void *host_xfer, void *const *pool_planes,
+                            hipStream_t kern_s, hipEvent_t wait_before_scatter);
 
 struct SlotPlanes {
     uintptr_t base[KVL_MAX_PLANES];
@@ -103,7 +105,8 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
     }
 
     std::vector<kvl_chunk_t> chunks;
-    if (!from_blocks) {
+    const bool zero_copy = !from_blocks && cfg->chunk_bytes == 0;
+    if (!from_blocks && !zero_copy) {
         try {
             rc = make_chunks(plan, cfg->chunk_bytes, chunks);
         } catch (const std::bad_alloc &) {
@@ -111,7 +114,7 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
         }
         if (rc != KVL_OK) return rc;
     }
-    rc = ensure_ring_events(plan, from_blocks ? 1 : slots);
+    rc = ensure_ring_events(plan, slots ? slots : 1);
     if (rc != KVL_OK) return rc;
 
     hipStream_t cs = (hipStream_t)cfg->copy_stream, ks = (hipStream_t)cfg->kernel_stream,
@@ -171,11 +174,19 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
                 if (cfg->host_fill(cfg->host_fill_user, l, host_slot, plan->payload_bytes) != 0)
                     return KVL_EINVAL;
             }
-            rc = enqueue_h2d_layer(plan, chunks, host_slot, cfg->dev_staging, cfg->chunk_bytes, slots,
-                                   slot_planes, cs, ks, l >= S ? cend[l - S] : nullptr, &ring_pos);
+            if (zero_copy) {
+                rc = plan->units.empty() ? KVL_OK
+                                         : enqueue_zero_copy_layer(plan, host_slot, slot_planes, ks,
+                                                                   l >= S ? cend[l - S] : nullptr);
+                // the host slot is free again once this kernel has read it
+                if (rc == KVL_OK) KVL_HIP(hipEventRecord(h2d_done[l], ks));
+            } else {
+                rc = enqueue_h2d_layer(plan, chunks, host_slot, cfg->dev_staging, cfg->chunk_bytes, slots,
+                                       slot_planes, cs, ks, l >= S ? cend[l - S] : nullptr, &ring_pos);
+            }
         }
         if (rc != KVL_OK) return rc;
-        KVL_HIP(hipEventRecord(h2d_done[l], cs));
+        if (!zero_copy) KVL_HIP(hipEventRecord(h2d_done[l], cs));
         KVL_HIP(hipEventRecord(loaded[l], ks));
 
         KVL_HIP(hipStreamWaitEvent(ms, loaded[l], 0));

@@ -239,7 +239,7 @@ def test_copy_linear():
 
 @pytest.mark.parametrize("name,make", [CASES[1], CASES[3], CASES[6], CASES[7], CASES[9]],
                          ids=[CASES[i][0] for i in (1, 3, 6, 7, 9)])
-@pytest.mark.parametrize("chunk_kb,slots", [(64, 1), (64, 3), (1024, 2)])
+@pytest.mark.parametrize("chunk_kb,slots", [(64, 1), (64, 3), (1024, 2), (0, 0)])
 def test_h2d_unpack(name, make, chunk_kb, slots):
     w = make()
     bs, rows = w.layout.block_tokens, w.layout.row_bytes
@@ -250,7 +250,7 @@ def test_h2d_unpack(name, make, chunk_kb, slots):
     s = dev_plan(w, "dst", K.KVL_SCATTER, unit_bytes=16384)
     host = pinned_from(x)
     chunk = chunk_kb * 1024
-    staging = torch.zeros(chunk * slots, dtype=torch.uint8, device="cuda")
+    staging = torch.zeros(chunk * slots, dtype=torch.uint8, device="cuda") if chunk else None   # 0: zero copy
     d_dst = planes_to_dev(W.sentinel_pool(w, "dst"))
     torch.cuda.synchronize()
     cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
@@ -379,7 +379,8 @@ def test_h2d_errors():
 
 @pytest.mark.parametrize("S", [1, 2, 3])
 @pytest.mark.parametrize("H", [1, 2, 6])
-def test_stream_layers_observables(S, H):
+@pytest.mark.parametrize("chunk", [8192, 0], ids=["staged", "zerocopy"])
+def test_stream_layers_observables(S, H, chunk):
     L = 6
     w = W.tiny(212, 6, 16, (64, 32), 96, 200, n_layers=L)
     bs, rows = w.layout.block_tokens, w.layout.row_bytes
@@ -411,7 +412,7 @@ def test_stream_layers_observables(S, H):
 
     torch.cuda.synchronize()
     cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
-    st = K.kvl_stream_layers(s, host, slots, staging, 8192, 50, cs, ks, ms, n_layers=L, probes=probes,
+    st = K.kvl_stream_layers(s, host, slots, staging if chunk else None, chunk, 50, cs, ks, ms, n_layers=L, probes=probes,
                              probe_out=probe_out, snapshots=snaps, host_fill=fill, per_layer_times=True)
     assert filled == [(l, l % H) for l in range(L)]
     for l in range(L):
