@@ -391,8 +391,6 @@ def short_hop(index: int, reps: int = 8) -> dict:
             pk.append(e0.elapsed_time(e1))
             up.append(e1.elapsed_time(e2))
     verified = verify_tags(w, src, dst, xfer, T)
-    g.destroy()
-    s.destroy()
     pm, um = float(np.mean(pk)), float(np.mean(up))
     out = {"workload": WORKLOADS[index], "payload_bytes_per_layer": payload, "hit_tokens": T,
            "pack_ms": round(pm, 4), "unpack_ms": round(um, 4),
@@ -402,6 +400,33 @@ def short_hop(index: int, reps: int = 8) -> dict:
            "tokens_layers_per_s": round(T / ((pm + um) * 1e-3), 1), "verified_rows_vs_oracle": verified}
     if payload < (64 << 20):
         out["note"] = "launch- and cache-bound: the payload fits the on-die cache and a launch costs more than the copy"
+        # in this regime the host's launch cost is what a HIP graph removes: capture a run of
+        # hops (as the layers of one batch would be), replay it
+        HOPS = 16
+
+        def hops():
+            for _ in range(HOPS):
+                K.kvl_pack_layer(g, src, xfer, stream=stream)
+                K.kvl_unpack_layer(s, xfer, dst, stream=stream)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(stream):
+            with torch.cuda.graph(graph, stream=stream):
+                hops()
+            res = {}
+            for name, fn in (("eager", hops), ("graph", graph.replay)):
+                for _ in range(5):
+                    fn()
+                stream.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(50):
+                    fn()
+                stream.synchronize()
+                res[name] = (time.perf_counter() - t0) / (50 * HOPS) * 1e6
+        out["hop_us_eager"], out["hop_us_hip_graph"] = round(res["eager"], 2), round(res["graph"], 2)
+        out["hops_per_graph"] = HOPS
+        del graph
+    g.destroy()
+    s.destroy()
     del src, dst, xfer
     torch.cuda.empty_cache()
     return out

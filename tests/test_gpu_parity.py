@@ -463,3 +463,41 @@ def test_stream_layers_from_full_blocks(S, where):
     with pytest.raises(K.KvlError) as e:
         K.kvl_stream_layers(merged, None, slots, None, 0, 50, cs, ks, ms, n_layers=L, full_blocks=buf)
     assert e.value.code == K.KVL_EINVAL
+
+
+def test_hip_graph_capture_and_replay():
+    """pack and unpack only launch kernels, so a caller may capture them in a HIP graph (the
+    launch-bound regime of small payloads).  Every replay, with fresh inputs and eager work in
+    between, must equal the oracle."""
+    w = W.config(1)
+    L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    n = g.payload_bytes
+    src = [planes_to_dev(W.fill_pool(w, l, "src")) for l in range(L)]
+    dst = [planes_to_dev(W.sentinel_pool(w, "dst")) for l in range(L)]
+    x = [torch.zeros(n, dtype=torch.uint8, device="cuda") for _ in range(L)]
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(graph, stream=st):
+            for l in range(L):
+                K.kvl_pack_layer(g, src[l], x[l], stream=st)
+                K.kvl_unpack_layer(s, x[l], dst[l], stream=st)
+    for rep in range(3):
+        fills = [W.fill_pool(w, 10 * rep + l, "src") for l in range(L)]
+        for l in range(L):
+            src[l][0].copy_(to_dev(fills[l][0]))          # eager work between replays
+            dst[l][0].fill_(0xA5)
+            x[l].zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            graph.replay()
+        st.synchronize()
+        for l in range(L):
+            want_x = oracle.pack(bs, rows, w.hit, w.src.tables, fills[l])
+            want = W.sentinel_pool(w, "dst")
+            oracle.unpack(bs, rows, w.hit, w.dst.tables, want_x, want)
+            assert same_bytes(to_host(x[l]), want_x), f"replay {rep} layer {l}: transfer buffer"
+            assert same_bytes(to_host(dst[l][0]), want[0]), f"replay {rep} layer {l}: pool"
