@@ -70,3 +70,21 @@ def test_missing_library_fails_loudly():
         "sys.exit(0)\n" % ROOT)
     r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True)
     assert r.returncode == 7, r.stdout + r.stderr
+
+
+def test_headers_are_plain_c_and_link_from_c(tmp_path):
+    """include/*.h compile as strict C99 and the library can be driven from a C program (no GPU)."""
+    import subprocess
+    import sysconfig
+    import torch
+    from paper_2602_21548_amd import binding as B
+    exe = str(tmp_path / "c_abi_check")
+    libdir = os.path.dirname(B.LIB_PATH)
+    torch_lib = os.path.join(os.path.dirname(torch.__file__), "lib")
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I" + os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "host_sanitize", "c_abi_check.c"), "-o", exe,
+           "-L" + libdir, "-lkvl", "-Wl,-rpath," + libdir, "-Wl,-rpath," + torch_lib, "-Wl,--allow-shlib-undefined"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0 and "c abi ok" in out.stdout, (out.returncode, out.stdout, out.stderr[-2000:])
