@@ -373,8 +373,10 @@ def short_hop(index: int, reps: int = 8) -> dict:
     L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
     src = [torch.from_numpy(p).to(dev) for p in W.fill_pool_fast(w, 0, "src")]
     dst = [torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device=dev) for r in rows]
+    t0 = time.perf_counter()
     g = K.kvl_plan(K.make_layout(L, bs, rows, w.src.pool_blocks), w.hit, w.app, w.src.tables, K.KVL_GATHER)
     s = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables, K.KVL_SCATTER)
+    plan_ms = (time.perf_counter() - t0) * 1e3 / 2
     payload, T = g.payload_bytes, g.hit_tokens
     xfer = torch.empty(payload, dtype=torch.uint8, device=dev)
     stream = torch.cuda.Stream()
@@ -397,7 +399,8 @@ def short_hop(index: int, reps: int = 8) -> dict:
            "pack_payload_gbps": round(payload / pm / 1e6, 1), "unpack_payload_gbps": round(payload / um / 1e6, 1),
            "pack_frac_of_hbm_peak": round(2 * payload / pm / 1e6 / HBM_PEAK_GBPS, 4),
            "unpack_frac_of_hbm_peak": round(2 * payload / um / 1e6 / HBM_PEAK_GBPS, 4),
-           "tokens_layers_per_s": round(T / ((pm + um) * 1e-3), 1), "verified_rows_vs_oracle": verified}
+           "tokens_layers_per_s": round(T / ((pm + um) * 1e-3), 1), "verified_rows_vs_oracle": verified,
+           "plan_ms": round(plan_ms, 3), "descriptors": g.n_units}
     if payload < (64 << 20):
         out["note"] = "launch- and cache-bound: the payload fits the on-die cache and a launch costs more than the copy"
         # in this regime the host's launch cost is what a HIP graph removes: capture a run of

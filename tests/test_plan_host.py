@@ -338,3 +338,18 @@ def test_hip_errors_are_surfaced_not_swallowed():
     with pytest.raises(K.KvlError) as e:
         K.kvl_plan(lay, [1], [0], [np.array([0], np.int32)], K.KVL_GATHER)
     assert e.value.code == K.KVL_EHIP and "hip" in str(e.value).lower()
+
+
+def test_row_index_limits():
+    """Descriptors index rows with 32 bits: more than 2^32-1 moved tokens is refused, not wrapped."""
+    bs = 1 << 20
+    lay = K.make_layout(1, bs, (16,), 4095)                      # 4095 x 2^20 pool rows: just below 2^32
+    tbl = np.arange(3072, dtype=np.int32)
+    hit = [3 << 30, 3 << 30]                                     # 6 Gi tokens in all
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_plan(lay, hit, [0, 0], [tbl, tbl], K.KVL_GATHER | K.KVL_HOST_ONLY)
+    assert e.value.code == K.KVL_ERANGE
+    p = K.kvl_plan(lay, hit[:1], [0], [tbl], K.KVL_GATHER | K.KVL_HOST_ONLY, unit_bytes=1 << 30)
+    assert p.hit_tokens == 3 << 30 and p.payload_bytes == (3 << 30) * 16
+    u = p.units().astype(np.int64)
+    assert u[:, 2].sum() == 3 << 30 and (u[:, 2] * 16).max() <= 1 << 30      # descriptors stay within 1 GiB
