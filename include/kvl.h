@@ -181,15 +181,17 @@ int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_byt
 
 /* Prefill-engine read path, host buffer -> HBM for one layer (Section 4.1,
  * steps 3-4 of that path): the transfer buffer lies in PINNED host memory; it is
- * copied in chunks of at most chunk_bytes with hipMemcpyAsync on copy_stream
- * into a ring of floor(staging_bytes / chunk_bytes) slots in dev_staging
- * (device memory, 16-byte aligned) and every landed chunk is scattered by a
- * kernel on kernel_stream.  The call first orders copy_stream after the work
- * already enqueued on kernel_stream, so a staging area may be reused by the
- * next call at once.  The pool is complete when kernel_stream reaches the end
- * of the enqueued work.  KVL_ESPACE: staging smaller than one chunk, or a
- * chunk smaller than one descriptor.  copy_stream and kernel_stream should
- * differ for the copies to overlap the scatter.
+ * copied in chunks of at most chunk_bytes with hipMemcpyAsync into
+ * k = min(8, floor(staging_bytes / chunk_bytes)) slots of dev_staging (device
+ * memory, 16-byte aligned) and every landed chunk is scattered by a kernel.  Each
+ * slot has a stream of the library's own on which its copies and scatters
+ * alternate; the k of them run side by side, so the scatters hide under the
+ * copies.  The call orders that work after everything already enqueued on
+ * copy_stream and kernel_stream, and makes kernel_stream wait for its end: the
+ * pool is complete when kernel_stream reaches the end of the enqueued work, and
+ * a staging area may be reused by the next call at once.  KVL_ESPACE: staging
+ * smaller than one chunk, or a chunk smaller than one descriptor.  Chunks of
+ * 8 MiB or more keep the per-copy submission cost (Section 5.2) negligible.
  * chunk_bytes == 0 selects the zero-copy form: no staging, no copies; one scatter
  * kernel on kernel_stream reads the pinned buffer across the host link itself
  * (dev_staging, staging_bytes and copy_stream are then unused). */

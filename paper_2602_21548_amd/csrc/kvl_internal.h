@@ -22,9 +22,10 @@ struct kvl_plan_s {
     kvl_unit_t *d_units = nullptr;               // device copy (absent for KVL_HOST_ONLY)
     int device = -1;
     kvl_tuning_t tuning{};                       // resolved (no zero fields)
-    // events reused by the h2d path: one "landed" and one "slot free" per ring slot
-    std::vector<hipEvent_t> ev_landed, ev_free;
-    hipEvent_t ev_entry = nullptr;
+    // h2d path: one lane (a stream of the library's own) and one "lane done" event per staging slot
+    std::vector<hipStream_t> lanes;
+    std::vector<hipEvent_t> ev_lane_done;
+    hipEvent_t ev_entry = nullptr, ev_entry2 = nullptr;
 };
 
 namespace kvl {
@@ -62,7 +63,8 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
                  uint32_t plane_begin, uint32_t plane_end,
                  void *const *pool_planes, const uintptr_t *xfer_plane, hipStream_t stream);
 
-int ensure_ring_events(kvl_plan_t *plan, size_t slots);
+int ensure_lanes(kvl_plan_t *plan, size_t lanes);
+int lanes_follow(kvl_plan_t *plan, size_t lanes, hipStream_t copy_s, hipStream_t kern_s);
 
 // Enqueue the move of one layer between a buffer of Full Blocks and a paged pool.
 int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint64_t blocks_bytes,

@@ -42,18 +42,6 @@ int make_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, std::vector<kvl_ch
     return KVL_OK;
 }
 
-int ensure_ring_events(kvl_plan_t *plan, size_t slots) {
-    while (plan->ev_landed.size() < slots) {
-        hipEvent_t a = nullptr, b = nullptr;
-        KVL_HIP(hipEventCreateWithFlags(&a, hipEventDisableTiming));
-        plan->ev_landed.push_back(a);
-        KVL_HIP(hipEventCreateWithFlags(&b, hipEventDisableTiming));
-        plan->ev_free.push_back(b);
-    }
-    if (!plan->ev_entry) KVL_HIP(hipEventCreateWithFlags(&plan->ev_entry, hipEventDisableTiming));
-    return KVL_OK;
-}
-
 static int resolve_tuning(const kvl_tuning_t *in, kvl_tuning_t *out) {
     kvl_tuning_t t{};
     if (in) t = *in;
@@ -236,9 +224,13 @@ int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, ui
 void kvl_plan_destroy(kvl_plan_t *plan) {
     if (!plan) return;
     if (plan->d_units) (void)hipFree(plan->d_units);
-    for (hipEvent_t e : plan->ev_landed) (void)hipEventDestroy(e);
-    for (hipEvent_t e : plan->ev_free) (void)hipEventDestroy(e);
+    for (hipStream_t s : plan->lanes) {
+        (void)hipStreamSynchronize(s);
+        (void)hipStreamDestroy(s);
+    }
+    for (hipEvent_t e : plan->ev_lane_done) (void)hipEventDestroy(e);
     if (plan->ev_entry) (void)hipEventDestroy(plan->ev_entry);
+    if (plan->ev_entry2) (void)hipEventDestroy(plan->ev_entry2);
     delete plan;
 }
 

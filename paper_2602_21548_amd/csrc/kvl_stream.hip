@@ -3,10 +3,11 @@
 // layer-wise prefill only a few layers' cache is resident at a time).
 //
 // Three streams and a handful of events carry the ordering:
-//   copy stream    host -> staging chunks, throttled by the staging ring
-//   kernel stream  scatter of each landed chunk; the first scatter of layer l
-//                  waits for "compute of layer l - S finished" (the slot it is
-//                  about to overwrite is no longer being read)
+//   lanes          (library-owned, one per staging slot) host -> staging copy and
+//                  scatter of each chunk, alternating in order; a lane's first
+//                  scatter of layer l waits for "compute of layer l - S finished"
+//                  (the slot it is about to overwrite is no longer being read)
+//   kernel stream  collects the lanes at the end of each layer: "layer l loaded"
 //   compute stream compute(l) waits for "layer l loaded"
 #include <algorithm>
 #include <vector>
@@ -18,9 +19,8 @@ namespace kvl {
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 int enqueue_h2d_layer(kvl_plan_t *plan, const std::vector<kvl_chunk_t> &chunks,
-                      const void *host_xfer, void *dev_staging, uint64_t chunk_bytes, size_t slots,
-                      void *const *pool_planes, hipStream_t copy_s, hipStream_t kern_s,
-                      hipEvent_t wait_before_scatter, size_t *ring_pos);
+                      const void *host_xfer, void *dev_staging, uint64_t chunk_bytes, size_t lanes,
+                      void *const *pool_planes, hipStream_t kern_s, hipEvent_t wait_before_scatter);
 int check_h2d_args(const kvl_plan_t *plan, const void *host, const void *staging,
                    uint64_t staging_bytes, uint64_t chunk_bytes, size_t *slots);
 int enqueue_zero_copy_layer(const kvl_plan_t *plan, const void *host_xfer, void *const *pool_planes,
@@ -54,6 +54,7 @@ struct RunState {
     std::vector<hipEvent_t> events;
     kvl_probe_t *d_probes = nullptr;
     hipStream_t streams[3] = {nullptr, nullptr, nullptr};
+    const std::vector<hipStream_t> *lanes = nullptr;
 
     int make(hipEvent_t *e, bool timing) {
         KVL_HIP(hipEventCreateWithFlags(e, timing ? hipEventDefault : hipEventDisableTiming));
@@ -62,6 +63,8 @@ struct RunState {
     }
     ~RunState() {
         // nothing enqueued by the run may outlive what it refers to
+        if (lanes)
+            for (hipStream_t s : *lanes) (void)hipStreamSynchronize(s);
         for (hipStream_t s : streams) (void)hipStreamSynchronize(s);
         for (hipEvent_t e : events) (void)hipEventDestroy(e);
         if (d_probes) (void)hipFree(d_probes);
@@ -114,7 +117,7 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
         }
         if (rc != KVL_OK) return rc;
     }
-    rc = ensure_ring_events(plan, slots ? slots : 1);
+    rc = ensure_lanes(plan, slots ? slots : 1);
     if (rc != KVL_OK) return rc;
 
     hipStream_t cs = (hipStream_t)cfg->copy_stream, ks = (hipStream_t)cfg->kernel_stream,
@@ -128,6 +131,7 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
 
     RunState st;
     st.streams[0] = cs; st.streams[1] = ks; st.streams[2] = ms;
+    st.lanes = &plan->lanes;
     hipEvent_t ev_start = nullptr, ev_sync = nullptr;
     std::vector<hipEvent_t> loaded(L), cbeg(L), cend(L), h2d_done(L);
     try {
@@ -158,7 +162,11 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
     KVL_HIP(hipStreamWaitEvent(ks, ev_start, 0));
     KVL_HIP(hipStreamWaitEvent(ms, ev_start, 0));
 
-    size_t ring_pos = 0;
+    // the lanes start where the three streams start
+    if (!from_blocks && !zero_copy) {
+        rc = lanes_follow(plan, slots, cs, ks);
+        if (rc != KVL_OK) return rc;
+    }
     for (uint32_t l = 0; l < L; ++l) {
         const uint32_t s = l % S;
         void *const *slot_planes = cfg->dev_slot_planes + (size_t)s * P;
@@ -182,11 +190,12 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
                 if (rc == KVL_OK) KVL_HIP(hipEventRecord(h2d_done[l], ks));
             } else {
                 rc = enqueue_h2d_layer(plan, chunks, host_slot, cfg->dev_staging, cfg->chunk_bytes, slots,
-                                       slot_planes, cs, ks, l >= S ? cend[l - S] : nullptr, &ring_pos);
+                                       slot_planes, ks, l >= S ? cend[l - S] : nullptr);
+                // every copy of the layer has been scattered by then: the host slot is free again
+                if (rc == KVL_OK) KVL_HIP(hipEventRecord(h2d_done[l], ks));
             }
         }
         if (rc != KVL_OK) return rc;
-        if (!zero_copy) KVL_HIP(hipEventRecord(h2d_done[l], cs));
         KVL_HIP(hipEventRecord(loaded[l], ks));
 
         KVL_HIP(hipStreamWaitEvent(ms, loaded[l], 0));
