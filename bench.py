@@ -199,6 +199,10 @@ def main() -> int:
     pack_ms = np.array([a.elapsed_time(b) for a, b, _ in per_kernel])
     unpack_ms = np.array([b.elapsed_time(c) for _, b, c in per_kernel])
     value = L * payload / (ms_per_step * 1e-3) / 1e9
+    for name, ms in (("pack", pack_ms), ("unpack", unpack_ms)):
+        worst = np.argsort(ms)[-4:][::-1]
+        log(f"[bench] {name}: median {np.median(ms):.3f} ms; slowest launches (step, layer, ms): "
+            + ", ".join(f"({i // L}, {i % L}, {ms[i]:.2f})" for i in worst))
 
     # plan cost on its own (host work + descriptor upload), outside the timed steps
     t0 = time.perf_counter()
