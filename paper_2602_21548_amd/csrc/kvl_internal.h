@@ -44,12 +44,6 @@ void set_hip_error(hipError_t e);
 constexpr uint32_t kDefaultUnitBytes = 128u << 10;
 constexpr uint32_t kDefaultBlockThreads = 256;
 constexpr uint32_t kNumVariants = 128;       // explicit variants are 1 .. kNumVariants
-constexpr uint32_t kDefaultPackCode = 2u | 4u | (2u << 3);   // tile x1, nt loads, sc1 stores
-constexpr uint32_t kDefaultUnpackCode = 2u | 4u | (3u << 3);    // tile x1, nt loads, sc1+nt stores
-constexpr uint32_t kDefaultUnpackCodeOddRows = 2u | (3u << 3);  // tile x1, plain loads, sc1+nt stores
-constexpr bool kLinearNtLoad = true;
-constexpr int kLinearStorePolicy = 2;
-
 bool valid_block_threads(uint32_t t);
 
 // Cut [0, n_units) of one plane into chunks of at most chunk_bytes.

@@ -40,6 +40,13 @@
 
 namespace kvl {
 
+// default variant codes (see the list above) and the plain copy's policies
+constexpr uint32_t kDefaultPackCode = 2u | 4u | (2u << 3);   // tile x1, nt loads, sc1 stores
+constexpr uint32_t kDefaultUnpackCode = 2u | 4u | (3u << 3);    // tile x1, nt loads, sc1+nt stores
+constexpr uint32_t kDefaultUnpackCodeOddRows = 2u | (3u << 3);  // tile x1, plain loads, sc1+nt stores
+constexpr bool kLinearNtLoad = true;
+constexpr int kLinearStorePolicy = 2;
+
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 // Every buffer is device (or device-mapped) memory: say so, so that the
 // compiler emits global_load / global_store rather than flat accesses.
