@@ -487,6 +487,18 @@ def host_link_legs(args) -> dict:
     h2d_gbps = payload / min(times) / 1e9
 
     st = K.kvl_stream_layers(plan, host, slots, staging, chunk, w.notes["compute_us"], cs, ks, ms, n_layers=L)
+    # the other direction: gather one layer straight into the pinned host buffer (the step that
+    # sends a layer's cache on to the decode engine's host buffer)
+    gplan = K.kvl_plan(lay, w.hit, w.app, w.dst.tables, K.KVL_GATHER)
+    d2h = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        K.kvl_pack_layer(gplan, slots[0], host[1], stream=ks)
+        ks.synchronize()
+        d2h.append(time.perf_counter() - t0)
+    gplan.destroy()
+    d2h_gbps = payload / min(d2h) / 1e9
     # the same 61 layers with the zero-copy form (scatter kernel reads the pinned buffers itself)
     zc = K.kvl_stream_layers(plan, host, slots, None, 0, w.notes["compute_us"], cs, ks, ms, n_layers=L)
     plan.destroy()
@@ -502,6 +514,7 @@ def host_link_legs(args) -> dict:
         "stream_layers": L, "stream_total_ms": round(st["total_ms"], 2),
         "stream_gbps": round(st["link_gbps"], 2), "stream_frac_of_link": round(st["link_gbps"] / peak, 4),
         "stream_exposed_ms": round(st["exposed_ms"], 2),
+        "pack_to_host_layer_gbps": round(d2h_gbps, 2),
         "stream_zero_copy_gbps": round(zc["link_gbps"], 2),
         "stream_zero_copy_frac_of_link": round(zc["link_gbps"] / peak, 4),
         "payload_bytes_per_layer": payload,

@@ -167,7 +167,10 @@ int kvl_plan_get_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes,
 /* Decode side (Section 4.1, decode-engine read path: the layer's hit cache
  * leaves the decode engine's buffer as Layer Blocks): gather.
  * pool_planes: host array of n_planes device pointers, layer l's plane bases.
- * xfer: device buffer of xfer_capacity >= payload bytes (else KVL_ESPACE).
+ * xfer: device buffer of xfer_capacity >= payload bytes (else KVL_ESPACE); it may
+ * also be pinned host memory mapped into the device's address space (the host
+ * buffer of the engine the cache is sent on to): the kernel then writes it
+ * across the host link itself.
  * Needs a KVL_GATHER plan.  Enqueues on stream. */
 int kvl_pack_layer(const kvl_plan_t *plan, const void *const *pool_planes,
                    void *xfer, uint64_t xfer_capacity, void *stream);

@@ -295,8 +295,13 @@ def _plane_ptrs(plan: Plan, planes: Sequence[torch.Tensor], what: str):
 
 
 def kvl_pack_layer(plan: Plan, pool_planes: Sequence[torch.Tensor], xfer: torch.Tensor, stream=None) -> None:
+    """xfer: a device tensor, or a pinned host tensor (the kernel then writes it over the host link)."""
     arr = _plane_ptrs(plan, pool_planes, "kvl_pack_layer pool")
-    _check(_lib.kvl_pack_layer(plan.handle, arr, _dev(xfer, "xfer"), _nbytes(xfer), _stream_handle(stream)),
+    if isinstance(xfer, torch.Tensor) and not xfer.is_cuda:
+        ptr = _pinned(xfer, "xfer", 0)
+    else:
+        ptr = _dev(xfer, "xfer")
+    _check(_lib.kvl_pack_layer(plan.handle, arr, ptr, _nbytes(xfer), _stream_handle(stream)),
            "kvl_pack_layer")
 
 

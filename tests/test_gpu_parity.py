@@ -505,3 +505,39 @@ def test_hip_graph_capture_and_replay():
             oracle.unpack(bs, rows, w.hit, w.dst.tables, want_x, want)
             assert same_bytes(to_host(x[l]), want_x), f"replay {rep} layer {l}: transfer buffer"
             assert same_bytes(to_host(dst[l][0]), want[0]), f"replay {rep} layer {l}: pool"
+
+
+@pytest.mark.parametrize("name,make", H2D_CASES, ids=[c[0] for c in H2D_CASES])
+def test_host_buffers_both_ways_whole_prompt(name, make):
+    """The prefill-engine read path after a layer's compute (Section 4.1, steps 5-9): hit and miss
+    rows together go to the decode engine's host buffer (pack straight into pinned memory), and
+    from there into the decode engine's HBM (host-buffer load of the whole prompt)."""
+    w = make()
+    if name == "cfg1":
+        w.hit[:] = [1000, 992, 1001, 983]
+        w.app[:] = [7, 16, 0, 25]
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    zero, tot = np.zeros_like(w.hit), w.hit + w.app
+    pe = W.fill_pool(w, 2, "dst")
+    want_x = oracle.pack_range(bs, rows, zero, tot, w.dst.tables, pe)
+    want_de = W.sentinel_pool(w, "src")
+    oracle.unpack_range(bs, rows, zero, tot, w.src.tables, want_x, want_de)
+    g = K.kvl_plan(K.make_layout(1, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables,
+                   K.KVL_GATHER | K.KVL_TOKENS_ALL)
+    s = K.kvl_plan(K.make_layout(1, bs, rows, w.src.pool_blocks), w.hit, w.app, w.src.tables,
+                   K.KVL_SCATTER | K.KVL_TOKENS_ALL, unit_bytes=16384)
+    n = g.payload_bytes
+    host = torch.full((n + 64,), 0x3C, dtype=torch.uint8).pin_memory()
+    d_pe = planes_to_dev(pe)
+    d_de = planes_to_dev(W.sentinel_pool(w, "src"))
+    staging = torch.zeros(3 * 65536, dtype=torch.uint8, device="cuda")
+    cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    K.kvl_pack_layer(g, d_pe, host, stream=ks)
+    ks.synchronize()
+    got = host.numpy()
+    assert same_bytes(got[:n], want_x) and np.all(got[n:] == 0x3C)
+    K.kvl_h2d_unpack_layer(s, host, staging, 65536, d_de, cs, ks)
+    ks.synchronize()
+    for a, b in zip(d_de, want_de):
+        assert same_bytes(to_host(a), b)
