@@ -145,9 +145,12 @@ def main() -> int:
     WIN = min(2, L)
     log(f"[bench] {WORKLOADS[args.config]}")
     t0 = time.perf_counter()
-    src = []
+    src, src_tags = [], []
     for s in range(WIN):
-        src.append([torch.from_numpy(p).to(dev) for p in W.fill_pool_fast(w, s, "src")])
+        host_planes = W.fill_pool_fast(w, s, "src")
+        src_tags.append(row_heads(host_planes, rows))          # kept on the host for the oracle check
+        src.append([torch.from_numpy(p).to(dev) for p in host_planes])
+        del host_planes
     dst = [[torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device=dev) for r in rows]
            for _ in range(WIN)]
     probe = K.kvl_plan(lay_src, w.hit, w.app, w.src.tables, K.KVL_GATHER | K.KVL_HOST_ONLY)
@@ -212,7 +215,7 @@ def main() -> int:
 
     # every row's placement, checked against the oracle through 8-byte row tags
     last_slot = (L - 1) % WIN              # the transfer buffer and this slot hold the last layer
-    verified = verify_tags(w, src[last_slot], dst[last_slot], xfer, T)
+    verified = verify_tags(w, src_tags[last_slot], dst[last_slot], xfer, T)
 
     ceiling = copy_ceiling(stream, args.calibration_copy_gib or 4.0)
 
@@ -266,7 +269,12 @@ def main() -> int:
     return 0
 
 
-def verify_tags(w, src_planes, dst_planes, xfer, T) -> int:
+def row_heads(host_planes, rows):
+    """First 8 bytes of every row of each plane (host arrays, before they go to the device)."""
+    return [np.ascontiguousarray(p.reshape(-1, r)[:, :8]).reshape(-1) for p, r in zip(host_planes, rows)]
+
+
+def verify_tags(w, tag_src, dst_planes, xfer, T) -> int:
     """The fast fill writes (layer, plane, physical row) into the first 8 bytes of
     every pool row.  Packing and unpacking those tags with the CPU oracle says where
     every row must have gone; compare with what the GPU path left behind."""
@@ -274,7 +282,6 @@ def verify_tags(w, src_planes, dst_planes, xfer, T) -> int:
     import oracle
     bs, rows = w.layout.block_tokens, w.layout.row_bytes
     tag_rows = tuple(8 for _ in rows)
-    tag_src = [p.view(-1, r)[:, :8].contiguous().cpu().numpy().reshape(-1) for p, r in zip(src_planes, rows)]
     want_x = oracle.pack(bs, tag_rows, w.hit, w.src.tables, tag_src, threads=8)
     want_dst = [np.full(w.dst.pool_blocks * bs * 8, 0xA5, dtype=np.uint8) for _ in rows]
     oracle.unpack(bs, tag_rows, w.hit, w.dst.tables, want_x, want_dst, threads=8)
@@ -378,7 +385,10 @@ def short_hop(index: int, reps: int = 8) -> dict:
     dev = torch.device("cuda:0")
     w = W.config(index)
     L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
-    src = [torch.from_numpy(p).to(dev) for p in W.fill_pool_fast(w, 0, "src")]
+    host_planes = W.fill_pool_fast(w, 0, "src")
+    src_tags = row_heads(host_planes, rows)
+    src = [torch.from_numpy(p).to(dev) for p in host_planes]
+    del host_planes
     dst = [torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device=dev) for r in rows]
     t0 = time.perf_counter()
     g = K.kvl_plan(K.make_layout(L, bs, rows, w.src.pool_blocks), w.hit, w.app, w.src.tables, K.KVL_GATHER)
@@ -399,7 +409,7 @@ def short_hop(index: int, reps: int = 8) -> dict:
         if i >= 2:
             pk.append(e0.elapsed_time(e1))
             up.append(e1.elapsed_time(e2))
-    verified = verify_tags(w, src, dst, xfer, T)
+    verified = verify_tags(w, src_tags, dst, xfer, T)
     pm, um = float(np.mean(pk)), float(np.mean(up))
     out = {"workload": WORKLOADS[index], "payload_bytes_per_layer": payload, "hit_tokens": T,
            "pack_ms": round(pm, 4), "unpack_ms": round(um, 4),
