@@ -242,7 +242,7 @@ H2D_CASES = [c for c in CASES if c[0] in ("tiny-runs-2planes", "tiny-oddrow", "c
 
 
 @pytest.mark.parametrize("name,make", H2D_CASES, ids=[c[0] for c in H2D_CASES])
-@pytest.mark.parametrize("chunk_kb,slots", [(64, 1), (64, 3), (1024, 2), (0, 0)])
+@pytest.mark.parametrize("chunk_kb,slots", [(64, 1), (64, 3), (1024, 2), (16, 8), (16, 12), (0, 0)])
 def test_h2d_unpack(name, make, chunk_kb, slots):
     w = make()
     bs, rows = w.layout.block_tokens, w.layout.row_bytes
