@@ -27,6 +27,8 @@ int ensure_lanes(kvl_plan_t *plan, size_t lanes) {
         hipStream_t s = nullptr;
         KVL_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
         plan->lanes.push_back(s);
+    }
+    while (plan->ev_lane_done.size() < lanes) {
         hipEvent_t e = nullptr;
         KVL_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
         plan->ev_lane_done.push_back(e);
@@ -116,7 +118,7 @@ extern "C" {
 int kvl_h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xfer, void *dev_staging,
                          uint64_t staging_bytes, uint64_t chunk_bytes, void *const *pool_planes,
                          void *copy_stream, void *kernel_stream) {
-    kvl_plan_t *plan = const_cast<kvl_plan_t *>(plan_c);   // the plan's event ring is scratch state
+    kvl_plan_t *plan = const_cast<kvl_plan_t *>(plan_c);   // the plan's lanes and events are scratch state
     size_t slots = 0;
     int rc = kvl::check_h2d_args(plan, pinned_host_xfer, dev_staging, staging_bytes, chunk_bytes, &slots);
     if (rc != KVL_OK) return rc;
