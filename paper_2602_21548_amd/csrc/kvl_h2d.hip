@@ -16,6 +16,7 @@
 // layer).  An earlier form with one copy stream, one kernel stream and two
 // events per chunk lost 15-25 % of the link at 8-16 MiB chunks to those events.
 #include <algorithm>
+#include <new>
 #include <vector>
 
 #include "kvl_internal.h"
@@ -113,11 +114,9 @@ int check_h2d_args(const kvl_plan_t *plan, const void *host, const void *staging
 
 }  // namespace kvl
 
-extern "C" {
-
-int kvl_h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xfer, void *dev_staging,
-                         uint64_t staging_bytes, uint64_t chunk_bytes, void *const *pool_planes,
-                         void *copy_stream, void *kernel_stream) {
+static int h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xfer, void *dev_staging,
+                            uint64_t staging_bytes, uint64_t chunk_bytes, void *const *pool_planes,
+                            void *copy_stream, void *kernel_stream) {
     kvl_plan_t *plan = const_cast<kvl_plan_t *>(plan_c);   // the plan's lanes and events are scratch state
     size_t slots = 0;
     int rc = kvl::check_h2d_args(plan, pinned_host_xfer, dev_staging, staging_bytes, chunk_bytes, &slots);
@@ -127,11 +126,7 @@ int kvl_h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xfer,
     if (chunk_bytes == 0)
         return kvl::enqueue_zero_copy_layer(plan, pinned_host_xfer, pool_planes, (hipStream_t)kernel_stream, nullptr);
     std::vector<kvl_chunk_t> chunks;
-    try {
-        rc = kvl::make_chunks(plan, chunk_bytes, chunks);
-    } catch (const std::bad_alloc &) {
-        return KVL_ENOMEM;
-    }
+    rc = kvl::make_chunks(plan, chunk_bytes, chunks);
     if (rc != KVL_OK) return rc;
     rc = kvl::ensure_lanes(plan, slots);
     if (rc != KVL_OK) return rc;
@@ -140,6 +135,19 @@ int kvl_h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xfer,
     if (rc != KVL_OK) return rc;
     return kvl::enqueue_h2d_layer(plan, chunks, pinned_host_xfer, dev_staging, chunk_bytes, slots,
                                   pool_planes, ks, nullptr);
+}
+
+extern "C" {
+
+int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer, void *dev_staging,
+                         uint64_t staging_bytes, uint64_t chunk_bytes, void *const *pool_planes,
+                         void *copy_stream, void *kernel_stream) {
+    try {
+        return h2d_unpack_layer(plan, pinned_host_xfer, dev_staging, staging_bytes, chunk_bytes, pool_planes,
+                                copy_stream, kernel_stream);
+    } catch (const std::bad_alloc &) {
+        return KVL_ENOMEM;
+    }
 }
 
 int kvl_h2d_blockwise_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,

@@ -10,6 +10,7 @@
 //   kernel stream  collects the lanes at the end of each layer: "layer l loaded"
 //   compute stream compute(l) waits for "layer l loaded"
 #include <algorithm>
+#include <new>
 #include <vector>
 
 #include "kvl_internal.h"
@@ -73,8 +74,7 @@ struct RunState {
 
 }  // namespace kvl
 
-extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg,
-                                 kvl_stream_stats_t *stats) {
+static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, kvl_stream_stats_t *stats) {
     using namespace kvl;
     kvl_plan_t *plan = const_cast<kvl_plan_t *>(plan_c);
     if (!plan || !cfg) return KVL_EINVAL;
@@ -110,11 +110,7 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
     std::vector<kvl_chunk_t> chunks;
     const bool zero_copy = !from_blocks && cfg->chunk_bytes == 0;
     if (!from_blocks && !zero_copy) {
-        try {
-            rc = make_chunks(plan, cfg->chunk_bytes, chunks);
-        } catch (const std::bad_alloc &) {
-            return KVL_ENOMEM;
-        }
+        rc = make_chunks(plan, cfg->chunk_bytes, chunks);
         if (rc != KVL_OK) return rc;
     }
     rc = ensure_lanes(plan, slots ? slots : 1);
@@ -134,11 +130,7 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
     st.lanes = &plan->lanes;
     hipEvent_t ev_start = nullptr, ev_sync = nullptr;
     std::vector<hipEvent_t> loaded(L), cbeg(L), cend(L), h2d_done(L);
-    try {
-        st.events.reserve(4 * (size_t)L + 2);
-    } catch (const std::bad_alloc &) {
-        return KVL_ENOMEM;
-    }
+    st.events.reserve(4 * (size_t)L + 2);
     if ((rc = st.make(&ev_start, true)) != KVL_OK) return rc;
     if ((rc = st.make(&ev_sync, false)) != KVL_OK) return rc;
     for (uint32_t l = 0; l < L; ++l) {
@@ -247,4 +239,12 @@ extern "C" int kvl_stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_
         }
     }
     return KVL_OK;
+}
+
+extern "C" int kvl_stream_layers(const kvl_plan_t *plan, const kvl_stream_cfg_t *cfg, kvl_stream_stats_t *stats) {
+    try {
+        return stream_layers(plan, cfg, stats);
+    } catch (const std::bad_alloc &) {
+        return KVL_ENOMEM;
+    }
 }
