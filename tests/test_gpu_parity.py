@@ -541,3 +541,35 @@ def test_host_buffers_both_ways_whole_prompt(name, make):
     ks.synchronize()
     for a, b in zip(d_de, want_de):
         assert same_bytes(to_host(a), b)
+
+
+def test_stream_layers_argument_errors():
+    w = W.tiny(215, 3, 16, (32,), 32, 60, allow_zero_hit=False)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    g = dev_plan(w, "dst", K.KVL_GATHER)
+    n = s.payload_bytes
+    host = [torch.zeros(n, dtype=torch.uint8, pin_memory=True)]
+    slots = [[torch.zeros(32 * 16 * 32, dtype=torch.uint8, device="cuda")]]
+    staging = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+
+    def call(plan=s, **kw):
+        args = dict(host_layers=host, dev_slots=slots, dev_staging=staging, chunk_bytes=1 << 16, compute_us=10,
+                    copy_stream=cs, kernel_stream=ks, compute_stream=ms, n_layers=2)
+        args.update(kw)
+        return K.kvl_stream_layers(plan, **args)
+
+    assert call()["h2d_bytes"] == 2 * n                                   # the well-formed call works
+    for bad in (dict(compute_us=2_000_000),                               # absurd compute time
+                dict(probes=[(0, 8)], probe_out=out),                     # probe not 16-byte aligned
+                dict(probes=[(1, 0)], probe_out=out),                     # plane out of range
+                dict(probes=[(0, 32 * 16 * 32)], probe_out=out),          # probe beyond the slot
+                dict(chunk_bytes=16),                                     # chunk smaller than a descriptor
+                dict(plan=g)):                                            # gather plan
+        with pytest.raises(K.KvlError) as e:
+            call(**bad)
+        assert e.value.code in (K.KVL_EINVAL, K.KVL_ESPACE), bad
+    with pytest.raises(K.KvlError):
+        call(dev_slots=[])                                                # no destination slot
+    torch.cuda.synchronize()
