@@ -227,6 +227,19 @@ int kvl_fullblocks_to_pool_layer(const kvl_plan_t *plan, const void *full_blocks
 int kvl_pool_to_fullblocks_layer(const kvl_plan_t *plan, const void *const *pool_planes, uint32_t layer,
                                  void *full_blocks, uint64_t full_blocks_bytes, void *stream);
 
+/* Confine the scatter kernels of the host-buffer path to some compute units.
+ * The paper isolates cache traffic from the model's own traffic with network QoS
+ * (Section 5.1); on the GPU the matching question is how many compute units the
+ * load may occupy.  The staged chunks arrive at host-link rate, which a handful
+ * of compute units can scatter, so the library's lanes can be created with a
+ * compute-unit mask (hipExtStreamCreateWithCUMask: bit i of mask[] enables CU i;
+ * n_words 32-bit words).  n_words == 0 removes the mask.  Existing lanes are
+ * drained and re-created; a mask the runtime cannot honour (on MI355X: fewer than
+ * one compute unit in each of the 8 XCDs, i.e. fewer than the first 8 bits) shows
+ * up as KVL_EHIP from the next host-buffer call.  Every masked lane takes a
+ * hardware queue of its own.  Streams the caller passes in are the caller's to mask. */
+int kvl_plan_set_lane_cu_mask(kvl_plan_t *plan, const uint32_t *mask, uint32_t n_words);
+
 /* The same result with one hipMemcpyAsync per descriptor and plane, straight from
  * the pinned host buffer into the paged pool: no staging, no kernel.  This is the
  * many-small-copies pattern whose per-copy submission cost Section 5.2 measures

@@ -109,6 +109,7 @@ _SIGNATURES = {
                                                C.POINTER(C.c_void_p), C.c_void_p]),
     "kvl_pool_to_fullblocks_layer": (C.c_int, [_PLAN_P, C.POINTER(C.c_void_p), C.c_uint32, C.c_void_p,
                                                C.c_uint64, C.c_void_p]),
+    "kvl_plan_set_lane_cu_mask": (C.c_int, [_PLAN_P, C.POINTER(C.c_uint32), C.c_uint32]),
     "kvl_h2d_blockwise_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
                                           C.POINTER(C.c_uint64)]),
     "kvl_stream_layers": (C.c_int, [_PLAN_P, C.POINTER(kvl_stream_cfg_t), C.POINTER(kvl_stream_stats_t)]),
@@ -242,6 +243,17 @@ class Plan:
         a, b = C.c_uint64(), C.c_uint64()
         _check(_lib.kvl_plan_fullblock_geometry(self.handle, C.byref(a), C.byref(b)), "kvl_plan_fullblock_geometry")
         return int(a.value), int(b.value)
+
+    def set_lane_cu_mask(self, enabled_cus: Optional[Sequence[int]]) -> None:
+        """Confine the host-buffer path's scatter kernels to the given compute units (None: no mask)."""
+        if not enabled_cus:
+            _check(_lib.kvl_plan_set_lane_cu_mask(self.handle, None, 0), "kvl_plan_set_lane_cu_mask")
+            return
+        words = max(enabled_cus) // 32 + 1
+        arr = (C.c_uint32 * words)()
+        for cu in enabled_cus:
+            arr[cu // 32] |= 1 << (cu % 32)
+        _check(_lib.kvl_plan_set_lane_cu_mask(self.handle, arr, words), "kvl_plan_set_lane_cu_mask")
 
     def set_tuning(self, block_threads: int = 0, variant: int = 0) -> None:
         t = kvl_tuning_t(0, block_threads, variant, 0)

@@ -26,7 +26,11 @@ namespace kvl {
 int ensure_lanes(kvl_plan_t *plan, size_t lanes) {
     while (plan->lanes.size() < lanes) {
         hipStream_t s = nullptr;
-        KVL_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        if (plan->lane_cu_mask.empty())
+            KVL_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        else
+            KVL_HIP(hipExtStreamCreateWithCUMask(&s, (uint32_t)plan->lane_cu_mask.size(),
+                                                 plan->lane_cu_mask.data()));
         plan->lanes.push_back(s);
     }
     while (plan->ev_lane_done.size() < lanes) {
@@ -148,6 +152,24 @@ int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer, v
     } catch (const std::bad_alloc &) {
         return KVL_ENOMEM;
     }
+}
+
+int kvl_plan_set_lane_cu_mask(kvl_plan_t *plan, const uint32_t *mask, uint32_t n_words) {
+    if (!plan || (n_words && !mask) || (plan->flags & KVL_HOST_ONLY)) return KVL_EINVAL;
+    bool any = n_words == 0;
+    for (uint32_t i = 0; i < n_words; ++i) any = any || mask[i] != 0;
+    if (!any) return KVL_EINVAL;                       // a mask with no compute unit at all
+    try {
+        for (hipStream_t s : plan->lanes) {
+            KVL_HIP(hipStreamSynchronize(s));
+            KVL_HIP(hipStreamDestroy(s));
+        }
+        plan->lanes.clear();
+        plan->lane_cu_mask.assign(mask, mask + n_words);
+    } catch (const std::bad_alloc &) {
+        return KVL_ENOMEM;
+    }
+    return KVL_OK;
 }
 
 int kvl_h2d_blockwise_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,

@@ -24,6 +24,7 @@ struct kvl_plan_s {
     kvl_tuning_t tuning{};                       // resolved (no zero fields)
     // h2d path: one lane (a stream of the library's own) and one "lane done" event per staging slot
     std::vector<hipStream_t> lanes;
+    std::vector<uint32_t> lane_cu_mask;          // empty: lanes may use every compute unit
     std::vector<hipEvent_t> ev_lane_done;
     hipEvent_t ev_entry = nullptr, ev_entry2 = nullptr;
 };

@@ -573,3 +573,25 @@ def test_stream_layers_argument_errors():
     with pytest.raises(K.KvlError):
         call(dev_slots=[])                                                # no destination slot
     torch.cuda.synchronize()
+
+
+def test_h2d_lanes_confined_to_a_few_compute_units():
+    """A compute-unit mask on the library's lanes changes where the scatters run, not what they write."""
+    w = W.config(2, n_requests=7, token_scale=1 / 32)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    n = oracle.payload_bytes(w.hit, rows)
+    x = W.random_payload(w, 4, n)
+    want = W.sentinel_pool(w, "dst")
+    oracle.unpack(bs, rows, w.hit, w.dst.tables, x, want)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    host = pinned_from(x)
+    staging = torch.zeros(4 << 20, dtype=torch.uint8, device="cuda")
+    cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+    for mask in (list(range(8)), None):
+        s.set_lane_cu_mask(mask)
+        got = planes_to_dev(W.sentinel_pool(w, "dst"))
+        torch.cuda.synchronize()
+        K.kvl_h2d_unpack_layer(s, host, staging, 1 << 20, got, cs, ks)
+        ks.synchronize()
+        for a, b in zip(got, want):
+            assert same_bytes(to_host(a), b), f"mask {mask and len(mask)}"
