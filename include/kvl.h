@@ -133,9 +133,12 @@ int kvl_plan(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t
              uint32_t flags, kvl_plan_t **out);
 int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t n_req,
                    uint32_t flags, const kvl_tuning_t *tuning, kvl_plan_t **out);
-/* Frees the plan and its device descriptors.  Work enqueued with the plan must
- * have finished (synchronise the streams first). */
+/* Frees the plan.  Work enqueued with the plan must have finished (synchronise
+ * the streams first).  The device descriptor array goes back to a small cache
+ * inside the library (at most 16 buffers / 256 MiB) from which later plans are
+ * served without a device allocation; kvl_release_cached_memory empties it. */
 void kvl_plan_destroy(kvl_plan_t *plan);
+void kvl_release_cached_memory(void);
 
 /* Change launch tuning (block_threads, variant) of an existing plan;
  * unit_bytes is fixed at plan time and ignored here. */

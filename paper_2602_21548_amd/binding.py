@@ -93,6 +93,7 @@ _SIGNATURES = {
     "kvl_plan_tuned": (C.c_int, [C.POINTER(kvl_layout_t), C.POINTER(kvl_request_t), C.c_uint32, C.c_uint32,
                                  C.POINTER(kvl_tuning_t), C.POINTER(_PLAN_P)]),
     "kvl_plan_destroy": (None, [_PLAN_P]),
+    "kvl_release_cached_memory": (None, []),
     "kvl_plan_set_tuning": (C.c_int, [_PLAN_P, C.POINTER(kvl_tuning_t)]),
     "kvl_plan_payload_bytes": (C.c_int, [_PLAN_P, C.POINTER(C.c_uint64)]),
     "kvl_plan_hit_tokens": (C.c_int, [_PLAN_P, C.POINTER(C.c_uint64)]),
@@ -484,6 +485,10 @@ def kvl_copy_linear(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
     if _nbytes(dst) < n:
         raise ValueError("dst smaller than src")
     _check(_lib.kvl_copy_linear(_dev(src, "src"), _dev(dst, "dst"), n, _stream_handle(stream)), "kvl_copy_linear")
+
+
+def kvl_release_cached_memory() -> None:
+    _lib.kvl_release_cached_memory()
 
 
 def kvl_strerror(code: int) -> str:

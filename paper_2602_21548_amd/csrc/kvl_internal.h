@@ -20,6 +20,7 @@ struct kvl_plan_s {
     bool vec16 = false;                          // every row size is a multiple of 16 bytes
     std::vector<kvl_unit_t> units;               // host copy of the descriptors
     kvl_unit_t *d_units = nullptr;               // device copy (absent for KVL_HOST_ONLY)
+    size_t d_units_capacity = 0;                 // bytes of the cached buffer d_units lives in
     int device = -1;
     kvl_tuning_t tuning{};                       // resolved (no zero fields)
     // h2d path: one lane (a stream of the library's own) and one "lane done" event per staging slot

@@ -2,6 +2,7 @@
 // descriptors (kvl_plan), plan inspection, error text.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "kvl_internal.h"
@@ -40,6 +41,61 @@ int make_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, std::vector<kvl_ch
         }
     }
     return KVL_OK;
+}
+
+// Descriptor arrays come from a small per-process cache, so that a caller who
+// builds a plan per batch does not pay a device allocation and a device free
+// (both synchronise the device, and a free can stall the next launch for tens
+// of milliseconds) on every batch.
+namespace {
+struct CachedBuffer {
+    void *ptr;
+    size_t capacity;
+    int device;
+};
+std::mutex g_cache_mutex;
+std::vector<CachedBuffer> g_cache;
+constexpr size_t kCacheEntries = 16;
+constexpr size_t kCacheBytes = 256u << 20;      // never keep more than this much idle
+
+size_t round_capacity(size_t bytes) {
+    size_t cap = 64u << 10;
+    while (cap < bytes) cap <<= 1;
+    return cap;
+}
+}  // namespace
+
+static hipError_t descriptor_alloc(void **out, size_t bytes, size_t *capacity, int device) {
+    const size_t want = round_capacity(bytes);
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        for (size_t i = 0; i < g_cache.size(); ++i) {
+            if (g_cache[i].device == device && g_cache[i].capacity == want) {
+                *out = g_cache[i].ptr;
+                *capacity = want;
+                g_cache.erase(g_cache.begin() + (long)i);
+                return hipSuccess;
+            }
+        }
+    }
+    *capacity = want;
+    return hipMalloc(out, want);
+}
+
+static void descriptor_release(void *ptr, size_t capacity, int device) {
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        size_t held = 0;
+        for (const CachedBuffer &b : g_cache) held += b.capacity;
+        if (g_cache.size() < kCacheEntries && held + capacity <= kCacheBytes) {
+            try {
+                g_cache.push_back(CachedBuffer{ptr, capacity, device});
+                return;
+            } catch (const std::bad_alloc &) {
+            }
+        }
+    }
+    (void)hipFree(ptr);
 }
 
 static int resolve_tuning(const kvl_tuning_t *in, kvl_tuning_t *out) {
@@ -193,7 +249,7 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
         hipError_t e = hipGetDevice(&plan->device);
         if (e == hipSuccess && !plan->units.empty()) {
             const size_t bytes = plan->units.size() * sizeof(kvl_unit_t);
-            e = hipMalloc((void **)&plan->d_units, bytes);
+            e = descriptor_alloc((void **)&plan->d_units, bytes, &plan->d_units_capacity, plan->device);
             if (e == hipSuccess)
                 e = hipMemcpy(plan->d_units, plan->units.data(), bytes, hipMemcpyHostToDevice);
         }
@@ -223,7 +279,7 @@ int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, ui
 
 void kvl_plan_destroy(kvl_plan_t *plan) {
     if (!plan) return;
-    if (plan->d_units) (void)hipFree(plan->d_units);
+    if (plan->d_units) kvl::descriptor_release(plan->d_units, plan->d_units_capacity, plan->device);
     for (hipStream_t s : plan->lanes) {
         (void)hipStreamSynchronize(s);
         (void)hipStreamDestroy(s);
@@ -298,6 +354,15 @@ int kvl_plan_get_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, kvl_chunk_
     const size_t k = (size_t)std::min<uint64_t>(capacity, c.size());
     if (k) std::memcpy(out, c.data(), k * sizeof(kvl_chunk_t));
     return KVL_OK;
+}
+
+void kvl_release_cached_memory(void) {
+    std::vector<kvl::CachedBuffer> drop;
+    {
+        std::lock_guard<std::mutex> lock(kvl::g_cache_mutex);
+        drop.swap(kvl::g_cache);
+    }
+    for (const kvl::CachedBuffer &b : drop) (void)hipFree(b.ptr);
 }
 
 const char *kvl_strerror(int code) {
