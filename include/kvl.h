@@ -133,8 +133,9 @@ int kvl_plan(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t
              uint32_t flags, kvl_plan_t **out);
 int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t n_req,
                    uint32_t flags, const kvl_tuning_t *tuning, kvl_plan_t **out);
-/* Frees the plan.  Work enqueued with the plan must have finished (synchronise
- * the streams first).  The device descriptor array goes back to a small cache
+/* Frees the plan.  Work enqueued with the plan should have finished (synchronise
+ * the streams first; the call waits for the device to go idle in any case, as a
+ * device free would).  The device descriptor array goes back to a small cache
  * inside the library (at most 16 buffers / 256 MiB) from which later plans are
  * served without a device allocation; kvl_release_cached_memory empties it. */
 void kvl_plan_destroy(kvl_plan_t *plan);

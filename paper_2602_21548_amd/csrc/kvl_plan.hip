@@ -83,6 +83,10 @@ static hipError_t descriptor_alloc(void **out, size_t bytes, size_t *capacity, i
 }
 
 static void descriptor_release(void *ptr, size_t capacity, int device) {
+    // A kernel that still reads these descriptors must not see the next plan's: wait for the
+    // device as the device free this replaces would have (it is idle if the caller has
+    // synchronised its streams, as it should).
+    (void)hipDeviceSynchronize();
     {
         std::lock_guard<std::mutex> lock(g_cache_mutex);
         size_t held = 0;
