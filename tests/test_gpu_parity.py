@@ -142,6 +142,17 @@ def test_random_batches(seed):
     run_range_hop(w, K.KVL_TOKENS_ALL, unit_bytes=ub, block_threads=64)
 
 
+@pytest.mark.parametrize("bs", [8, 32, 128, 256])
+@pytest.mark.parametrize("row", [64, 656, 2048, 16384])
+def test_block_geometries(bs, row):
+    """Block sizes from 512 bytes to 4 MiB under the default tuning: blocks far smaller than a
+    tile, blocks that are split into several descriptors, rows with and without 128-byte alignment."""
+    blocks_per_req = max(2, min(24, (6 << 20) // (bs * row)))
+    w = W.tiny(300 + bs + row, 5, bs, (row,), 5 * (blocks_per_req + 3) + 7, bs * blocks_per_req, kind="runs")
+    run_hop(w)
+    run_range_hop(w, K.KVL_TOKENS_ALL)
+
+
 def test_layers_are_independent_pools():
     w = W.config(1)
     for layer in range(w.layout.n_layers):
