@@ -163,20 +163,19 @@ def main() -> int:
     stream = torch.cuda.Stream()
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
 
-    def step(record=None):
+    def step(events=None):
+        """One batch.  events: a list of L (before pack, between, after unpack) event triples."""
         g = K.kvl_plan(lay_src, w.hit, w.app, w.src.tables, K.KVL_GATHER)
         s = K.kvl_plan(lay_dst, w.hit, w.app, w.dst.tables, K.KVL_SCATTER)
         for l in range(L):
-            if record is not None:
-                e0, e1, e2 = ev(), ev(), ev()
-                e0.record(stream)
+            if events is not None:
+                events[l][0].record(stream)
             K.kvl_pack_layer(g, src[l % WIN], xfer, stream=stream)
-            if record is not None:
-                e1.record(stream)
+            if events is not None:
+                events[l][1].record(stream)
             K.kvl_unpack_layer(s, xfer, dst[l % WIN], stream=stream)
-            if record is not None:
-                e2.record(stream)
-                record.append((e0, e1, e2))
+            if events is not None:
+                events[l][2].record(stream)
         stream.synchronize()
         g.destroy()
         s.destroy()
@@ -192,12 +191,15 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    per_kernel = []
+    # the events are made before the clock starts; the timed region only records them
+    all_events = [[(ev(), ev(), ev()) for _ in range(L)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(per_kernel)
+    for k in range(args.steps):
+        step(all_events[k])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    per_kernel = [t for row in all_events for t in row]
     ms_per_step = wall * 1e3 / args.steps
     pack_ms = np.array([a.elapsed_time(b) for a, b, _ in per_kernel])
     unpack_ms = np.array([b.elapsed_time(c) for _, b, c in per_kernel])
