@@ -100,7 +100,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOADS))
     ap.add_argument("--skip-host-link", action="store_true", help="leave out the pinned-host legs")
     ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU-oracle baseline")
