@@ -606,3 +606,42 @@ def test_h2d_lanes_confined_to_a_few_compute_units():
         ks.synchronize()
         for a, b in zip(got, want):
             assert same_bytes(to_host(a), b), f"mask {mask and len(mask)}"
+
+
+def test_two_host_threads_with_their_own_plans():
+    """Plans are per-thread objects; the library's shared state (descriptor cache, error slots)
+    must stand two threads building, running and destroying plans at the same time."""
+    import threading
+    errors = []
+
+    def worker(seed):
+        try:
+            w = W.tiny(400 + seed, 6, 16, (1152,), 256, 400, kind="random")
+            bs, rows = w.layout.block_tokens, w.layout.row_bytes
+            src = W.fill_pool(w, seed, "src")
+            want_x = oracle.pack(bs, rows, w.hit, w.src.tables, src)
+            want = W.sentinel_pool(w, "dst")
+            oracle.unpack(bs, rows, w.hit, w.dst.tables, want_x, want)
+            d_src = planes_to_dev(src)
+            st = torch.cuda.Stream()
+            for _ in range(25):
+                g = dev_plan(w, "src", K.KVL_GATHER)
+                s = dev_plan(w, "dst", K.KVL_SCATTER)
+                x = torch.zeros(g.payload_bytes, dtype=torch.uint8, device="cuda")
+                d = planes_to_dev(W.sentinel_pool(w, "dst"))
+                torch.cuda.current_stream().synchronize()
+                K.kvl_pack_layer(g, d_src, x, stream=st)
+                K.kvl_unpack_layer(s, x, d, stream=st)
+                st.synchronize()
+                assert same_bytes(to_host(x), want_x) and same_bytes(to_host(d[0]), want[0])
+                g.destroy()
+                s.destroy()
+        except Exception as e:  # noqa: BLE001
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
