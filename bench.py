@@ -233,6 +233,7 @@ def main() -> int:
                 "min_launch_ms": round(float(ms.min()), 4), "launches": int(ms.size)}
 
     tail = None if args.only_steps else tail_return_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN)
+    fused = None if args.only_steps else fused_move_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN, payload)
 
     roof_pack = roof("kvl_pack_tile_kernel", pack_ms)
     roof_unpack = roof("kvl_unpack_tile_kernel", unpack_ms)
@@ -253,7 +254,7 @@ def main() -> int:
         "tokens_layers_per_s": round(T * L / (ms_per_step * 1e-3), 1),
         "plan_ms": round(plan_ms, 3), "verified_rows_vs_oracle": verified,
         "linear_copy_ceiling_gbps": round(ceiling, 1),
-        "tail_return": tail,
+        "tail_return": tail, "fused_move": fused,
     }
     del src, dst, xfer
     torch.cuda.empty_cache()
@@ -357,6 +358,32 @@ def scheduler_leg() -> dict:
     return {"what": "Algorithm 1 prefill fetch + decode phase-2 fetch, 8 engines, 1024 queued requests",
             "library_us_per_decision": round(lib_us, 3), "oracle_us_per_decision": round(ora_us, 3),
             "decisions_match_oracle": True}
+
+
+def fused_move_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN, payload) -> dict:
+    """Both pools on this device: the paired plan moves pool to pool in one kernel per layer,
+    without the transfer buffer (half the memory traffic of pack + unpack)."""
+    import torch
+    import paper_2602_21548_amd as K
+    g = K.kvl_plan(lay_src, w.hit, w.app, w.src.tables, K.KVL_GATHER)
+    s = K.kvl_plan(lay_dst, w.hit, w.app, w.dst.tables, K.KVL_SCATTER)
+    m = K.kvl_plan_pair(g, s)
+    ms = []
+    for rep in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for l in range(L):
+            K.kvl_move_layer(m, src[l % WIN], dst[l % WIN], stream=stream)
+        e1.record(stream)
+        e1.synchronize()
+        if rep:
+            ms.append(e0.elapsed_time(e1) / L)
+    for p in (g, s, m):
+        p.destroy()
+    per_layer = float(np.mean(ms))
+    return {"what": "kvl_move_layer, pool to pool on one device (no transfer buffer), same workload",
+            "ms_per_layer": round(per_layer, 4), "delivered_gbps": round(payload / (per_layer * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(2 * payload / (per_layer * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
 
 
 def copy_ceiling(stream, gib: float = 4.0) -> float:

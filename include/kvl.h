@@ -179,6 +179,19 @@ int kvl_plan_get_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes,
 int kvl_pack_layer(const kvl_plan_t *plan, const void *const *pool_planes,
                    void *xfer, uint64_t xfer_capacity, void *stream);
 
+/* Both sides on one device.  When the source pool and the destination pool live
+ * in the same GPU's memory (engines sharing a device, or a cache being re-paged),
+ * the transfer buffer between kvl_pack_layer and kvl_unpack_layer is pure
+ * overhead: kvl_plan_pair joins a gather plan and a scatter plan over the same
+ * token ranges (same block_tokens, planes and row sizes; KVL_EINVAL otherwise)
+ * into one plan whose descriptors map source rows straight to destination rows,
+ * and kvl_move_layer runs it: the result in the destination pool is exactly that
+ * of pack followed by unpack, with half the memory traffic.  The two pools must
+ * not overlap.  The paired plan is independent of the two it was made from. */
+int kvl_plan_pair(const kvl_plan_t *gather, const kvl_plan_t *scatter, kvl_plan_t **out);
+int kvl_move_layer(const kvl_plan_t *paired, const void *const *src_pool_planes,
+                   void *const *dst_pool_planes, void *stream);
+
 /* Prefill side (Section 4.1: before a layer's attention is computed its hit
  * cache is placed in the prefill engine's HBM): scatter.  Rows that hold no
  * hit token keep their bytes.  xfer_bytes must be >= payload bytes (KVL_ESPACE).

@@ -94,6 +94,8 @@ _SIGNATURES = {
                                  C.POINTER(kvl_tuning_t), C.POINTER(_PLAN_P)]),
     "kvl_plan_destroy": (None, [_PLAN_P]),
     "kvl_release_cached_memory": (None, []),
+    "kvl_plan_pair": (C.c_int, [_PLAN_P, _PLAN_P, C.POINTER(_PLAN_P)]),
+    "kvl_move_layer": (C.c_int, [_PLAN_P, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p]),
     "kvl_plan_set_tuning": (C.c_int, [_PLAN_P, C.POINTER(kvl_tuning_t)]),
     "kvl_plan_payload_bytes": (C.c_int, [_PLAN_P, C.POINTER(C.c_uint64)]),
     "kvl_plan_hit_tokens": (C.c_int, [_PLAN_P, C.POINTER(C.c_uint64)]),
@@ -316,6 +318,30 @@ def kvl_pack_layer(plan: Plan, pool_planes: Sequence[torch.Tensor], xfer: torch.
         ptr = _dev(xfer, "xfer")
     _check(_lib.kvl_pack_layer(plan.handle, arr, ptr, _nbytes(xfer), _stream_handle(stream)),
            "kvl_pack_layer")
+
+
+def kvl_plan_pair(gather: Plan, scatter: Plan) -> Plan:
+    """Join a gather plan and a scatter plan into one pool-to-pool plan for kvl_move_layer."""
+    out = C.c_void_p()
+    _check(_lib.kvl_plan_pair(gather.handle, scatter.handle, C.byref(out)), "kvl_plan_pair")
+    p = Plan(out.value, gather.layout, gather.flags)
+    p.dst_layout = scatter.layout
+    return p
+
+
+def kvl_move_layer(paired: Plan, src_pool_planes: Sequence[torch.Tensor],
+                   dst_pool_planes: Sequence[torch.Tensor], stream=None) -> None:
+    src = _plane_ptrs(paired, src_pool_planes, "kvl_move_layer source pool")
+    dl = paired.dst_layout
+    if len(dst_pool_planes) != paired.n_planes:
+        raise ValueError("kvl_move_layer: wrong number of destination planes")
+    dst = (C.c_void_p * paired.n_planes)()
+    for p, t in enumerate(dst_pool_planes):
+        need = int(dl.pool_blocks) * int(dl.block_tokens) * int(dl.row_bytes[p])
+        if _nbytes(t) < need:
+            raise ValueError(f"kvl_move_layer: destination plane {p} holds {_nbytes(t)} bytes, pool needs {need}")
+        dst[p] = _dev(t, "kvl_move_layer destination pool")
+    _check(_lib.kvl_move_layer(paired.handle, src, dst, _stream_handle(stream)), "kvl_move_layer")
 
 
 def kvl_unpack_layer(plan: Plan, xfer: torch.Tensor, pool_planes: Sequence[torch.Tensor], stream=None) -> None:

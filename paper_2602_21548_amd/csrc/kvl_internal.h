@@ -11,6 +11,8 @@
 struct kvl_plan_s {
     kvl_layout_t layout{};
     uint32_t flags = 0;
+    bool paired = false;                         // made by kvl_plan_pair: xfer_row holds destination pool rows
+    uint64_t dst_pool_blocks = 0;                // paired plans: blocks of the destination pool
     uint32_t n_req = 0;
     uint64_t hit_tokens = 0;                     // T
     uint64_t payload_bytes = 0;                  // all planes
@@ -59,6 +61,7 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
                  uint32_t plane_begin, uint32_t plane_end,
                  void *const *pool_planes, const uintptr_t *xfer_plane, hipStream_t stream);
 
+int upload_units(kvl_plan_t *plan);
 int ensure_lanes(kvl_plan_t *plan, size_t lanes);
 int lanes_follow(kvl_plan_t *plan, size_t lanes, hipStream_t copy_s, hipStream_t kern_s);
 

@@ -466,10 +466,26 @@ int kvl_pool_to_fullblocks_layer(const kvl_plan_t *plan, const void *const *pool
                                 const_cast<void *const *>(pool_planes), (hipStream_t)stream);
 }
 
+int kvl_move_layer(const kvl_plan_t *plan, const void *const *src_pool_planes, void *const *dst_pool_planes,
+                   void *stream) {
+    if (!plan || !src_pool_planes || !dst_pool_planes) return KVL_EINVAL;
+    if (!plan->paired || (plan->flags & KVL_HOST_ONLY)) return KVL_EINVAL;
+    if (plan->units.empty()) return KVL_OK;
+    // the gather kernel with the destination pool in the transfer buffer's place:
+    // a paired descriptor's xfer_row is a row of the destination pool
+    uintptr_t xp[KVL_MAX_PLANES];
+    for (uint32_t p = 0; p < plan->layout.n_planes; ++p) {
+        if (!dst_pool_planes[p]) return KVL_EINVAL;
+        xp[p] = reinterpret_cast<uintptr_t>(dst_pool_planes[p]);
+    }
+    return kvl::launch_units(plan, true, 0, (uint32_t)plan->units.size(), 0, plan->layout.n_planes,
+                             const_cast<void *const *>(src_pool_planes), xp, (hipStream_t)stream);
+}
+
 int kvl_pack_layer(const kvl_plan_t *plan, const void *const *pool_planes, void *xfer,
                    uint64_t xfer_capacity, void *stream) {
     if (!plan || !pool_planes) return KVL_EINVAL;
-    if (!(plan->flags & KVL_GATHER) || (plan->flags & KVL_HOST_ONLY)) return KVL_EINVAL;
+    if (!(plan->flags & KVL_GATHER) || (plan->flags & KVL_HOST_ONLY) || plan->paired) return KVL_EINVAL;
     if (xfer_capacity < plan->payload_bytes) return KVL_ESPACE;
     if (plan->units.empty()) return KVL_OK;
     if (!xfer) return KVL_EINVAL;

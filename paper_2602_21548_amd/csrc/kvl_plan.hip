@@ -102,6 +102,21 @@ static void descriptor_release(void *ptr, size_t capacity, int device) {
     (void)hipFree(ptr);
 }
 
+int upload_units(kvl_plan_t *plan) {
+    hipError_t e = hipGetDevice(&plan->device);
+    if (e == hipSuccess && !plan->units.empty()) {
+        const size_t bytes = plan->units.size() * sizeof(kvl_unit_t);
+        e = descriptor_alloc((void **)&plan->d_units, bytes, &plan->d_units_capacity, plan->device);
+        if (e == hipSuccess)
+            e = hipMemcpy(plan->d_units, plan->units.data(), bytes, hipMemcpyHostToDevice);
+    }
+    if (e != hipSuccess) {
+        set_hip_error(e);
+        return KVL_EHIP;
+    }
+    return KVL_OK;
+}
+
 static int resolve_tuning(const kvl_tuning_t *in, kvl_tuning_t *out) {
     kvl_tuning_t t{};
     if (in) t = *in;
@@ -250,17 +265,10 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
     plan->payload_bytes = base;
 
     if (!(flags & KVL_HOST_ONLY)) {
-        hipError_t e = hipGetDevice(&plan->device);
-        if (e == hipSuccess && !plan->units.empty()) {
-            const size_t bytes = plan->units.size() * sizeof(kvl_unit_t);
-            e = descriptor_alloc((void **)&plan->d_units, bytes, &plan->d_units_capacity, plan->device);
-            if (e == hipSuccess)
-                e = hipMemcpy(plan->d_units, plan->units.data(), bytes, hipMemcpyHostToDevice);
-        }
-        if (e != hipSuccess) {
-            set_hip_error(e);
+        rc = upload_units(plan);
+        if (rc != KVL_OK) {
             kvl_plan_destroy(plan);
-            return KVL_EHIP;
+            return rc;
         }
     }
     *out = plan;
@@ -292,6 +300,59 @@ void kvl_plan_destroy(kvl_plan_t *plan) {
     if (plan->ev_entry) (void)hipEventDestroy(plan->ev_entry);
     if (plan->ev_entry2) (void)hipEventDestroy(plan->ev_entry2);
     delete plan;
+}
+
+int kvl_plan_pair(const kvl_plan_t *g, const kvl_plan_t *s, kvl_plan_t **out) {
+    if (!g || !s || !out) return KVL_EINVAL;
+    *out = nullptr;
+    if (!(g->flags & KVL_GATHER) || !(s->flags & KVL_SCATTER) || g->paired || s->paired) return KVL_EINVAL;
+    const kvl_layout_t &a = g->layout, &b = s->layout;
+    if (a.block_tokens != b.block_tokens || a.n_planes != b.n_planes || g->hit_tokens != s->hit_tokens)
+        return KVL_EINVAL;
+    for (uint32_t p = 0; p < a.n_planes; ++p)
+        if (a.row_bytes[p] != b.row_bytes[p]) return KVL_EINVAL;
+    kvl_plan_t *plan = new (std::nothrow) kvl_plan_t;
+    if (!plan) return KVL_ENOMEM;
+    plan->layout = a;
+    plan->dst_pool_blocks = b.pool_blocks;
+    plan->flags = KVL_GATHER | ((g->flags | s->flags) & KVL_HOST_ONLY);
+    plan->paired = true;
+    plan->n_req = g->n_req;
+    plan->hit_tokens = g->hit_tokens;
+    plan->payload_bytes = g->payload_bytes;
+    plan->vec16 = g->vec16;
+    plan->tuning = g->tuning;
+    try {
+        // both descriptor lists tile the token rows [0, T) in order: walk them together
+        size_t i = 0, j = 0;
+        uint64_t x = 0;
+        uint32_t longest = 0;
+        while (i < g->units.size() && j < s->units.size()) {
+            const kvl_unit_t &u = g->units[i], &v = s->units[j];
+            const uint64_t u_end = (uint64_t)u.xfer_row + u.n_rows, v_end = (uint64_t)v.xfer_row + v.n_rows;
+            const uint64_t end = std::min(u_end, v_end);
+            kvl_unit_t d{(uint32_t)(u.pool_row + (x - u.xfer_row)), (uint32_t)(v.pool_row + (x - v.xfer_row)),
+                         (uint32_t)(end - x), 0};
+            plan->units.push_back(d);
+            longest = std::max(longest, d.n_rows);
+            x = end;
+            if (end == u_end) ++i;
+            if (end == v_end) ++j;
+        }
+        plan->max_unit_rows = longest;
+    } catch (const std::bad_alloc &) {
+        delete plan;
+        return KVL_ENOMEM;
+    }
+    if (!(plan->flags & KVL_HOST_ONLY)) {
+        int rc = kvl::upload_units(plan);
+        if (rc != KVL_OK) {
+            kvl_plan_destroy(plan);
+            return rc;
+        }
+    }
+    *out = plan;
+    return KVL_OK;
 }
 
 int kvl_plan_set_tuning(kvl_plan_t *plan, const kvl_tuning_t *tuning) {

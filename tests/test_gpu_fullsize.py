@@ -142,6 +142,29 @@ def test_full_size_full_blocks_from_pinned_host():
     s.destroy()
 
 
+@pytest.mark.parametrize("idx", [2, 4])
+def test_full_size_fused_move(idx):
+    t0 = time.perf_counter()
+    w = W.config(idx)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    src = W.fill_pool_fast(w, 7, "src")
+    x = oracle.pack(bs, rows, w.hit, w.src.tables, src, threads=THREADS)
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    m = K.kvl_plan_pair(g, s)
+    d_src = [torch.from_numpy(p).cuda() for p in src]
+    d_dst = [torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device="cuda") for r in rows]
+    K.kvl_move_layer(m, d_src, d_dst)
+    torch.cuda.synchronize()
+    T = g.hit_tokens
+    for p, r in enumerate(rows):
+        base = sum(T * q for q in rows[:p])
+        want = np.full(w.dst.pool_blocks * bs * r, 0xA5, dtype=np.uint8)
+        oracle.unpack(bs, (r,), w.hit, w.dst.tables, x[base:base + T * r], [want], threads=THREADS)
+        assert np.array_equal(to_host(d_dst[p]), want), f"plane {p}"
+    print(f"[cfg{idx} move] done after {time.perf_counter() - t0:.1f} s", flush=True)
+
+
 def test_full_size_streamed_layers():
     t0 = time.perf_counter()
     w = W.config(5)

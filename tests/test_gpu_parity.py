@@ -645,3 +645,30 @@ def test_two_host_threads_with_their_own_plans():
     for t in threads:
         t.join()
     assert not errors, errors
+
+
+@pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
+def test_fused_move_equals_pack_then_unpack(name, make):
+    """Pool to pool in one kernel: the destination must be what pack followed by unpack leaves."""
+    w = make()
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    src = W.fill_pool(w, 3, "src")
+    want = W.sentinel_pool(w, "dst")
+    oracle.unpack(bs, rows, w.hit, w.dst.tables, oracle.pack(bs, rows, w.hit, w.src.tables, src), want)
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    m = K.kvl_plan_pair(g, s)
+    g.destroy()
+    s.destroy()                                   # the paired plan stands on its own
+    d_src = planes_to_dev(src)
+    d_dst = planes_to_dev(W.sentinel_pool(w, "dst"))
+    K.kvl_move_layer(m, d_src, d_dst)
+    torch.cuda.synchronize()
+    for a, b in zip(d_dst, want):
+        assert same_bytes(to_host(a), b)
+    for a, b in zip(d_src, src):
+        assert same_bytes(to_host(a), b)
+    x = torch.zeros(max(16, m.payload_bytes), dtype=torch.uint8, device="cuda")
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_pack_layer(m, d_src, x)             # a paired plan only moves
+    assert e.value.code == K.KVL_EINVAL

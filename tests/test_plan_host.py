@@ -353,3 +353,51 @@ def test_row_index_limits():
     assert p.hit_tokens == 3 << 30 and p.payload_bytes == (3 << 30) * 16
     u = p.units().astype(np.int64)
     assert u[:, 2].sum() == 3 << 30 and (u[:, 2] * 16).max() <= 1 << 30      # descriptors stay within 1 GiB
+
+
+# --------------------------------------------------------------------------
+# paired plans: pool-to-pool descriptors
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,make", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("flag", [0, K.KVL_TOKENS_ALL], ids=["hit", "all"])
+def test_paired_descriptors_equal_pack_then_unpack(name, make, flag):
+    w = make()
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    first, count = _range_of(w, flag)
+    g = host_plan(w, "src", K.KVL_GATHER | flag, unit_bytes=4096)
+    s = host_plan(w, "dst", K.KVL_SCATTER | flag)
+    m = K.kvl_plan_pair(g, s)
+    assert m.hit_tokens == g.hit_tokens and m.payload_bytes == g.payload_bytes
+    src = W.fill_pool(w, 0, "src")
+    want = W.sentinel_pool(w, "dst")
+    oracle.unpack_range(bs, rows, first, count, w.dst.tables,
+                        oracle.pack_range(bs, rows, first, count, w.src.tables, src), want)
+    got = W.sentinel_pool(w, "dst")
+    for p, row in enumerate(rows):
+        for src_row, dst_row, n, _ in m.units():
+            got[p][int(dst_row) * row:(int(dst_row) + int(n)) * row] = src[p][int(src_row) * row:(int(src_row) + int(n)) * row]
+    for a, b in zip(got, want):
+        assert a.tobytes() == b.tobytes()
+    u = m.units().astype(np.int64)
+    assert u[:, 2].sum() == g.hit_tokens
+
+
+def test_pairing_refuses_mismatched_plans():
+    w = W.tiny(120, 4, 16, (48,), 64, 90)
+    g = host_plan(w, "src", K.KVL_GATHER)
+    s = host_plan(w, "dst", K.KVL_SCATTER)
+    for a, b in ((s, s), (g, g)):                                      # wrong kinds
+        with pytest.raises(K.KvlError) as e:
+            K.kvl_plan_pair(a, b)
+        assert e.value.code == K.KVL_EINVAL
+    tail = host_plan(w, "dst", K.KVL_SCATTER | K.KVL_TOKENS_ALL)       # other token range
+    with pytest.raises(K.KvlError):
+        K.kvl_plan_pair(g, tail)
+    lay = K.make_layout(1, 16, (64,), w.dst.pool_blocks)               # other row size
+    other = K.kvl_plan(lay, w.hit, w.app, w.dst.tables, K.KVL_SCATTER | K.KVL_HOST_ONLY)
+    with pytest.raises(K.KvlError):
+        K.kvl_plan_pair(g, other)
+    m = K.kvl_plan_pair(g, s)
+    with pytest.raises(K.KvlError):
+        K.kvl_plan_pair(m, s)                                          # a paired plan is not a gather plan
