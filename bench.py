@@ -46,7 +46,7 @@ def log(*a):
 
 def kernel_source_hash() -> str:
     h = hashlib.sha256()
-    for f in ("kvl_kernels.hip",):
+    for f in ("kvl_copy_kernels.h",):
         h.update(open(os.path.join(ROOT, "paper_2602_21548_amd", "csrc", f), "rb").read())
     return h.hexdigest()[:16]
 

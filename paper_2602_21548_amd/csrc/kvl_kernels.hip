@@ -1,270 +1,17 @@
-// Device side of pack / unpack: copy kernels for gfx950 and their launchers.
-//
-// The work is pure data movement (no arithmetic on the payload).  A copy
-// descriptor names a span of token rows that is contiguous in the paged pool and
-// in the transfer buffer, so each descriptor is a straight 16-byte-vector copy;
-// what the block table fragments is only where each span starts.  The kernels
-// therefore read a descriptor (wave-uniform, through the scalar cache), form two
-// 64-bit addresses and stream the span with several 16-byte loads in flight per
-// lane before the matching stores.  Consecutive lanes touch consecutive 16-byte
-// vectors, so every wavefront load or store covers 1 KiB of contiguous memory.
-//
-// kvl_tuning_t::variant is 0 for the default below, else 1 + code with
-// code = mode | ntl << 2 | sp << 3 | deep << 5 | noalign << 6:
-//   mode 0  one workgroup per descriptor, each lane loops over the span
-//   mode 1  one wavefront per descriptor, each lane loops over the span
-//   mode 2  tiled: a descriptor is cut into tiles of blockDim vectors and every
-//           lane moves exactly one 16-byte vector
-//   mode 3  tiled, two vectors per lane
-//   ntl     non-temporal loads
-//   sp      store cache policy: 0 plain, 1 nt, 2 sc1, 3 sc1 nt
-//   deep    modes 0-1: 8 instead of 4 vectors in flight per lane
-//   noalign modes 2-3: do not line tiles up with the destination's 128-byte lines
-//           (they are lined up by default whenever the rows are not multiples of 128 bytes)
-// Measured on MI355X (5.2 GB of 72 KiB blocks in random order), the tiled form
-// with one vector per lane and 256-lane workgroups is the fastest: it leaves no
-// dependency between a lane's memory operations and lets the hardware fill the
-// memory system with resident wavefronts.  Cache policies, measured with gather
-// and scatter alternating as they do in use: the gather (random reads,
-// sequential writes) runs best with non-temporal loads and sc1 stores; the
-// scatter (sequential reads, random writes) with sc1+nt stores, and with
-// non-temporal loads only if the rows are multiples of 128 bytes (otherwise
-// neighbouring wavefronts share source lines, and a non-temporal load fetches
-// the shared line twice).  Together the policies are worth 5-15 % over plain
-// loads and stores.  With rows that are not multiples of 128 bytes the tiles are
-// also lined up with the destination's cache lines (worth 5-9 % on 656-byte rows).
+// Launchers of the copy kernels and the entry points built on them (pack, unpack, move,
+// storage layout, plain copy).  The kernels themselves are in kvl_copy_kernels.h.
 #include <algorithm>
 #include <cstdio>
 
-#include "kvl_internal.h"
+#include "kvl_copy_kernels.h"
 
 namespace kvl {
-
-// default variant codes (see the list above) and the plain copy's policies
-constexpr uint32_t kDefaultPackCode = 2u | 4u | (2u << 3);   // tile x1, nt loads, sc1 stores
-constexpr uint32_t kDefaultUnpackCode = 2u | 4u | (3u << 3);    // tile x1, nt loads, sc1+nt stores
-constexpr uint32_t kDefaultUnpackCodeOddRows = 2u | (3u << 3);  // tile x1, plain loads, sc1+nt stores
-constexpr bool kLinearNtLoad = true;
-constexpr int kLinearStorePolicy = 2;
-
-typedef uint32_t v4u __attribute__((ext_vector_type(4)));
-// Every buffer is device (or device-mapped) memory: say so, so that the
-// compiler emits global_load / global_store rather than flat accesses.
-typedef const v4u __attribute__((address_space(1))) *gsrc_t;
-typedef v4u __attribute__((address_space(1))) *gdst_t;
-
-struct CopyArgs {
-    const kvl_unit_t *units;       // device descriptors
-    uint32_t unit_begin;           // first descriptor of this launch
-    uint32_t n_units;              // descriptors in this launch
-    uint32_t plane_begin;          // blockIdx.y + plane_begin is the plane
-    uint32_t row_elems[KVL_MAX_PLANES];  // row size in 16-byte vectors (vector kernels) or bytes
-    uintptr_t pool[KVL_MAX_PLANES];      // plane base of the paged pool
-    uintptr_t xfer[KVL_MAX_PLANES];      // address of transfer row 0 of the plane
-};
 
 // The descriptors live on the device that was current when the plan was made.
 static int check_device(const kvl_plan_t *plan) {
     int dev = -1;
     KVL_HIP(hipGetDevice(&dev));
     return dev == plan->device ? KVL_OK : KVL_EINVAL;
-}
-
-template <bool NT>
-__device__ __forceinline__ v4u load16(gsrc_t p) {
-    if (NT) return __builtin_nontemporal_load(p);
-    return *p;
-}
-
-// Store with a cache policy.  The compiler only offers the non-temporal hint;
-// the system-scope write-through forms (sc1) are written out as instructions.
-// A store needs no wait: nothing here reads what it wrote.
-template <int SP>
-__device__ __forceinline__ void store16(gdst_t p, v4u v) {
-    if (SP == 0) *p = v;
-    else if (SP == 1) __builtin_nontemporal_store(v, p);
-    else if (SP == 2) asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
-    else asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
-}
-
-// `lanes` threads copy n 16-byte vectors; this thread is `lane`.  U loads are
-// issued before the first store so that U KiB per wavefront are in flight.
-template <int U, bool NTL, int SP>
-__device__ __forceinline__ void copy_span(gsrc_t __restrict__ src, gdst_t __restrict__ dst,
-                                          uint32_t n, uint32_t lane, uint32_t lanes) {
-    // n is below 2^32: a descriptor never spans more than 1 GiB
-    const uint32_t step = lanes * U;
-    const uint32_t last = lanes * (U - 1);
-    uint32_t i = lane;
-    // no division: a lane takes a full step while its last vector is in range
-    for (; (uint64_t)i + last < n; i += step) {
-        v4u v[U];
-#pragma unroll
-        for (int k = 0; k < U; ++k) v[k] = load16<NTL>(src + i + k * lanes);
-#pragma unroll
-        for (int k = 0; k < U; ++k) store16<SP>(dst + i + k * lanes, v[k]);
-    }
-    // ragged tail: this lane has at most U-1 vectors left
-    v4u v[U];
-#pragma unroll
-    for (int k = 0; k < U - 1; ++k) {
-        const uint64_t j = (uint64_t)i + (uint64_t)k * lanes;
-        if (j < n) v[k] = load16<NTL>(src + j);
-    }
-#pragma unroll
-    for (int k = 0; k < U - 1; ++k) {
-        const uint64_t j = (uint64_t)i + (uint64_t)k * lanes;
-        if (j < n) store16<SP>(dst + j, v[k]);
-    }
-}
-
-template <bool PACK, bool WAVE, int U, bool NTL, int SP>
-__device__ __forceinline__ void units_body(const CopyArgs &a) {
-    uint32_t u_idx, lane, lanes;
-    if (WAVE) {
-        const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        u_idx = blockIdx.x * (blockDim.x >> 6) + wave;
-        lane = threadIdx.x & 63u;
-        lanes = 64;
-    } else {
-        u_idx = blockIdx.x;
-        lane = threadIdx.x;
-        lanes = blockDim.x;
-    }
-    if (u_idx >= a.n_units) return;
-    const kvl_unit_t u = a.units[a.unit_begin + u_idx];
-    const uint32_t p = a.plane_begin + blockIdx.y;
-    const uint64_t row = a.row_elems[p];
-    const uintptr_t pool = a.pool[p] + (uint64_t)u.pool_row * row * 16u;
-    const uintptr_t xfer = a.xfer[p] + (uint64_t)u.xfer_row * row * 16u;
-    const uint32_t n = u.n_rows * (uint32_t)row;
-    if (PACK) copy_span<U, NTL, SP>((gsrc_t)pool, (gdst_t)xfer, n, lane, lanes);
-    else copy_span<U, NTL, SP>((gsrc_t)xfer, (gdst_t)pool, n, lane, lanes);
-}
-
-// gather: paged pool -> transfer buffer
-template <bool WAVE, int U, bool NTL, int SP>
-__global__ void __launch_bounds__(1024) kvl_pack_kernel(const CopyArgs a) {
-    units_body<true, WAVE, U, NTL, SP>(a);
-}
-
-// scatter: transfer buffer -> paged pool
-template <bool WAVE, int U, bool NTL, int SP>
-__global__ void __launch_bounds__(1024) kvl_unpack_kernel(const CopyArgs a) {
-    units_body<false, WAVE, U, NTL, SP>(a);
-}
-
-// Tiled form: the grid is (descriptors x tiles_per_unit, planes); a workgroup
-// takes tile `t` of its descriptor and each lane moves VPT vectors.  With one
-// vector per lane there is no loop and no dependency between a lane's memory
-// operations: the hardware keeps the memory system busy by the sheer number of
-// resident wavefronts rather than by unrolling.
-template <bool PACK, int VPT, bool NTL, int SP>
-__device__ __forceinline__ void tile_body(const CopyArgs &a, uint32_t tiles_per_unit, uint32_t align_dst) {
-    const uint32_t u_idx = blockIdx.x / tiles_per_unit;
-    const uint32_t tile = blockIdx.x - u_idx * tiles_per_unit;
-    const kvl_unit_t u = a.units[a.unit_begin + u_idx];
-    const uint32_t p = a.plane_begin + blockIdx.y;
-    const uint32_t row = a.row_elems[p];
-    const uint32_t n = u.n_rows * row;
-    const uintptr_t pool = a.pool[p] + (uint64_t)u.pool_row * row * 16u;
-    const uintptr_t xfer = a.xfer[p] + (uint64_t)u.xfer_row * row * 16u;
-    gsrc_t src = (gsrc_t)(PACK ? pool : xfer);
-    gdst_t dst = (gdst_t)(PACK ? xfer : pool);
-    // With rows that are not multiples of 128 bytes a span starts anywhere in a
-    // cache line.  Tiles are then laid from the 128-byte boundary below the
-    // span's first destination byte, so that every wavefront's store covers
-    // whole lines (its load may straddle them, which costs far less): the first
-    // `lead` lanes of the first tile idle.
-    const uint32_t lead = align_dst ? ((uint32_t)((PACK ? xfer : pool) >> 4) & 7u) : 0u;
-    const uint32_t first = tile * (blockDim.x * VPT);
-    if (first >= n + lead) return;
-    v4u v[VPT];
-#pragma unroll
-    for (int k = 0; k < VPT; ++k) {
-        const uint32_t pos = first + k * blockDim.x + threadIdx.x;
-        if (pos >= lead && pos - lead < n) v[k] = load16<NTL>(src + (pos - lead));
-    }
-#pragma unroll
-    for (int k = 0; k < VPT; ++k) {
-        const uint32_t pos = first + k * blockDim.x + threadIdx.x;
-        if (pos >= lead && pos - lead < n) store16<SP>(dst + (pos - lead), v[k]);
-    }
-}
-
-template <int VPT, bool NTL, int SP>
-__global__ void __launch_bounds__(1024) kvl_pack_tile_kernel(const CopyArgs a, uint32_t tiles_per_unit,
-                                                             uint32_t align_dst) {
-    tile_body<true, VPT, NTL, SP>(a, tiles_per_unit, align_dst);
-}
-
-template <int VPT, bool NTL, int SP>
-__global__ void __launch_bounds__(1024) kvl_unpack_tile_kernel(const CopyArgs a, uint32_t tiles_per_unit,
-                                                               uint32_t align_dst) {
-    tile_body<false, VPT, NTL, SP>(a, tiles_per_unit, align_dst);
-}
-
-// Fallback for row sizes or addresses that are not multiples of 16 bytes: one
-// workgroup per descriptor, byte by byte.  Correct for any layout, not fast.
-template <bool PACK>
-__global__ void __launch_bounds__(1024) kvl_bytes_kernel(const CopyArgs a) {
-    const kvl_unit_t u = a.units[a.unit_begin + blockIdx.x];
-    const uint32_t p = a.plane_begin + blockIdx.y;
-    const uint64_t row = a.row_elems[p];
-    uint8_t *pool = reinterpret_cast<uint8_t *>(a.pool[p]) + (uint64_t)u.pool_row * row;
-    uint8_t *xfer = reinterpret_cast<uint8_t *>(a.xfer[p]) + (uint64_t)u.xfer_row * row;
-    const uint64_t n = (uint64_t)u.n_rows * row;
-    for (uint64_t i = threadIdx.x; i < n; i += blockDim.x) {
-        if (PACK) xfer[i] = pool[i];
-        else pool[i] = xfer[i];
-    }
-}
-
-// Storage layout <-> paged pool for one layer.  Same tiling as above; the far
-// side is a buffer of Full Blocks ([layer, tokens, bytes] per block), so a
-// descriptor (which never spans blocks here) lands at
-//   block_index * FB + (layer, plane) offset + row-in-block * row.
-// The buffer may be pinned host memory: then these accesses cross the host link.
-struct FullBlockArgs {
-    const kvl_unit_t *units;
-    uint32_t n_units;
-    uint32_t block_tokens;
-    uint32_t row_elems[KVL_MAX_PLANES];       // 16-byte vectors (VEC) or bytes per row
-    uintptr_t pool[KVL_MAX_PLANES];
-    uintptr_t blocks;                          // base of the Full-Block buffer
-    uint64_t fb_elems;                         // elements per Full Block
-    uint64_t layer_plane_off[KVL_MAX_PLANES];  // element offset of (layer, plane) inside a Full Block
-};
-
-template <bool TO_POOL, bool VEC>
-__global__ void __launch_bounds__(256) kvl_fullblock_kernel(const FullBlockArgs a, uint32_t tiles_per_unit) {
-    const uint32_t u_idx = blockIdx.x / tiles_per_unit;
-    const uint32_t tile = blockIdx.x - u_idx * tiles_per_unit;
-    const kvl_unit_t u = a.units[u_idx];
-    const uint32_t p = blockIdx.y;
-    const uint32_t row = a.row_elems[p];
-    const uint32_t n = u.n_rows * row;
-    const uint32_t i = tile * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const uint32_t within = u.pool_row % a.block_tokens;
-    const uint64_t in_pool = (uint64_t)u.pool_row * row + i;
-    const uint64_t in_blocks = (uint64_t)u.block_index * a.fb_elems + a.layer_plane_off[p] +
-                               (uint64_t)within * row + i;
-    if (VEC) {
-        if (TO_POOL) store16<3>((gdst_t)a.pool[p] + in_pool, load16<false>((gsrc_t)a.blocks + in_blocks));
-        else store16<0>((gdst_t)a.blocks + in_blocks, load16<true>((gsrc_t)a.pool[p] + in_pool));
-    } else {
-        uint8_t *pool = reinterpret_cast<uint8_t *>(a.pool[p]);
-        uint8_t *blocks = reinterpret_cast<uint8_t *>(a.blocks);
-        if (TO_POOL) pool[in_pool] = blocks[in_blocks];
-        else blocks[in_blocks] = pool[in_pool];
-    }
-}
-
-// Straight copy, one vector per lane: the tiled kernel without descriptors.
-__global__ void __launch_bounds__(256) kvl_linear_kernel(const v4u *src, v4u *dst, uint64_t n) {
-    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) store16<kLinearStorePolicy>((gdst_t)dst + i, load16<kLinearNtLoad>((gsrc_t)src + i));
 }
 
 template <bool PACK, bool WAVE, int U, bool NTL, int SP>
