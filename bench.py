@@ -117,7 +117,7 @@ def main() -> int:
     if args.only_steps:
         args.skip_host_link = args.skip_cpu = args.skip_other_configs = True
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 "
+        print("bench.py: the library runs on one GPU; --gpus must be 1 "
               "(the load path shards by request across GPUs without any collective)", file=sys.stderr)
         return 2
 

@@ -15,8 +15,8 @@ moment it is made, token counts are conserved, Z is the stated formula) and by
 an independent event-driven simulation on small cases -- parity with the paper's
 own implementation is unpinned.
 
-Readings: Algorithm 1 classifies the engines once per fetch, before the loop, as
-its listing does; ties go to the lowest index; tokens(r) is the request's total
+Readings: Algorithm 1 classifies the engines once per fetch, before the loop (the
+algorithm states the classification ahead of the loop); ties go to the lowest index; tokens(r) is the request's total
 length; phase 1 adds a request's length to its group's sum at once; HBM need and
 free HBM are counted in tokens.
 """

@@ -1,4 +1,4 @@
-"""Submission-cost study for the host-buffer load path (run on a GPU machine):
+"""Submission-cost study for the host-buffer load path (needs an MI355X):
 
     python -m paper_2602_21548_amd.h2d_study [--requests N]
 
