@@ -672,3 +672,29 @@ def test_fused_move_equals_pack_then_unpack(name, make):
     with pytest.raises(K.KvlError) as e:
         K.kvl_pack_layer(m, d_src, x)             # a paired plan only moves
     assert e.value.code == K.KVL_EINVAL
+
+
+def test_plans_do_not_leak_device_memory():
+    w = W.config(3, n_requests=12, token_scale=1 / 16)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    host = torch.zeros(oracle.payload_bytes(w.hit, rows), dtype=torch.uint8, pin_memory=True)
+    pool = planes_to_dev(W.sentinel_pool(w, "dst"))
+    staging = torch.zeros(4 << 20, dtype=torch.uint8, device="cuda")
+    cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def cycle():
+        s = dev_plan(w, "dst", K.KVL_SCATTER, unit_bytes=16384)
+        K.kvl_h2d_unpack_layer(s, host, staging, 1 << 20, pool, cs, ks)      # creates the plan's lanes
+        ks.synchronize()
+        s.destroy()
+
+    for _ in range(20):
+        cycle()
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(300):
+        cycle()
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < (8 << 20), f"{(free0 - free1) >> 20} MiB of device memory gone after 300 plans"
+    K.kvl_release_cached_memory()
