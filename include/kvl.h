@@ -75,6 +75,7 @@ extern "C" {
 #define KVL_HOST_ONLY  4u  /* make descriptors on the host only (no device is touched);
                               such a plan can be inspected but not executed */
 #define KVL_NO_MERGE   8u  /* do not merge physically adjacent blocks into one run */
+#define KVL_NO_POINTER_CHECKS 64u  /* skip kvl_check_buffer on every call made with this plan */
 /* Which token rows of each request the plan moves.  Default: the hit prefix
  * [0, hit).  The other two serve the step after a layer's computation
  * (Section 4.1): the decode-engine read path sends on only the miss tokens'
@@ -340,6 +341,15 @@ int kvl_measure_h2d_peak(const void *pinned_host, void *dev, uint64_t bytes, uin
  * gather with perfect locality could reach, and the known-size kernel used to
  * calibrate HBM byte counters. */
 int kvl_copy_linear(const void *src, void *dst, uint64_t bytes, void *stream);
+
+/* What every entry point asks of a buffer before a kernel may touch it: is
+ * [ptr, ptr + bytes) memory this device can address?  Device allocations are
+ * checked against their extent (KVL_ESPACE if the span runs past it); host memory
+ * passes only if allow_host is non-zero and it is pinned and mapped (pageable host
+ * memory and stray pointers give KVL_EINVAL).  A wrong pointer thus comes back as
+ * an error code instead of a memory fault on the GPU.  Costs a few microseconds
+ * per buffer; a plan made with KVL_NO_POINTER_CHECKS skips it. */
+int kvl_check_buffer(const void *ptr, uint64_t bytes, int allow_host);
 
 const char *kvl_strerror(int code);
 /* hipError_t of the last KVL_EHIP on this thread, and its text. */

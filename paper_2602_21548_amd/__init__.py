@@ -12,7 +12,7 @@ _EXPORTS = (
     "kvl_strerror", "kvl_release_cached_memory", "kvl_variant_name", "kvl_version", "LIB_PATH",
     "KVL_OK", "KVL_EINVAL", "KVL_ERANGE", "KVL_EALIAS", "KVL_ESPACE", "KVL_EHIP", "KVL_ENOMEM",
     "KVL_GATHER", "KVL_SCATTER", "KVL_HOST_ONLY", "KVL_NO_MERGE", "KVL_MAX_PLANES",
-    "KVL_TOKENS_APPEND", "KVL_TOKENS_ALL",
+    "KVL_TOKENS_APPEND", "KVL_TOKENS_ALL", "KVL_NO_POINTER_CHECKS", "kvl_check_buffer",
 )
 __all__ = list(_EXPORTS)
 

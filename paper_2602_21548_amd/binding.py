@@ -22,6 +22,7 @@ KVL_MAX_PLANES = 4
 KVL_OK, KVL_EINVAL, KVL_ERANGE, KVL_EALIAS, KVL_ESPACE, KVL_EHIP, KVL_ENOMEM = 0, -1, -2, -3, -4, -5, -6
 KVL_GATHER, KVL_SCATTER, KVL_HOST_ONLY, KVL_NO_MERGE = 1, 2, 4, 8
 KVL_TOKENS_APPEND, KVL_TOKENS_ALL = 16, 32
+KVL_NO_POINTER_CHECKS = 64
 
 
 class KvlError(RuntimeError):
@@ -119,6 +120,7 @@ _SIGNATURES = {
     "kvl_measure_h2d_peak": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p,
                                        C.POINTER(C.c_double)]),
     "kvl_copy_linear": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
+    "kvl_check_buffer": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int]),
     "kvl_strerror": (C.c_char_p, [C.c_int]),
     "kvl_last_hip_error": (C.c_int, []),
     "kvl_last_hip_error_string": (C.c_char_p, []),
@@ -511,6 +513,11 @@ def kvl_copy_linear(src: torch.Tensor, dst: torch.Tensor, stream=None) -> None:
     if _nbytes(dst) < n:
         raise ValueError("dst smaller than src")
     _check(_lib.kvl_copy_linear(_dev(src, "src"), _dev(dst, "dst"), n, _stream_handle(stream)), "kvl_copy_linear")
+
+
+def kvl_check_buffer(ptr: int, nbytes: int, allow_host: bool = False) -> int:
+    """The library's own buffer check on a raw address; returns a KVL_* code."""
+    return int(_lib.kvl_check_buffer(ptr, nbytes, int(allow_host)))
 
 
 def kvl_release_cached_memory() -> None:

@@ -127,6 +127,10 @@ static int h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xf
     if (rc != KVL_OK) return rc;
     if (!pool_planes) return KVL_EINVAL;
     if (plan->units.empty()) return KVL_OK;
+    rc = kvl::check_pool(plan, pool_planes, plan->layout.pool_blocks);
+    if (rc == KVL_OK) rc = kvl::check_buffer(plan, pinned_host_xfer, plan->payload_bytes, true);
+    if (rc == KVL_OK && chunk_bytes) rc = kvl::check_buffer(plan, dev_staging, slots * chunk_bytes, false);
+    if (rc != KVL_OK) return rc;
     if (chunk_bytes == 0)
         return kvl::enqueue_zero_copy_layer(plan, pinned_host_xfer, pool_planes, (hipStream_t)kernel_stream, nullptr);
     std::vector<kvl_chunk_t> chunks;
@@ -179,6 +183,9 @@ int kvl_h2d_blockwise_layer(const kvl_plan_t *plan, const void *pinned_host_xfer
     if (n_copies) *n_copies = 0;
     if (plan->units.empty()) return KVL_OK;
     if (!pinned_host_xfer) return KVL_EINVAL;
+    int rc = kvl::check_pool(plan, pool_planes, plan->layout.pool_blocks);
+    if (rc == KVL_OK) rc = kvl::check_buffer(plan, pinned_host_xfer, plan->payload_bytes, true);
+    if (rc != KVL_OK) return rc;
     const char *host = static_cast<const char *>(pinned_host_xfer);
     uint64_t copies = 0;
     for (uint32_t p = 0; p < plan->layout.n_planes; ++p) {

@@ -62,6 +62,9 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
                  void *const *pool_planes, const uintptr_t *xfer_plane, hipStream_t stream);
 
 int upload_units(kvl_plan_t *plan);
+// kvl_check_buffer unless the plan opted out
+int check_buffer(const kvl_plan_t *plan, const void *ptr, uint64_t bytes, bool allow_host);
+int check_pool(const kvl_plan_t *plan, const void *const *planes, uint64_t pool_blocks);
 int ensure_lanes(kvl_plan_t *plan, size_t lanes);
 int lanes_follow(kvl_plan_t *plan, size_t lanes, hipStream_t copy_s, hipStream_t kern_s);
 

@@ -7,6 +7,17 @@
 
 namespace kvl {
 
+// Every plane of a pool must be device-addressable memory of the pool's full size.
+int check_pool(const kvl_plan_t *plan, const void *const *planes, uint64_t pool_blocks) {
+    for (uint32_t p = 0; p < plan->layout.n_planes; ++p) {
+        if (!planes[p]) return KVL_EINVAL;
+        const uint64_t bytes = pool_blocks * plan->layout.block_tokens * (uint64_t)plan->layout.row_bytes[p];
+        int rc = check_buffer(plan, planes[p], bytes, false);
+        if (rc != KVL_OK) return rc;
+    }
+    return KVL_OK;
+}
+
 // The descriptors live on the device that was current when the plan was made.
 static int check_device(const kvl_plan_t *plan) {
     int dev = -1;
@@ -159,6 +170,9 @@ int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint
     if (plan->units.empty()) return KVL_OK;
     if (!blocks) return KVL_EINVAL;
     int rc_dev = check_device(plan);
+    if (rc_dev == KVL_OK) rc_dev = check_pool(plan, pool_planes, plan->layout.pool_blocks);
+    if (rc_dev == KVL_OK)
+        rc_dev = check_buffer(plan, reinterpret_cast<const void *>(blocks), plan->blocks_touched * fb, true);
     if (rc_dev != KVL_OK) return rc_dev;
     bool vec = plan->vec16 && blocks % 16 == 0;
     for (uint32_t p = 0; p < P; ++p) {
@@ -218,6 +232,9 @@ int kvl_move_layer(const kvl_plan_t *plan, const void *const *src_pool_planes, v
     if (!plan || !src_pool_planes || !dst_pool_planes) return KVL_EINVAL;
     if (!plan->paired || (plan->flags & KVL_HOST_ONLY)) return KVL_EINVAL;
     if (plan->units.empty()) return KVL_OK;
+    int rc = kvl::check_pool(plan, src_pool_planes, plan->layout.pool_blocks);
+    if (rc == KVL_OK) rc = kvl::check_pool(plan, dst_pool_planes, plan->dst_pool_blocks);
+    if (rc != KVL_OK) return rc;
     // the gather kernel with the destination pool in the transfer buffer's place:
     // a paired descriptor's xfer_row is a row of the destination pool
     uintptr_t xp[KVL_MAX_PLANES];
@@ -236,6 +253,9 @@ int kvl_pack_layer(const kvl_plan_t *plan, const void *const *pool_planes, void 
     if (xfer_capacity < plan->payload_bytes) return KVL_ESPACE;
     if (plan->units.empty()) return KVL_OK;
     if (!xfer) return KVL_EINVAL;
+    int rc = kvl::check_pool(plan, pool_planes, plan->layout.pool_blocks);
+    if (rc == KVL_OK) rc = kvl::check_buffer(plan, xfer, plan->payload_bytes, true);
+    if (rc != KVL_OK) return rc;
     uintptr_t xp[KVL_MAX_PLANES];
     for (uint32_t p = 0; p < plan->layout.n_planes; ++p)
         xp[p] = reinterpret_cast<uintptr_t>(xfer) + plan->plane_base[p];
@@ -250,6 +270,9 @@ int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_byt
     if (xfer_bytes < plan->payload_bytes) return KVL_ESPACE;
     if (plan->units.empty()) return KVL_OK;
     if (!xfer) return KVL_EINVAL;
+    int rc = kvl::check_pool(plan, pool_planes, plan->layout.pool_blocks);
+    if (rc == KVL_OK) rc = kvl::check_buffer(plan, xfer, plan->payload_bytes, true);
+    if (rc != KVL_OK) return rc;
     uintptr_t xp[KVL_MAX_PLANES];
     for (uint32_t p = 0; p < plan->layout.n_planes; ++p)
         xp[p] = reinterpret_cast<uintptr_t>(xfer) + plan->plane_base[p];

@@ -102,6 +102,11 @@ static void descriptor_release(void *ptr, size_t capacity, int device) {
     (void)hipFree(ptr);
 }
 
+int check_buffer(const kvl_plan_t *plan, const void *ptr, uint64_t bytes, bool allow_host) {
+    if (plan->flags & KVL_NO_POINTER_CHECKS) return KVL_OK;
+    return kvl_check_buffer(ptr, bytes, allow_host ? 1 : 0);
+}
+
 int upload_units(kvl_plan_t *plan) {
     hipError_t e = hipGetDevice(&plan->device);
     if (e == hipSuccess && !plan->units.empty()) {
@@ -135,7 +140,8 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
     if (!layout || !out || (n_req && !req)) return KVL_EINVAL;
     *out = nullptr;
     if (!(flags & (KVL_GATHER | KVL_SCATTER))) return KVL_EINVAL;
-    if (flags & ~(KVL_GATHER | KVL_SCATTER | KVL_HOST_ONLY | KVL_NO_MERGE | KVL_TOKENS_APPEND | KVL_TOKENS_ALL))
+    if (flags & ~(KVL_GATHER | KVL_SCATTER | KVL_HOST_ONLY | KVL_NO_MERGE | KVL_TOKENS_APPEND | KVL_TOKENS_ALL |
+                  KVL_NO_POINTER_CHECKS))
         return KVL_EINVAL;
     if ((flags & KVL_TOKENS_APPEND) && (flags & KVL_TOKENS_ALL)) return KVL_EINVAL;
     if (layout->block_tokens == 0 || layout->n_planes == 0 || layout->n_planes > KVL_MAX_PLANES)
@@ -419,6 +425,27 @@ int kvl_plan_get_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, kvl_chunk_
     const size_t k = (size_t)std::min<uint64_t>(capacity, c.size());
     if (k) std::memcpy(out, c.data(), k * sizeof(kvl_chunk_t));
     return KVL_OK;
+}
+
+int kvl_check_buffer(const void *ptr, uint64_t bytes, int allow_host) {
+    if (!ptr) return bytes ? KVL_EINVAL : KVL_OK;
+    hipPointerAttribute_t a{};
+    if (hipPointerGetAttributes(&a, ptr) != hipSuccess) {
+        (void)hipGetLastError();                     // not an error of ours: the pointer is unknown to HIP
+        return KVL_EINVAL;
+    }
+    if (a.type == hipMemoryTypeDevice || a.type == hipMemoryTypeManaged) {
+        hipDeviceptr_t base = nullptr;
+        size_t size = 0;
+        if (hipMemGetAddressRange(&base, &size, const_cast<void *>(ptr)) != hipSuccess) {
+            (void)hipGetLastError();
+            return KVL_OK;                           // extent unknown: nothing more to check
+        }
+        const uintptr_t p = reinterpret_cast<uintptr_t>(ptr), b = reinterpret_cast<uintptr_t>(base);
+        return (p >= b && bytes <= size && p - b <= size - bytes) ? KVL_OK : KVL_ESPACE;
+    }
+    if (a.type == hipMemoryTypeHost) return (allow_host && a.devicePointer) ? KVL_OK : KVL_EINVAL;
+    return KVL_EINVAL;                               // unregistered (pageable) host memory, arrays
 }
 
 void kvl_release_cached_memory(void) {

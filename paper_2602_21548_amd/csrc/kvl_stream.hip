@@ -100,6 +100,21 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
     }
     for (uint32_t i = 0; i < S * P; ++i)
         if (!cfg->dev_slot_planes[i]) return KVL_EINVAL;
+    if (!plan->units.empty()) {
+        for (uint32_t sl = 0; sl < S && rc == KVL_OK; ++sl)
+            rc = check_pool(plan, cfg->dev_slot_planes + (size_t)sl * P, plan->layout.pool_blocks);
+        if (!from_blocks) {
+            for (uint32_t h = 0; h < H && rc == KVL_OK; ++h)
+                rc = check_buffer(plan, cfg->host_layers[h], plan->payload_bytes, true);
+            if (rc == KVL_OK && cfg->chunk_bytes)
+                rc = check_buffer(plan, cfg->dev_staging, slots * cfg->chunk_bytes, false);
+        }
+        if (rc != KVL_OK) return rc;
+    }
+    if (cfg->n_probes) {
+        rc = check_buffer(plan, cfg->probe_out, (uint64_t)L * cfg->n_probes * 16, false);
+        if (rc != KVL_OK) return rc;
+    }
     for (uint32_t i = 0; i < cfg->n_probes; ++i) {
         const kvl_probe_t &pr = cfg->probes[i];
         const uint64_t plane_bytes = plan->layout.pool_blocks * plan->layout.block_tokens *

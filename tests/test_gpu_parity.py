@@ -698,3 +698,50 @@ def test_plans_do_not_leak_device_memory():
     free1, _ = torch.cuda.mem_get_info()
     assert free0 - free1 < (8 << 20), f"{(free0 - free1) >> 20} MiB of device memory gone after 300 plans"
     K.kvl_release_cached_memory()
+
+
+def test_check_buffer_classifies_pointers():
+    dev = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    pinned = torch.zeros(1 << 16, dtype=torch.uint8, pin_memory=True)
+    pageable = np.zeros(1 << 16, dtype=np.uint8)
+    assert K.kvl_check_buffer(dev.data_ptr(), 1 << 20) == K.KVL_OK
+    assert K.kvl_check_buffer(dev.data_ptr() + 4096, (1 << 20) - 4096) == K.KVL_OK
+    assert K.kvl_check_buffer(dev.data_ptr(), 1 << 46) == K.KVL_ESPACE       # past any allocation's end
+    assert K.kvl_check_buffer(pinned.data_ptr(), 1 << 16, allow_host=True) == K.KVL_OK
+    assert K.kvl_check_buffer(pinned.data_ptr(), 1 << 16, allow_host=False) == K.KVL_EINVAL
+    assert K.kvl_check_buffer(pageable.ctypes.data, 1 << 16, allow_host=True) == K.KVL_EINVAL
+    assert K.kvl_check_buffer(0, 0) == K.KVL_OK and K.kvl_check_buffer(0, 16) == K.KVL_EINVAL
+    # the failed look-ups above must not leave a sticky HIP error behind
+    torch.cuda.synchronize()
+    assert int((dev + 1).sum()) == 1 << 20
+
+
+def test_entry_points_refuse_memory_the_device_cannot_address():
+    """Raw C-ABI calls (the Python layer would stop these earlier) with pageable host
+    memory where device or pinned memory is required: an error code, no launch."""
+    import ctypes as C
+    lib = K.binding._lib
+    w = W.tiny(260, 3, 16, (32,), 32, 60, allow_zero_hit=False)
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    pool = torch.zeros(32 * 16 * 32, dtype=torch.uint8, device="cuda")
+    xfer = torch.zeros(g.payload_bytes, dtype=torch.uint8, device="cuda")
+    host_pool = np.zeros(32 * 16 * 32, dtype=np.uint8)
+    host_xfer = np.zeros(g.payload_bytes, dtype=np.uint8)
+    good, bad = (C.c_void_p * 1)(pool.data_ptr()), (C.c_void_p * 1)(host_pool.ctypes.data)
+    n = C.c_uint64(g.payload_bytes)
+    assert lib.kvl_pack_layer(g.handle, bad, C.c_void_p(xfer.data_ptr()), n, None) == K.KVL_EINVAL
+    assert lib.kvl_pack_layer(g.handle, good, C.c_void_p(host_xfer.ctypes.data), n, None) == K.KVL_EINVAL
+    assert lib.kvl_unpack_layer(s.handle, C.c_void_p(host_xfer.ctypes.data), n, good, None) == K.KVL_EINVAL
+    assert lib.kvl_unpack_layer(s.handle, C.c_void_p(xfer.data_ptr()), n, bad, None) == K.KVL_EINVAL
+    # a pool plane that is device memory but shorter than the layout says
+    tail = (C.c_void_p * 1)(pool.data_ptr() + pool.numel() - 64)
+    big = K.make_layout(1, 16, (32,), 1 << 27)     # a 64 GiB pool: past the end of what holds `pool`
+    gb = K.kvl_plan(big, w.hit, w.app, w.src.tables, K.KVL_GATHER)
+    assert lib.kvl_pack_layer(gb.handle, tail, C.c_void_p(xfer.data_ptr()), n, None) == K.KVL_ESPACE
+    # the same calls pass once the memory is right, and a plan may opt out of the checks
+    assert lib.kvl_pack_layer(g.handle, good, C.c_void_p(xfer.data_ptr()), n, None) == K.KVL_OK
+    lay = K.make_layout(w.layout.n_layers, 16, (32,), 32)
+    g2 = K.kvl_plan(lay, w.hit, w.app, w.src.tables, K.KVL_GATHER | K.KVL_NO_POINTER_CHECKS)
+    assert lib.kvl_pack_layer(g2.handle, good, C.c_void_p(xfer.data_ptr()), n, None) == K.KVL_OK
+    torch.cuda.synchronize()
