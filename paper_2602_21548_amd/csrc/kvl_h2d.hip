@@ -163,15 +163,23 @@ int kvl_plan_set_lane_cu_mask(kvl_plan_t *plan, const uint32_t *mask, uint32_t n
     bool any = n_words == 0;
     for (uint32_t i = 0; i < n_words; ++i) any = any || mask[i] != 0;
     if (!any) return KVL_EINVAL;                       // a mask with no compute unit at all
+    // the lanes are made anew, under the new mask, by the next call that needs them
+    hipError_t first = hipSuccess;
+    for (hipStream_t s : plan->lanes) {
+        hipError_t e = hipStreamSynchronize(s);
+        if (first == hipSuccess) first = e;
+        e = hipStreamDestroy(s);
+        if (first == hipSuccess) first = e;
+    }
+    plan->lanes.clear();
     try {
-        for (hipStream_t s : plan->lanes) {
-            KVL_HIP(hipStreamSynchronize(s));
-            KVL_HIP(hipStreamDestroy(s));
-        }
-        plan->lanes.clear();
         plan->lane_cu_mask.assign(mask, mask + n_words);
     } catch (const std::bad_alloc &) {
         return KVL_ENOMEM;
+    }
+    if (first != hipSuccess) {
+        kvl::set_hip_error(first);
+        return KVL_EHIP;
     }
     return KVL_OK;
 }
@@ -206,6 +214,9 @@ int kvl_h2d_blockwise_layer(const kvl_plan_t *plan, const void *pinned_host_xfer
 int kvl_measure_h2d_peak(const void *pinned_host, void *dev, uint64_t bytes, uint32_t reps,
                          void *stream, double *gbps) {
     if (!pinned_host || !dev || !gbps || bytes == 0 || reps == 0) return KVL_EINVAL;
+    int rc = kvl_check_buffer(pinned_host, bytes, 1);
+    if (rc == KVL_OK) rc = kvl_check_buffer(dev, bytes, 0);
+    if (rc != KVL_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     hipEvent_t a = nullptr, b = nullptr;
     KVL_HIP(hipEventCreate(&a));

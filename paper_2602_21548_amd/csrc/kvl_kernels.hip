@@ -107,7 +107,7 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
         a.row_elems[p] = vec ? plan->layout.row_bytes[p] / 16 : plan->layout.row_bytes[p];
 
     const uint32_t threads = plan->tuning.block_threads;
-    // default: tiled, one vector per lane; cache policies as measured (see the top of this file)
+    // default: tiled, one vector per lane; cache policies as measured (see the top of kvl_copy_kernels.h)
     uint32_t v;
     if (plan->tuning.variant) {
         v = plan->tuning.variant - 1;
@@ -285,6 +285,9 @@ int kvl_copy_linear(const void *src, void *dst, uint64_t bytes, void *stream) {
     if (!src || !dst) return KVL_EINVAL;
     if (bytes % 16 || reinterpret_cast<uintptr_t>(src) % 16 || reinterpret_cast<uintptr_t>(dst) % 16)
         return KVL_EINVAL;
+    int rc = kvl_check_buffer(src, bytes, 1);
+    if (rc == KVL_OK) rc = kvl_check_buffer(dst, bytes, 1);
+    if (rc != KVL_OK) return rc;
     const uint64_t n = bytes / 16;
     const uint64_t blocks = (n + 255) / 256;
     if (blocks > (uint64_t)INT32_MAX) return KVL_ERANGE;

@@ -86,7 +86,11 @@ static void descriptor_release(void *ptr, size_t capacity, int device) {
     // A kernel that still reads these descriptors must not see the next plan's: wait for the
     // device as the device free this replaces would have (it is idle if the caller has
     // synchronised its streams, as it should).
+    int current = device;
+    (void)hipGetDevice(&current);
+    if (current != device) (void)hipSetDevice(device);
     (void)hipDeviceSynchronize();
+    if (current != device) (void)hipSetDevice(current);
     {
         std::lock_guard<std::mutex> lock(g_cache_mutex);
         size_t held = 0;

@@ -115,6 +115,15 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
         rc = check_buffer(plan, cfg->probe_out, (uint64_t)L * cfg->n_probes * 16, false);
         if (rc != KVL_OK) return rc;
     }
+    if (cfg->snapshot_planes) {
+        for (size_t i = 0; i < (size_t)L * P; ++i) {
+            if (!cfg->snapshot_planes[i]) continue;
+            const uint64_t bytes = plan->layout.pool_blocks * plan->layout.block_tokens *
+                                   (uint64_t)plan->layout.row_bytes[i % P];
+            rc = check_buffer(plan, cfg->snapshot_planes[i], bytes, false);
+            if (rc != KVL_OK) return rc;
+        }
+    }
     for (uint32_t i = 0; i < cfg->n_probes; ++i) {
         const kvl_probe_t &pr = cfg->probes[i];
         const uint64_t plane_bytes = plan->layout.pool_blocks * plan->layout.block_tokens *
