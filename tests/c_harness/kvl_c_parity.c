@@ -1,0 +1,243 @@
+/*
+ * The library used from plain C, with nothing but the HIP runtime around it:
+ * device memory from hipMalloc, pinned memory from hipHostMalloc, no Python.
+ * One small batch goes pool -> transfer buffer -> second pool on the GPU and is
+ * compared byte for byte with the CPU oracle (compiled into this program from
+ * oracle/kvl_oracle.c).  Because every buffer here is an allocation of exactly
+ * its own size, the entry points' buffer checks are exercised at their edges: a
+ * pool one block short and a transfer buffer shorter than its stated capacity
+ * must come back as KVL_ESPACE, pageable host memory as KVL_EINVAL, and none
+ * of them may launch anything.
+ *
+ * Prints one line per check and "c parity ok" at the end; exit status 0 only
+ * if every check passed.
+ */
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <hip/hip_runtime_api.h>
+
+#include "kvl.h"
+
+/* the oracle's entry points (oracle/kvl_oracle.c) */
+int kvo_pack(uint32_t bs, uint32_t n_planes, const uint32_t *row_bytes, uint32_t n_req, const uint32_t *hit,
+             const int32_t *const *tables, const uint8_t *const *pool_planes, uint8_t *xfer,
+             uint32_t r_begin, uint32_t r_end);
+int kvo_unpack(uint32_t bs, uint32_t n_planes, const uint32_t *row_bytes, uint32_t n_req, const uint32_t *hit,
+               const int32_t *const *tables, const uint8_t *xfer, uint8_t *const *pool_planes,
+               uint32_t r_begin, uint32_t r_end);
+uint64_t kvo_payload_bytes(uint32_t n_req, const uint32_t *hit, uint32_t n_planes, const uint32_t *row_bytes);
+
+#define HIP_OK(call)                                                                      \
+    do {                                                                                  \
+        hipError_t e_ = (call);                                                           \
+        if (e_ != hipSuccess) {                                                           \
+            fprintf(stderr, "%s:%d: %s: %s\n", __FILE__, __LINE__, #call, hipGetErrorString(e_)); \
+            exit(2);                                                                      \
+        }                                                                                 \
+    } while (0)
+
+static int failures = 0;
+
+static void expect(int got, int want, const char *what) {
+    printf("%-72s %s (%d)\n", what, got == want ? "ok" : "FAILED", got);
+    fflush(stdout);
+    if (got != want) ++failures;
+}
+
+/* splitmix64: the inputs are this program's own, seeded */
+static uint64_t rng_state = 20260221u;
+static uint64_t rnd(void) {
+    uint64_t z = (rng_state += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+enum { R = 5, BS = 16, P = 2, POOL_BLOCKS = 96 };
+
+int main(void) {
+    const uint32_t rows[P] = {656, 256};
+    const uint32_t hit[R] = {100, 16, 0, 333, 47}, app[R] = {9, 0, 20, 3, 1};
+    int32_t src_tab[R][32], dst_tab[R][32];
+    const int32_t *src_tabs[R], *dst_tabs[R];
+    kvl_request_t src_req[R], dst_req[R];
+
+    /* two independent seeded permutations of the pool's blocks, dealt out in order */
+    int32_t perm_a[POOL_BLOCKS], perm_b[POOL_BLOCKS];
+    for (int i = 0; i < POOL_BLOCKS; ++i) perm_a[i] = perm_b[i] = i;
+    for (int i = POOL_BLOCKS - 1; i > 0; --i) {
+        int j = (int)(rnd() % (uint64_t)(i + 1)), k = (int)(rnd() % (uint64_t)(i + 1));
+        int32_t t = perm_a[i]; perm_a[i] = perm_a[j]; perm_a[j] = t;
+        t = perm_b[i]; perm_b[i] = perm_b[k]; perm_b[k] = t;
+    }
+    uint32_t next = 0;
+    for (int r = 0; r < R; ++r) {
+        const uint32_t nb = (hit[r] + app[r] + BS - 1) / BS;
+        for (uint32_t b = 0; b < nb; ++b, ++next) {
+            src_tab[r][b] = perm_a[next];
+            dst_tab[r][b] = perm_b[next];
+        }
+        src_tabs[r] = src_tab[r];
+        dst_tabs[r] = dst_tab[r];
+        src_req[r].hit_tokens = dst_req[r].hit_tokens = hit[r];
+        src_req[r].append_tokens = dst_req[r].append_tokens = app[r];
+        src_req[r].n_blocks = dst_req[r].n_blocks = nb;
+        src_req[r].block_table = src_tab[r];
+        dst_req[r].block_table = dst_tab[r];
+    }
+    if (next > POOL_BLOCKS) return 2;
+
+    kvl_layout_t lay;
+    memset(&lay, 0, sizeof lay);
+    lay.n_layers = 1;
+    lay.block_tokens = BS;
+    lay.n_planes = P;
+    lay.row_bytes[0] = rows[0];
+    lay.row_bytes[1] = rows[1];
+    lay.pool_blocks = POOL_BLOCKS;
+
+    /* host copies: source pool of seeded bytes, destination pool of a sentinel */
+    size_t plane_bytes[P];
+    uint8_t *h_src[P], *h_dst[P], *h_dst_want[P];
+    void *d_src[P], *d_dst[P];
+    for (int p = 0; p < P; ++p) {
+        plane_bytes[p] = (size_t)POOL_BLOCKS * BS * rows[p];
+        h_src[p] = malloc(plane_bytes[p]);
+        h_dst[p] = malloc(plane_bytes[p]);
+        h_dst_want[p] = malloc(plane_bytes[p]);
+        for (size_t i = 0; i < plane_bytes[p]; ++i) h_src[p][i] = (uint8_t)rnd();
+        memset(h_dst_want[p], 0xA5, plane_bytes[p]);
+        HIP_OK(hipMalloc(&d_src[p], plane_bytes[p]));
+        HIP_OK(hipMalloc(&d_dst[p], plane_bytes[p]));
+        HIP_OK(hipMemcpy(d_src[p], h_src[p], plane_bytes[p], hipMemcpyHostToDevice));
+        HIP_OK(hipMemset(d_dst[p], 0xA5, plane_bytes[p]));
+    }
+
+    const uint64_t payload = kvo_payload_bytes(R, hit, P, rows);
+    uint8_t *want_xfer = malloc(payload), *got_xfer = malloc(payload);
+    if (kvo_pack(BS, P, rows, R, hit, src_tabs, (const uint8_t *const *)h_src, want_xfer, 0, R) != 0) return 2;
+    if (kvo_unpack(BS, P, rows, R, hit, dst_tabs, want_xfer, h_dst_want, 0, R) != 0) return 2;
+
+    kvl_plan_t *g = NULL, *s = NULL;
+    expect(kvl_plan(&lay, src_req, R, KVL_GATHER, &g), KVL_OK, "kvl_plan (gather)");
+    expect(kvl_plan(&lay, dst_req, R, KVL_SCATTER, &s), KVL_OK, "kvl_plan (scatter)");
+    if (failures) return 1;
+    uint64_t lib_payload = 0;
+    kvl_plan_payload_bytes(g, &lib_payload);
+    expect(lib_payload == payload, 1, "payload bytes equal the oracle's");
+
+    void *d_xfer = NULL, *d_short = NULL, *pinned = NULL;
+    HIP_OK(hipMalloc(&d_xfer, payload));
+    HIP_OK(hipMalloc(&d_short, payload - 4096));
+    HIP_OK(hipHostMalloc(&pinned, payload, hipHostMallocDefault));
+
+    /* --- refusals first.  Each bad buffer is shown to kvl_check_buffer alone before an
+     * entry point sees it, and the entry point is only called if that check refused it:
+     * whatever happens, nothing here launches a kernel on memory that is not there. --- */
+    expect(kvl_check_buffer(d_xfer, payload, 0), KVL_OK, "kvl_check_buffer: exact device allocation");
+    expect(kvl_check_buffer(d_xfer, payload + 1, 0), KVL_ESPACE, "kvl_check_buffer: one byte past the allocation");
+    expect(kvl_check_buffer((char *)d_xfer + payload - 16, 16, 0), KVL_OK, "kvl_check_buffer: last 16 bytes");
+    expect(kvl_check_buffer(pinned, payload, 1), KVL_OK, "kvl_check_buffer: pinned host memory where allowed");
+    expect(kvl_check_buffer(pinned, payload, 0), KVL_EINVAL, "kvl_check_buffer: pinned host memory where not");
+
+    void *short_pool[P] = {d_src[0], NULL};
+    HIP_OK(hipMalloc(&short_pool[1], plane_bytes[1] - (size_t)BS * rows[1]));
+    void *host_pool[P] = {h_dst[0], h_dst[1]};
+    int refused;
+    refused = kvl_check_buffer(short_pool[1], plane_bytes[1], 0);
+    expect(refused, KVL_ESPACE, "kvl_check_buffer: pool plane one block short");
+    if (refused != KVL_OK)
+        expect(kvl_pack_layer(g, (const void *const *)short_pool, d_xfer, payload, NULL), KVL_ESPACE,
+               "pack from a pool plane one block short");
+    refused = kvl_check_buffer(d_short, payload, 1);
+    expect(refused, KVL_ESPACE, "kvl_check_buffer: allocation shorter than the payload");
+    if (refused != KVL_OK) {
+        expect(kvl_pack_layer(g, (const void *const *)d_src, d_short, payload, NULL), KVL_ESPACE,
+               "pack into an allocation shorter than the stated capacity");
+        expect(kvl_unpack_layer(s, d_short, payload, d_dst, NULL), KVL_ESPACE,
+               "unpack from an allocation shorter than the stated size");
+    }
+    refused = kvl_check_buffer((char *)d_xfer + 16, payload, 1);
+    expect(refused, KVL_ESPACE, "kvl_check_buffer: span that starts 16 bytes into its allocation");
+    if (refused != KVL_OK)
+        expect(kvl_pack_layer(g, (const void *const *)d_src, (char *)d_xfer + 16, payload, NULL), KVL_ESPACE,
+               "pack into a buffer that starts 16 bytes into its allocation");
+    refused = kvl_check_buffer(got_xfer, payload, 1);
+    expect(refused, KVL_EINVAL, "kvl_check_buffer: pageable host memory");
+    if (refused != KVL_OK) {
+        expect(kvl_pack_layer(g, (const void *const *)d_src, got_xfer, payload, NULL), KVL_EINVAL,
+               "pack into pageable host memory");
+        expect(kvl_unpack_layer(s, d_xfer, payload, host_pool, NULL), KVL_EINVAL,
+               "unpack into a pool in pageable host memory");
+    }
+
+    /* --- the hop on the device --- */
+    HIP_OK(hipMemset(d_xfer, 0, payload));
+    expect(kvl_pack_layer(g, (const void *const *)d_src, d_xfer, payload, NULL), KVL_OK, "kvl_pack_layer");
+    HIP_OK(hipDeviceSynchronize());
+    HIP_OK(hipMemcpy(got_xfer, d_xfer, payload, hipMemcpyDeviceToHost));
+    expect(memcmp(got_xfer, want_xfer, payload) == 0, 1, "transfer buffer equals the oracle's");
+    expect(kvl_unpack_layer(s, d_xfer, payload, d_dst, NULL), KVL_OK, "kvl_unpack_layer");
+    HIP_OK(hipDeviceSynchronize());
+    for (int p = 0; p < P; ++p) {
+        HIP_OK(hipMemcpy(h_dst[p], d_dst[p], plane_bytes[p], hipMemcpyDeviceToHost));
+        expect(memcmp(h_dst[p], h_dst_want[p], plane_bytes[p]) == 0, 1,
+               p == 0 ? "destination pool plane 0 equals the oracle's (sentinel elsewhere)"
+                      : "destination pool plane 1 equals the oracle's (sentinel elsewhere)");
+    }
+
+    /* --- the same gather written straight into pinned host memory --- */
+    memset(pinned, 0, payload);
+    expect(kvl_pack_layer(g, (const void *const *)d_src, pinned, payload, NULL), KVL_OK,
+           "kvl_pack_layer into pinned host memory");
+    HIP_OK(hipDeviceSynchronize());
+    expect(memcmp(pinned, want_xfer, payload) == 0, 1, "pinned transfer buffer equals the oracle's");
+
+    /* --- host buffer -> staging -> pool --- */
+    for (int p = 0; p < P; ++p) HIP_OK(hipMemset(d_dst[p], 0xA5, plane_bytes[p]));
+    void *d_stage = NULL;
+    const uint64_t chunk = 131072, stage_bytes = 3 * chunk;   /* no descriptor exceeds 128 KiB */
+    HIP_OK(hipMalloc(&d_stage, stage_bytes));
+    hipStream_t cs, ks;
+    HIP_OK(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
+    HIP_OK(hipStreamCreateWithFlags(&ks, hipStreamNonBlocking));
+    expect(kvl_h2d_unpack_layer(s, pinned, d_stage, stage_bytes, chunk, d_dst, cs, ks), KVL_OK,
+           "kvl_h2d_unpack_layer (3 staging slots of 128 KiB)");
+    HIP_OK(hipStreamSynchronize(ks));
+    HIP_OK(hipStreamSynchronize(cs));
+    for (int p = 0; p < P; ++p) {
+        HIP_OK(hipMemcpy(h_dst[p], d_dst[p], plane_bytes[p], hipMemcpyDeviceToHost));
+        expect(memcmp(h_dst[p], h_dst_want[p], plane_bytes[p]) == 0, 1, "pool plane after the host-buffer load");
+    }
+    refused = kvl_check_buffer(d_stage, 4 * chunk, 0);
+    expect(refused, KVL_ESPACE, "kvl_check_buffer: staging area stated larger than its allocation");
+    if (refused != KVL_OK)
+        expect(kvl_h2d_unpack_layer(s, pinned, d_stage, 4 * chunk, chunk, d_dst, cs, ks), KVL_ESPACE,
+               "host-buffer load with a staging area stated larger than its allocation");
+
+    kvl_plan_destroy(g);
+    kvl_plan_destroy(s);
+    kvl_release_cached_memory();
+    HIP_OK(hipStreamDestroy(cs));
+    HIP_OK(hipStreamDestroy(ks));
+    HIP_OK(hipFree(d_stage));
+    HIP_OK(hipFree(short_pool[1]));
+    HIP_OK(hipFree(d_xfer));
+    HIP_OK(hipFree(d_short));
+    HIP_OK(hipHostFree(pinned));
+    for (int p = 0; p < P; ++p) {
+        HIP_OK(hipFree(d_src[p]));
+        HIP_OK(hipFree(d_dst[p]));
+        free(h_src[p]); free(h_dst[p]); free(h_dst_want[p]);
+    }
+    free(want_xfer); free(got_xfer);
+    if (failures) {
+        printf("c parity: %d check(s) FAILED\n", failures);
+        return 1;
+    }
+    printf("c parity ok\n");
+    return 0;
+}
