@@ -280,6 +280,14 @@ typedef struct {
  * deliver its bytes.  Return non-zero to abort the run. */
 typedef int (*kvl_host_fill_fn)(void *user, uint32_t layer, void *host_slot, uint64_t bytes);
 
+/* The caller's own per-layer computation, in place of the synthetic kernel.  Called
+ * on the calling thread, in layer order, once compute_stream has been made to wait
+ * for layer `layer`'s load: enqueue the layer's work on compute_stream and return
+ * (do not synchronise).  slot_planes are the n_planes device bases of the slot that
+ * holds the layer.  Whatever the callback enqueues is what the next load into that
+ * slot waits for.  Return non-zero to abort the run. */
+typedef int (*kvl_compute_fn)(void *user, uint32_t layer, void *const *slot_planes, void *compute_stream);
+
 typedef struct {
     uint32_t n_layers;                 /* 0: take layout.n_layers */
     uint32_t n_host_slots;             /* H >= 1 */
@@ -308,13 +316,18 @@ typedef struct {
      * with KVL_NO_MERGE. */
     const void *full_blocks;
     uint64_t full_blocks_bytes;
+    /* Optional: the caller's computation instead of the synthetic kernel (compute_us
+     * and the probes are then unused; snapshots are still taken after it). */
+    kvl_compute_fn compute;
+    void *compute_user;
 } kvl_stream_cfg_t;
 
 typedef struct {
     double total_ms;         /* first copy enqueued .. last compute finished (device clock) */
     double h2d_bytes;        /* bytes that crossed the host link */
     double link_gbps;        /* h2d_bytes / total_ms, GB/s */
-    double exposed_ms;       /* total_ms minus n_layers * compute_us: load time not hidden */
+    double exposed_ms;       /* total_ms minus the compute time (n_layers * compute_us, or the measured
+                                sum of the caller's computations): load time not hidden */
     /* optional per-layer times in ms since the start, host arrays of n_layers or NULL */
     float *t_loaded;         /* layer's scatter finished */
     float *t_compute_begin;
@@ -325,8 +338,8 @@ typedef struct {
  * computation of the layers before it; layer-wise prefill keeps only a few
  * layers' cache resident).  For l = 0 .. n_layers-1: layer l is loaded from
  * host_layers[l % H] into destination slot l % S by the h2d path; the compute
- * of layer l (a kernel that spins compute_us on the compute stream) starts
- * after that load; the load of layer l + S starts scattering only after the
+ * of layer l (a kernel that spins compute_us on the compute stream, or what
+ * cfg->compute enqueues there) starts after that load; the load of layer l + S starts scattering only after the
  * compute of layer l has finished.  Blocks until everything has finished and
  * fills *stats (may be NULL).  Needs a KVL_SCATTER plan. */
 int kvl_stream_layers(const kvl_plan_t *plan, const kvl_stream_cfg_t *cfg, kvl_stream_stats_t *stats);

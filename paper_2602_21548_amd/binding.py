@@ -64,6 +64,7 @@ class kvl_probe_t(C.Structure):
 
 
 HOST_FILL_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64)
+COMPUTE_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p), C.c_void_p)
 
 
 class kvl_stream_cfg_t(C.Structure):
@@ -77,7 +78,8 @@ class kvl_stream_cfg_t(C.Structure):
                 ("snapshot_planes", C.POINTER(C.c_void_p)),
                 ("host_fill", HOST_FILL_FN), ("host_fill_user", C.c_void_p),
                 ("copy_stream", C.c_void_p), ("kernel_stream", C.c_void_p), ("compute_stream", C.c_void_p),
-                ("full_blocks", C.c_void_p), ("full_blocks_bytes", C.c_uint64)]
+                ("full_blocks", C.c_void_p), ("full_blocks_bytes", C.c_uint64),
+                ("compute", COMPUTE_FN), ("compute_user", C.c_void_p)]
 
 
 class kvl_stream_stats_t(C.Structure):
@@ -418,9 +420,12 @@ def kvl_stream_layers(plan: Plan, host_layers: Sequence[torch.Tensor],
                       probe_out: Optional[torch.Tensor] = None,
                       snapshots: Optional[Sequence[Sequence[torch.Tensor]]] = None,
                       host_fill=None, per_layer_times: bool = False,
-                      full_blocks: Optional[torch.Tensor] = None) -> dict:
+                      full_blocks: Optional[torch.Tensor] = None, compute=None) -> dict:
     """kvl_stream_layers; returns the stats as a dict.  host_fill(layer, slot_index) is an
     optional Python callable run where the storage read of that layer would deliver.
+    compute(layer, slot_index, stream_handle) is an optional Python callable that enqueues
+    the caller's own work for that layer on the compute stream (given as a raw handle; wrap
+    it in torch.cuda.ExternalStream to use it from torch) in place of the synthetic kernel.
     With full_blocks (device or pinned host tensor) the layers are loaded from the storage
     layout instead; host_layers, dev_staging and chunk_bytes may then be None / 0."""
     L = n_layers or int(plan.layout.n_layers)
@@ -482,6 +487,18 @@ def kvl_stream_layers(plan: Plan, host_layers: Sequence[torch.Tensor],
         cb = HOST_FILL_FN(_tramp)
         cfg.host_fill = cb
         keep.append(cb)
+    if compute is not None:
+        def _ctramp(_user, layer, _planes, stream_ptr):
+            try:
+                compute(int(layer), int(layer) % S, int(stream_ptr or 0))
+                return 0
+            except Exception:  # surfaces as KVL_EINVAL from the call
+                import traceback
+                traceback.print_exc()
+                return 1
+        ccb = COMPUTE_FN(_ctramp)
+        cfg.compute = ccb
+        keep.append(ccb)
     cfg.copy_stream = _stream_handle(copy_stream)
     cfg.kernel_stream = _stream_handle(kernel_stream)
     cfg.compute_stream = _stream_handle(compute_stream)

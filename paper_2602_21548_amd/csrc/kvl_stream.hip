@@ -85,6 +85,7 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
     if (!from_blocks && (H == 0 || !cfg->host_layers)) return KVL_EINVAL;
     if (cfg->compute_us > 1000000u) return KVL_EINVAL;
     if (cfg->n_probes && (!cfg->probes || !cfg->probe_out)) return KVL_EINVAL;
+    if (cfg->compute && cfg->n_probes) return KVL_EINVAL;     // the probes belong to the synthetic kernel
     size_t slots = 0;
     int rc = KVL_OK;
     if (from_blocks) {
@@ -221,9 +222,13 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
         v4u *pout = cfg->n_probes
                         ? static_cast<v4u *>(cfg->probe_out) + (size_t)l * cfg->n_probes
                         : nullptr;
-        hipLaunchKernelGGL(kvl_compute_kernel, dim3(1), dim3(64), 0, ms, sp, st.d_probes,
-                           cfg->n_probes, pout, ticks, max_polls);
-        KVL_HIP(hipGetLastError());
+        if (cfg->compute) {
+            if (cfg->compute(cfg->compute_user, l, slot_planes, cfg->compute_stream) != 0) return KVL_EINVAL;
+        } else {
+            hipLaunchKernelGGL(kvl_compute_kernel, dim3(1), dim3(64), 0, ms, sp, st.d_probes,
+                               cfg->n_probes, pout, ticks, max_polls);
+            KVL_HIP(hipGetLastError());
+        }
         if (cfg->snapshot_planes) {
             for (uint32_t p = 0; p < P; ++p) {
                 void *snap = cfg->snapshot_planes[(size_t)l * P + p];
@@ -245,7 +250,16 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
         stats->total_ms = total;
         stats->h2d_bytes = (double)plan->payload_bytes * L;
         stats->link_gbps = total > 0.f ? stats->h2d_bytes / (total * 1e-3) / 1e9 : 0.0;
-        stats->exposed_ms = total - (double)L * cfg->compute_us * 1e-3;
+        double computed = (double)L * cfg->compute_us * 1e-3;
+        if (cfg->compute) {
+            computed = 0.0;
+            for (uint32_t l = 0; l < L; ++l) {
+                float t = 0.f;
+                KVL_HIP(hipEventElapsedTime(&t, cbeg[l], cend[l]));
+                computed += t;
+            }
+        }
+        stats->exposed_ms = total - computed;
         for (uint32_t l = 0; l < L; ++l) {
             float t = 0.f;
             if (stats->t_loaded) {

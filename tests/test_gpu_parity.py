@@ -745,3 +745,71 @@ def test_entry_points_refuse_memory_the_device_cannot_address():
     g2 = K.kvl_plan(lay, w.hit, w.app, w.src.tables, K.KVL_GATHER | K.KVL_NO_POINTER_CHECKS)
     assert lib.kvl_pack_layer(g2.handle, good, C.c_void_p(xfer.data_ptr()), n, None) == K.KVL_OK
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("S", [1, 2])
+@pytest.mark.parametrize("chunk", [8192, 0], ids=["staged", "zerocopy"])
+def test_stream_layers_with_the_callers_own_compute(S, chunk):
+    """The per-layer computation is the caller's: torch kernels enqueued from the callback
+    on the compute stream must see, layer by layer, what the oracle says the slot holds."""
+    L, H = 5, 2
+    w = W.tiny(261, 5, 16, (64, 32), 96, 180, n_layers=L)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    n = oracle.payload_bytes(w.hit, rows)
+    payloads = [W.random_payload(w, l, n) for l in range(L)]
+    o_slots = [W.sentinel_pool(w, "dst", 0xEE) for _ in range(S)]
+    o_host = [np.zeros(n, np.uint8) for _ in range(H)]
+    want = []
+    gen = oracle.stream_layers(bs, rows, w.hit, w.dst.tables, o_host, L, o_slots)
+    for l in range(L):
+        o_host[l % H][:] = payloads[l]
+        _, _, planes = next(gen)
+        want.append([p.copy() for p in planes])
+
+    s = dev_plan(w, "dst", K.KVL_SCATTER, unit_bytes=4096)
+    host = [torch.zeros(n, dtype=torch.uint8, pin_memory=True) for _ in range(H)]
+    slots = [planes_to_dev(W.sentinel_pool(w, "dst", 0xEE)) for _ in range(S)]
+    seen = [[torch.zeros_like(pl) for pl in slots[0]] for _ in range(L)]
+    sums = torch.zeros(L, dtype=torch.int64, device="cuda")
+    staging = torch.zeros(3 * 8192, dtype=torch.uint8, device="cuda")
+    calls = []
+
+    def fill(layer, slot):
+        host[slot].numpy()[:] = payloads[layer]
+
+    torch.cuda.synchronize()
+    cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+
+    def compute(layer, slot, stream_handle):
+        calls.append((layer, slot))
+        assert stream_handle == ms.cuda_stream
+        with torch.cuda.stream(ms):
+            for p in range(len(rows)):
+                seen[layer][p].copy_(slots[slot][p])
+            sums[layer] = slots[slot][0].sum(dtype=torch.int64)
+
+    st = K.kvl_stream_layers(s, host, slots, staging if chunk else None, chunk, 0, cs, ks, ms, n_layers=L,
+                             host_fill=fill, compute=compute, per_layer_times=True)
+    assert calls == [(l, l % S) for l in range(L)]
+    for l in range(L):
+        for p in range(len(rows)):
+            assert same_bytes(to_host(seen[l][p]), want[l][p]), f"layer {l} plane {p}"
+        assert int(sums[l]) == int(want[l][0].astype(np.int64).sum())
+    assert np.all(st["t_compute_begin"] >= st["t_loaded"] - 1e-3)
+    assert st["exposed_ms"] <= st["total_ms"]
+
+    # a callback that fails ends the run with an error, and nothing is left running
+    def broken(layer, slot, stream_handle):
+        if layer == 2:
+            raise RuntimeError("planted")
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_stream_layers(s, host, slots, staging if chunk else None, chunk, 0, cs, ks, ms, n_layers=L,
+                            host_fill=fill, compute=broken)
+    assert e.value.code == K.KVL_EINVAL
+    torch.cuda.synchronize()
+    # the synthetic kernel's probes make no sense with a caller's computation
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_stream_layers(s, host, slots, staging if chunk else None, chunk, 0, cs, ks, ms, n_layers=L,
+                            probes=[(0, 0)], probe_out=torch.zeros(L * 16, dtype=torch.uint8, device="cuda"),
+                            compute=compute)
+    assert e.value.code == K.KVL_EINVAL
