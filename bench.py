@@ -539,6 +539,7 @@ def host_link_legs(args) -> dict:
     h2d_gbps = payload / min(times) / 1e9
 
     st = K.kvl_stream_layers(plan, host, slots, staging, chunk, w.notes["compute_us"], cs, ks, ms, n_layers=L)
+    busy = stream_under_busy_compute(plan, host, slots, staging, chunk, cs, ks, ms, min(L, 8), peak)
     # the other direction: gather one layer straight into the pinned host buffer (the step that
     # sends a layer's cache on to the decode engine's host buffer)
     gplan = K.kvl_plan(lay, w.hit, w.app, w.dst.tables, K.KVL_GATHER)
@@ -558,7 +559,7 @@ def host_link_legs(args) -> dict:
     torch.cuda.empty_cache()
     fullblocks = full_block_leg(host[0], peak)
     return {
-        "full_blocks": fullblocks,
+        "full_blocks": fullblocks, "stream_under_hbm_bound_compute": busy,
         "workload": "cfg5 streamed MLA: 61 layers x 1152 B rows, 128 req, pinned host buffer -> paged HBM, "
                     "200 us synthetic compute per layer",
         "h2d_peak_gbps": round(peak, 2), "chunk_bytes": chunk, "staging_slots": 4,
@@ -571,6 +572,41 @@ def host_link_legs(args) -> dict:
         "stream_zero_copy_frac_of_link": round(zc["link_gbps"] / peak, 4),
         "payload_bytes_per_layer": payload,
     }
+
+
+def stream_under_busy_compute(plan, host, slots, staging, chunk, cs, ks, ms, layers, peak) -> dict:
+    """The streamed load with the caller's own computation in place of the 200 us stand-in: per
+    layer, plain device-to-device copies that keep every compute unit and the HBM busy for about
+    50 ms.  Shows what the load keeps of the link, and what it costs the computation, when the
+    GPU is not idle."""
+    import torch
+    import paper_2602_21548_amd as K
+    a = torch.full((4 << 30,), 1, dtype=torch.uint8, device="cuda")
+    b = torch.empty_like(a)
+    reps = 40
+
+    def compute(layer, slot, stream_handle):
+        for _ in range(reps):
+            K.kvl_copy_linear(a, b, stream=stream_handle)
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(ms)
+    compute(0, 0, ms.cuda_stream)
+    e1.record(ms)
+    e1.synchronize()
+    alone = e0.elapsed_time(e1)
+    st = K.kvl_stream_layers(plan, host, slots, staging, chunk, 0, cs, ks, ms, n_layers=layers,
+                             compute=compute, per_layer_times=True)
+    # the last layer's computation runs after every load has finished: leave it out
+    busy = (st["t_compute_end"] - st["t_compute_begin"])[:-1]
+    del a, b
+    torch.cuda.empty_cache()
+    return {"layers": layers, "compute": f"{reps} x 4 GiB device copies per layer on the compute stream",
+            "link_gbps": round(st["link_gbps"], 2), "frac_of_link": round(st["link_gbps"] / peak, 4),
+            "compute_ms_per_layer_alone": round(alone, 2),
+            "compute_ms_per_layer_during_load": round(float(busy.mean()), 2) if len(busy) else None,
+            "hw_queues": os.environ.get("GPU_MAX_HW_QUEUES", "runtime default")}
 
 
 def full_block_leg(pinned: "torch.Tensor", h2d_peak: float) -> dict:
