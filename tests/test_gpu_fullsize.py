@@ -246,3 +246,68 @@ def test_full_size_streamed_layers():
     # load of layer l + S does not finish before compute of layer l has ended
     assert np.all(tl[S:] >= te[:-S] - 1e-3)
     s.destroy()
+
+
+def test_row_indices_at_the_32_bit_limit():
+    """The largest pool a plan accepts: block_tokens * pool_blocks just below 2^32 token rows
+    (descriptors index rows with 32 bits), 68.7 GB per pool at 16-byte rows.  A few requests
+    use the first block, the last blocks and blocks in between.  The oracle works on the same
+    problem with the touched blocks renumbered 0, 1, 2, ... (a pool of only those blocks):
+    the bytes it expects in the transfer buffer and in every touched block are the same."""
+    bs, row = 64, 16
+    pool_blocks = (2 ** 32 - 1) // bs                     # one more block and kvl_plan says KVL_ERANGE
+    blk = bs * row
+    rng = np.random.Generator(np.random.PCG64(W.BASE_SEED + 977))
+    hit = np.array([100, 64, 130, 1], dtype=np.uint32)
+    app = np.array([0, 5, 0, 0], dtype=np.uint32)
+    mid = pool_blocks // 2
+    src_ids = [[pool_blocks - 1, 0], [pool_blocks - 2, 12345678], [mid, mid + 1, 3], [pool_blocks - 3]]
+    dst_ids = [[7, pool_blocks - 1], [mid - 1, 1], [pool_blocks - 4, pool_blocks - 3, pool_blocks - 2], [0]]
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_plan(K.make_layout(1, bs, (row,), pool_blocks + 1), hit, app,
+                   [np.array(t, np.int32) for t in src_ids], K.KVL_GATHER | K.KVL_HOST_ONLY)
+    assert e.value.code == K.KVL_ERANGE
+
+    def compact(ids):
+        order = sorted({b for t in ids for b in t})
+        number = {b: i for i, b in enumerate(order)}
+        return order, [np.array([number[b] for b in t], np.int32) for t in ids]
+
+    src_order, src_small = compact(src_ids)
+    dst_order, dst_small = compact(dst_ids)
+    small_src = rng.integers(0, 256, size=len(src_order) * blk, dtype=np.uint8)
+    want_x = oracle.pack(bs, (row,), hit, src_small, [small_src])
+    small_dst = np.full(len(dst_order) * blk, 0xA5, dtype=np.uint8)
+    oracle.unpack(bs, (row,), hit, dst_small, want_x, [small_dst])
+
+    torch.cuda.empty_cache()
+    lay = K.make_layout(1, bs, (row,), pool_blocks)
+    g = K.kvl_plan(lay, hit, app, [np.array(t, np.int32) for t in src_ids], K.KVL_GATHER)
+    s = K.kvl_plan(lay, hit, app, [np.array(t, np.int32) for t in dst_ids], K.KVL_SCATTER)
+    d_src = torch.empty(pool_blocks * blk, dtype=torch.uint8, device="cuda")      # only touched blocks are set
+    d_dst = torch.empty(pool_blocks * blk, dtype=torch.uint8, device="cuda")
+    for i, b in enumerate(src_order):
+        d_src[b * blk:(b + 1) * blk] = torch.from_numpy(small_src[i * blk:(i + 1) * blk]).cuda()
+    for b in dst_order:
+        d_dst[b * blk:(b + 1) * blk] = 0xA5
+    n = g.payload_bytes
+    d_x = torch.full((n + 4096,), 0x3C, dtype=torch.uint8, device="cuda")
+    K.kvl_pack_layer(g, [d_src], d_x)
+    K.kvl_unpack_layer(s, d_x, [d_dst])
+    torch.cuda.synchronize()
+    got = to_host(d_x)
+    assert same_bytes(got[:n], want_x) and np.all(got[n:] == 0x3C)
+    for i, b in enumerate(dst_order):
+        assert same_bytes(to_host(d_dst[b * blk:(b + 1) * blk]), small_dst[i * blk:(i + 1) * blk]), f"block {b}"
+    # the fused move between the two pools gives the same destination blocks
+    for b in dst_order:
+        d_dst[b * blk:(b + 1) * blk] = 0xA5
+    m = K.kvl_plan_pair(g, s)
+    K.kvl_move_layer(m, [d_src], [d_dst])
+    torch.cuda.synchronize()
+    for i, b in enumerate(dst_order):
+        assert same_bytes(to_host(d_dst[b * blk:(b + 1) * blk]), small_dst[i * blk:(i + 1) * blk]), f"move: block {b}"
+    for p in (m, g, s):
+        p.destroy()
+    del d_src, d_dst, d_x
+    torch.cuda.empty_cache()
