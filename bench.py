@@ -649,12 +649,52 @@ def full_block_leg(pinned: "torch.Tensor", h2d_peak: float) -> dict:
             best = max(best, per_layer * L / (e0.elapsed_time(e1) * 1e-3) / 1e9)
         out[f"{name}_gbps"] = round(best, 2)
     out["h2d_frac_of_link"] = round(out["h2d_gbps"] / h2d_peak, 4)
+    # the same load staged by the copy engine (strided copies into 2 slots of 64 MiB, converting kernels there)
+    chunk = 64 << 20
+    staging = torch.empty(2 * chunk, dtype=torch.uint8, device=dev)
+    cs = torch.cuda.Stream()
+    best = 0.0
+    for rep in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(st)
+        for l in range(L):
+            K.kvl_h2d_fullblocks_layer(s, buf, l, staging, chunk, pool, cs, st)
+        e1.record(st)
+        e1.synchronize()
+        cs.synchronize()
+        best = max(best, per_layer * L / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    out["h2d_staged_gbps"] = round(best, 2)
+    out["h2d_staged_frac_of_link"] = round(best / h2d_peak, 4)
     # the streamed load with the storage layout as its source: 61 layers under 200 us of compute each
     slots = [pool, [torch.full_like(p, 0xA5) for p in pool]]
     cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     stt = K.kvl_stream_layers(s, None, slots, None, 0, 200, cs, ks, ms, n_layers=L, full_blocks=buf)
     out["stream_from_full_blocks_gbps"] = round(stt["link_gbps"], 2)
     out["stream_from_full_blocks_ms"] = round(stt["total_ms"], 2)
+    # beside a computation that keeps the GPU busy (2 x 4 GiB device copies per layer): what each
+    # form of the load costs that computation
+    a = torch.full((4 << 30,), 1, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+
+    def compute(layer, slot, stream_handle):
+        K.kvl_copy_linear(a, b, stream=stream_handle)
+        K.kvl_copy_linear(a, b, stream=stream_handle)
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(ms)
+    compute(0, 0, ms.cuda_stream)
+    e1.record(ms)
+    e1.synchronize()
+    busy = {"compute_ms_per_layer_alone": round(e0.elapsed_time(e1), 3)}
+    for name, stg, ch in (("zero_copy", None, 0), ("staged", staging, chunk)):
+        r = K.kvl_stream_layers(s, None, slots, stg, ch, 0, cs, ks, ms, n_layers=L, full_blocks=buf,
+                                compute=compute, per_layer_times=True)
+        during = (r["t_compute_end"] - r["t_compute_begin"])[:-1]
+        busy[name] = {"total_ms": round(r["total_ms"], 1), "compute_ms_per_layer": round(float(during.mean()), 3)}
+    out["beside_busy_compute"] = busy
+    del a, b
     s.destroy()
     return out
 

@@ -244,6 +244,17 @@ int kvl_fullblocks_to_pool_layer(const kvl_plan_t *plan, const void *full_blocks
  * belong to other layers or to rows outside the ranges are left as they are */
 int kvl_pool_to_fullblocks_layer(const kvl_plan_t *plan, const void *const *pool_planes, uint32_t layer,
                                  void *full_blocks, uint64_t full_blocks_bytes, void *stream);
+/* Staged form of kvl_fullblocks_to_pool_layer for a buffer the copy engine should
+ * read (pinned host memory above all): layer `layer` of the blocks is brought into
+ * the slots of dev_staging by strided copies (hipMemcpy2DAsync: per chunk of
+ * floor(chunk_bytes / LB) blocks, rows of LB bytes at a pitch of FB) and converted
+ * into the pool from there by a kernel per chunk, on the library's lanes and with
+ * the stream semantics of kvl_h2d_unpack_layer.  No wavefront waits on the host
+ * link, so the load does not hold compute units that other kernels need.
+ * KVL_ESPACE also if chunk_bytes < LB or staging_bytes < chunk_bytes. */
+int kvl_h2d_fullblocks_layer(const kvl_plan_t *plan, const void *full_blocks, uint64_t full_blocks_bytes,
+                             uint32_t layer, void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
+                             void *const *pool_planes, void *copy_stream, void *kernel_stream);
 
 /* Confine the scatter kernels of the host-buffer path to some compute units.
  * The paper isolates cache traffic from the model's own traffic with network QoS
@@ -311,9 +322,9 @@ typedef struct {
     /* Optional storage-layout source.  When full_blocks is not NULL the layers are
      * loaded from a buffer of the plan's Full Blocks (device memory, or pinned host
      * memory mapped into the device) as kvl_fullblocks_to_pool_layer does: layer l
-     * by one converting kernel on kernel_stream.  host_layers, the staging area,
-     * chunk_bytes, copy_stream and host_fill are then unused.  Needs a plan made
-     * with KVL_NO_MERGE. */
+     * by one converting kernel on kernel_stream (chunk_bytes == 0), or staged through
+     * dev_staging as kvl_h2d_fullblocks_layer does (chunk_bytes != 0).  host_layers and
+     * host_fill are then unused.  Needs a plan made with KVL_NO_MERGE. */
     const void *full_blocks;
     uint64_t full_blocks_bytes;
     /* Optional: the caller's computation instead of the synthetic kernel (compute_us

@@ -115,6 +115,8 @@ _SIGNATURES = {
                                                C.POINTER(C.c_void_p), C.c_void_p]),
     "kvl_pool_to_fullblocks_layer": (C.c_int, [_PLAN_P, C.POINTER(C.c_void_p), C.c_uint32, C.c_void_p,
                                                C.c_uint64, C.c_void_p]),
+    "kvl_h2d_fullblocks_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_uint64,
+                                           C.c_uint64, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p]),
     "kvl_plan_set_lane_cu_mask": (C.c_int, [_PLAN_P, C.POINTER(C.c_uint32), C.c_uint32]),
     "kvl_h2d_blockwise_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
                                           C.POINTER(C.c_uint64)]),
@@ -392,6 +394,17 @@ def kvl_fullblocks_to_pool_layer(plan: Plan, full_blocks: torch.Tensor, layer: i
     _check(_lib.kvl_fullblocks_to_pool_layer(plan.handle, _dev_or_pinned(full_blocks, "full_blocks"),
                                              _nbytes(full_blocks), layer, arr, _stream_handle(stream)),
            "kvl_fullblocks_to_pool_layer")
+
+
+def kvl_h2d_fullblocks_layer(plan: Plan, full_blocks: torch.Tensor, layer: int, dev_staging: torch.Tensor,
+                             chunk_bytes: int, pool_planes: Sequence[torch.Tensor], copy_stream,
+                             kernel_stream) -> None:
+    """Staged Full-Block load of one layer: strided copies into dev_staging, converting kernels from there."""
+    arr = _plane_ptrs(plan, pool_planes, "kvl_h2d_fullblocks_layer pool")
+    _check(_lib.kvl_h2d_fullblocks_layer(plan.handle, _dev_or_pinned(full_blocks, "full_blocks"),
+                                         _nbytes(full_blocks), layer, _dev(dev_staging, "staging"),
+                                         _nbytes(dev_staging), chunk_bytes, arr, _stream_handle(copy_stream),
+                                         _stream_handle(kernel_stream)), "kvl_h2d_fullblocks_layer")
 
 
 def kvl_pool_to_fullblocks_layer(plan: Plan, pool_planes: Sequence[torch.Tensor], layer: int,

@@ -100,6 +100,52 @@ int enqueue_zero_copy_layer(const kvl_plan_t *plan, const void *host_xfer, void 
                         pool_planes, xp, kern_s);
 }
 
+// Staging area of the staged Full-Block load: chunks hold whole Layer Blocks.
+int check_fullblock_staging(const kvl_plan_t *plan, const void *staging, uint64_t staging_bytes,
+                            uint64_t chunk_bytes, size_t *slots) {
+    if (chunk_bytes % 16 || reinterpret_cast<uintptr_t>(staging) % 16) return KVL_EINVAL;
+    if (chunk_bytes < layer_block_bytes(plan) || staging_bytes < chunk_bytes) return KVL_ESPACE;
+    if (!plan->units.empty() && !staging) return KVL_EINVAL;
+    *slots = (size_t)std::min<uint64_t>(staging_bytes / chunk_bytes, 8);
+    return KVL_OK;
+}
+
+// One layer from a buffer of Full Blocks through the staging slots: per chunk of
+// blocks one strided copy (rows of one Layer Block at a pitch of one Full Block)
+// and one converting kernel, on the lanes as in enqueue_h2d_layer.
+int enqueue_h2d_fullblocks_layer(kvl_plan_t *plan, const void *full_blocks, uint32_t layer,
+                                 void *dev_staging, uint64_t chunk_bytes, size_t lanes,
+                                 void *const *pool_planes, hipStream_t kern_s, hipEvent_t wait_before_scatter) {
+    const uint64_t lb = layer_block_bytes(plan), fb = lb * plan->layout.n_layers;
+    const uint64_t nb = plan->blocks_touched, per_chunk = chunk_bytes / lb;
+    if (plan->block_first_unit.size() != nb + 1) {
+        // descriptors of a KVL_NO_MERGE plan are in block order and every block has at least one
+        plan->block_first_unit.assign(nb + 1, (uint32_t)plan->units.size());
+        for (size_t i = plan->units.size(); i-- > 0;) plan->block_first_unit[plan->units[i].block_index] = (uint32_t)i;
+    }
+    const char *src = static_cast<const char *>(full_blocks) + (uint64_t)layer * lb;
+    char *stage = static_cast<char *>(dev_staging);
+    size_t i = 0;
+    for (uint64_t b0 = 0; b0 < nb; b0 += per_chunk, ++i) {
+        const uint64_t b1 = std::min(nb, b0 + per_chunk);
+        const size_t lane = i % lanes;
+        hipStream_t ls = plan->lanes[lane];
+        char *dst = stage + lane * chunk_bytes;
+        KVL_HIP(hipMemcpy2DAsync(dst, lb, src + b0 * fb, fb, lb, b1 - b0, hipMemcpyDefault, ls));
+        if (i < lanes && wait_before_scatter) KVL_HIP(hipStreamWaitEvent(ls, wait_before_scatter, 0));
+        // block k's Layer Block sits at dst + (k - b0) * lb
+        int rc = fullblock_launch(plan, true, reinterpret_cast<uintptr_t>(dst) - b0 * lb, lb, 0,
+                                  plan->block_first_unit[b0], plan->block_first_unit[b1], pool_planes, ls);
+        if (rc != KVL_OK) return rc;
+    }
+    const size_t used = std::min(i, lanes);
+    for (size_t j = 0; j < used; ++j) {
+        KVL_HIP(hipEventRecord(plan->ev_lane_done[j], plan->lanes[j]));
+        KVL_HIP(hipStreamWaitEvent(kern_s, plan->ev_lane_done[j], 0));
+    }
+    return KVL_OK;
+}
+
 int check_h2d_args(const kvl_plan_t *plan, const void *host, const void *staging,
                    uint64_t staging_bytes, uint64_t chunk_bytes, size_t *slots) {
     if (!plan) return KVL_EINVAL;
@@ -145,7 +191,46 @@ static int h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xf
                                   pool_planes, ks, nullptr);
 }
 
+static int h2d_fullblocks_layer(const kvl_plan_t *plan_c, const void *full_blocks, uint64_t full_blocks_bytes,
+                                uint32_t layer, void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
+                                void *const *pool_planes, void *copy_stream, void *kernel_stream) {
+    using namespace kvl;
+    kvl_plan_t *plan = const_cast<kvl_plan_t *>(plan_c);   // lanes, events and the block index are scratch state
+    if (!pool_planes) return KVL_EINVAL;
+    int rc = check_fullblock_args(plan, true, full_blocks_bytes, layer);
+    if (rc != KVL_OK) return rc;
+    size_t slots = 0;
+    rc = check_fullblock_staging(plan, dev_staging, staging_bytes, chunk_bytes, &slots);
+    if (rc != KVL_OK) return rc;
+    if (plan->units.empty()) return KVL_OK;
+    if (!full_blocks) return KVL_EINVAL;
+    const uint64_t fb = layer_block_bytes(plan) * plan->layout.n_layers;
+    rc = check_device(plan);
+    if (rc == KVL_OK) rc = check_pool(plan, pool_planes, plan->layout.pool_blocks);
+    if (rc == KVL_OK) rc = check_buffer(plan, full_blocks, plan->blocks_touched * fb, true);
+    if (rc == KVL_OK) rc = check_buffer(plan, dev_staging, slots * chunk_bytes, false);
+    if (rc != KVL_OK) return rc;
+    rc = ensure_lanes(plan, slots);
+    if (rc != KVL_OK) return rc;
+    hipStream_t cs = (hipStream_t)copy_stream, ks = (hipStream_t)kernel_stream;
+    rc = lanes_follow(plan, slots, cs, ks);
+    if (rc != KVL_OK) return rc;
+    return enqueue_h2d_fullblocks_layer(plan, full_blocks, layer, dev_staging, chunk_bytes, slots, pool_planes,
+                                        ks, nullptr);
+}
+
 extern "C" {
+
+int kvl_h2d_fullblocks_layer(const kvl_plan_t *plan, const void *full_blocks, uint64_t full_blocks_bytes,
+                             uint32_t layer, void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
+                             void *const *pool_planes, void *copy_stream, void *kernel_stream) {
+    try {
+        return h2d_fullblocks_layer(plan, full_blocks, full_blocks_bytes, layer, dev_staging, staging_bytes,
+                                    chunk_bytes, pool_planes, copy_stream, kernel_stream);
+    } catch (const std::bad_alloc &) {
+        return KVL_ENOMEM;
+    }
+}
 
 int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer, void *dev_staging,
                          uint64_t staging_bytes, uint64_t chunk_bytes, void *const *pool_planes,

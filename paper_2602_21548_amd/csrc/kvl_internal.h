@@ -21,6 +21,7 @@ struct kvl_plan_s {
     uint64_t blocks_touched = 0;                 // Full Blocks a buffer of this plan's ranges holds
     bool vec16 = false;                          // every row size is a multiple of 16 bytes
     std::vector<kvl_unit_t> units;               // host copy of the descriptors
+    std::vector<uint32_t> block_first_unit;      // KVL_NO_MERGE plans, made on demand: first descriptor of each block
     kvl_unit_t *d_units = nullptr;               // device copy (absent for KVL_HOST_ONLY)
     size_t d_units_capacity = 0;                 // bytes of the cached buffer d_units lives in
     int device = -1;
@@ -68,6 +69,12 @@ int check_pool(const kvl_plan_t *plan, const void *const *planes, uint64_t pool_
 int ensure_lanes(kvl_plan_t *plan, size_t lanes);
 int lanes_follow(kvl_plan_t *plan, size_t lanes, hipStream_t copy_s, hipStream_t kern_s);
 
+int check_device(const kvl_plan_t *plan);
+uint64_t layer_block_bytes(const kvl_plan_t *plan);
+int check_fullblock_args(const kvl_plan_t *plan, bool to_pool, uint64_t blocks_bytes, uint32_t layer);
+int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint64_t block_pitch,
+                     uint64_t layer_off, uint32_t unit_begin, uint32_t unit_end,
+                     void *const *pool_planes, hipStream_t stream);
 // Enqueue the move of one layer between a buffer of Full Blocks and a paged pool.
 int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint64_t blocks_bytes,
                     uint32_t layer, void *const *pool_planes, hipStream_t stream);

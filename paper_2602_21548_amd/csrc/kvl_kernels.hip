@@ -19,7 +19,7 @@ int check_pool(const kvl_plan_t *plan, const void *const *planes, uint64_t pool_
 }
 
 // The descriptors live on the device that was current when the plan was made.
-static int check_device(const kvl_plan_t *plan) {
+int check_device(const kvl_plan_t *plan) {
     int dev = -1;
     KVL_HIP(hipGetDevice(&dev));
     return dev == plan->device ? KVL_OK : KVL_EINVAL;
@@ -155,43 +155,37 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
     return KVL_OK;
 }
 
-int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint64_t blocks_bytes,
-                           uint32_t layer, void *const *pool_planes, hipStream_t stream) {
-    if (!plan || !pool_planes) return KVL_EINVAL;
-    if ((plan->flags & KVL_HOST_ONLY) || !(plan->flags & KVL_NO_MERGE)) return KVL_EINVAL;
-    if (!(plan->flags & (to_pool ? KVL_SCATTER : KVL_GATHER))) return KVL_EINVAL;
-    if (layer >= plan->layout.n_layers) return KVL_EINVAL;
+// Launch the layout-converting kernel on descriptors [unit_begin, unit_end).  A
+// descriptor of block index k finds its rows at
+//   base + k * block_pitch + layer_off + (plane span, row) inside the Layer Block;
+// for a buffer of Full Blocks block_pitch is the Full-Block size and layer_off the
+// layer's offset in it, for a staging area of Layer Blocks block_pitch is the
+// Layer-Block size and layer_off is 0 (base may then lie before the area).
+int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint64_t block_pitch,
+                     uint64_t layer_off, uint32_t unit_begin, uint32_t unit_end,
+                     void *const *pool_planes, hipStream_t stream) {
+    if (unit_end <= unit_begin) return KVL_OK;
+    if (!plan->d_units || unit_end > plan->units.size()) return KVL_EINVAL;
     const uint32_t P = plan->layout.n_planes;
     const uint64_t bs = plan->layout.block_tokens;
-    uint64_t lb = 0;
-    for (uint32_t p = 0; p < P; ++p) lb += bs * plan->layout.row_bytes[p];
-    const uint64_t fb = lb * plan->layout.n_layers;
-    if (blocks_bytes < plan->blocks_touched * fb) return KVL_ESPACE;
-    if (plan->units.empty()) return KVL_OK;
-    if (!blocks) return KVL_EINVAL;
-    int rc_dev = check_device(plan);
-    if (rc_dev == KVL_OK) rc_dev = check_pool(plan, pool_planes, plan->layout.pool_blocks);
-    if (rc_dev == KVL_OK)
-        rc_dev = check_buffer(plan, reinterpret_cast<const void *>(blocks), plan->blocks_touched * fb, true);
-    if (rc_dev != KVL_OK) return rc_dev;
-    bool vec = plan->vec16 && blocks % 16 == 0;
+    bool vec = plan->vec16 && base % 16 == 0 && block_pitch % 16 == 0 && layer_off % 16 == 0;
     for (uint32_t p = 0; p < P; ++p) {
         if (!pool_planes[p]) return KVL_EINVAL;
         vec = vec && reinterpret_cast<uintptr_t>(pool_planes[p]) % 16 == 0;
     }
     const uint64_t e = vec ? 16 : 1;          // element size
     FullBlockArgs a{};
-    a.units = plan->d_units;
-    a.n_units = (uint32_t)plan->units.size();
+    a.units = plan->d_units + unit_begin;
+    a.n_units = unit_end - unit_begin;
     a.block_tokens = plan->layout.block_tokens;
-    a.blocks = blocks;
-    a.fb_elems = fb / e;
+    a.blocks = base;
+    a.fb_elems = block_pitch / e;
     uint64_t plane_off = 0;
     uint32_t max_row = 0;
     for (uint32_t p = 0; p < P; ++p) {
         a.row_elems[p] = (uint32_t)(plan->layout.row_bytes[p] / e);
         a.pool[p] = reinterpret_cast<uintptr_t>(pool_planes[p]);
-        a.layer_plane_off[p] = ((uint64_t)layer * lb + plane_off) / e;
+        a.layer_plane_off[p] = (layer_off + plane_off) / e;
         plane_off += bs * plan->layout.row_bytes[p];
         max_row = std::max(max_row, a.row_elems[p]);
     }
@@ -209,6 +203,42 @@ int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint
     }
     KVL_HIP(hipGetLastError());
     return KVL_OK;
+}
+
+// Bytes of one Layer Block (all planes of one block, one layer).
+uint64_t layer_block_bytes(const kvl_plan_t *plan) {
+    uint64_t lb = 0;
+    for (uint32_t p = 0; p < plan->layout.n_planes; ++p)
+        lb += (uint64_t)plan->layout.block_tokens * plan->layout.row_bytes[p];
+    return lb;
+}
+
+// What every Full-Block call asks of its plan and sizes.
+int check_fullblock_args(const kvl_plan_t *plan, bool to_pool, uint64_t blocks_bytes, uint32_t layer) {
+    if (!plan) return KVL_EINVAL;
+    if ((plan->flags & KVL_HOST_ONLY) || !(plan->flags & KVL_NO_MERGE)) return KVL_EINVAL;
+    if (!(plan->flags & (to_pool ? KVL_SCATTER : KVL_GATHER))) return KVL_EINVAL;
+    if (layer >= plan->layout.n_layers) return KVL_EINVAL;
+    const uint64_t fb = layer_block_bytes(plan) * plan->layout.n_layers;
+    if (blocks_bytes < plan->blocks_touched * fb) return KVL_ESPACE;
+    return KVL_OK;
+}
+
+int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint64_t blocks_bytes,
+                    uint32_t layer, void *const *pool_planes, hipStream_t stream) {
+    if (!pool_planes) return KVL_EINVAL;
+    int rc = check_fullblock_args(plan, to_pool, blocks_bytes, layer);
+    if (rc != KVL_OK) return rc;
+    if (plan->units.empty()) return KVL_OK;
+    if (!blocks) return KVL_EINVAL;
+    const uint64_t lb = layer_block_bytes(plan), fb = lb * plan->layout.n_layers;
+    rc = check_device(plan);
+    if (rc == KVL_OK) rc = check_pool(plan, pool_planes, plan->layout.pool_blocks);
+    if (rc == KVL_OK)
+        rc = check_buffer(plan, reinterpret_cast<const void *>(blocks), plan->blocks_touched * fb, true);
+    if (rc != KVL_OK) return rc;
+    return fullblock_launch(plan, to_pool, blocks, fb, (uint64_t)layer * lb, 0, (uint32_t)plan->units.size(),
+                            pool_planes, stream);
 }
 
 }  // namespace kvl

@@ -26,6 +26,11 @@ int check_h2d_args(const kvl_plan_t *plan, const void *host, const void *staging
                    uint64_t staging_bytes, uint64_t chunk_bytes, size_t *slots);
 int enqueue_zero_copy_layer(const kvl_plan_t *plan, const void *host_xfer, void *const *pool_planes,
                             hipStream_t kern_s, hipEvent_t wait_before_scatter);
+int check_fullblock_staging(const kvl_plan_t *plan, const void *staging, uint64_t staging_bytes,
+                            uint64_t chunk_bytes, size_t *slots);
+int enqueue_h2d_fullblocks_layer(kvl_plan_t *plan, const void *full_blocks, uint32_t layer,
+                                 void *dev_staging, uint64_t chunk_bytes, size_t lanes,
+                                 void *const *pool_planes, hipStream_t kern_s, hipEvent_t wait_before_scatter);
 
 struct SlotPlanes {
     uintptr_t base[KVL_MAX_PLANES];
@@ -92,6 +97,12 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
         if (!(plan->flags & KVL_SCATTER) || (plan->flags & KVL_HOST_ONLY) || !(plan->flags & KVL_NO_MERGE))
             return KVL_EINVAL;
         if (L > plan->layout.n_layers) return KVL_EINVAL;
+        rc = check_fullblock_args(plan, true, cfg->full_blocks_bytes, L - 1);
+        if (rc != KVL_OK) return rc;
+        if (cfg->chunk_bytes) {         // staged form: the copy engine brings the Layer Blocks in
+            rc = check_fullblock_staging(plan, cfg->dev_staging, cfg->staging_bytes, cfg->chunk_bytes, &slots);
+            if (rc != KVL_OK) return rc;
+        }
     } else {
         rc = check_h2d_args(plan, cfg->host_layers[0], cfg->dev_staging, cfg->staging_bytes,
                             cfg->chunk_bytes, &slots);
@@ -107,9 +118,9 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
         if (!from_blocks) {
             for (uint32_t h = 0; h < H && rc == KVL_OK; ++h)
                 rc = check_buffer(plan, cfg->host_layers[h], plan->payload_bytes, true);
-            if (rc == KVL_OK && cfg->chunk_bytes)
-                rc = check_buffer(plan, cfg->dev_staging, slots * cfg->chunk_bytes, false);
         }
+        if (rc == KVL_OK && cfg->chunk_bytes)
+            rc = check_buffer(plan, cfg->dev_staging, slots * cfg->chunk_bytes, false);
         if (rc != KVL_OK) return rc;
     }
     if (cfg->n_probes) {
@@ -180,14 +191,20 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
     KVL_HIP(hipStreamWaitEvent(ms, ev_start, 0));
 
     // the lanes start where the three streams start
-    if (!from_blocks && !zero_copy) {
+    const bool staged_blocks = from_blocks && cfg->chunk_bytes != 0;
+    if ((!from_blocks && !zero_copy) || staged_blocks) {
         rc = lanes_follow(plan, slots, cs, ks);
         if (rc != KVL_OK) return rc;
     }
     for (uint32_t l = 0; l < L; ++l) {
         const uint32_t s = l % S;
         void *const *slot_planes = cfg->dev_slot_planes + (size_t)s * P;
-        if (from_blocks) {
+        if (staged_blocks) {
+            rc = plan->units.empty() ? KVL_OK
+                                     : enqueue_h2d_fullblocks_layer(plan, cfg->full_blocks, l, cfg->dev_staging,
+                                                                    cfg->chunk_bytes, slots, slot_planes, ks,
+                                                                    l >= S ? cend[l - S] : nullptr);
+        } else if (from_blocks) {
             // the slot may be overwritten once the compute that read it has finished
             if (l >= S) KVL_HIP(hipStreamWaitEvent(ks, cend[l - S], 0));
             rc = fullblock_layer(plan, true, reinterpret_cast<uintptr_t>(cfg->full_blocks),

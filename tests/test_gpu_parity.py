@@ -356,6 +356,25 @@ def test_full_block_layout(name, make, where, flag):
         st.synchronize()
         for a, b in zip(got, want):
             assert same_bytes(to_host(a), b), f"layer {l} loaded from Full Blocks differs from the oracle"
+        # the same load staged through HBM by the copy engine: 1 or 3 Layer Blocks per chunk, 1 or 2 slots
+        lb = fb // L
+        for blocks_per_chunk, n_slots in ((1, 1), (3, 2)):
+            chunk = -(-blocks_per_chunk * lb // 16) * 16
+            staging = torch.zeros(n_slots * chunk, dtype=torch.uint8, device="cuda")
+            got = planes_to_dev(W.sentinel_pool(w, "dst"))
+            cs = torch.cuda.Stream()
+            torch.cuda.synchronize()
+            K.kvl_h2d_fullblocks_layer(s, buf, l, staging, chunk, got, cs, st)
+            st.synchronize()
+            cs.synchronize()
+            for a, b in zip(got, want):
+                assert same_bytes(to_host(a), b), f"layer {l} staged from Full Blocks differs from the oracle"
+    if fb // L >= 32:
+        tiny_stage = torch.zeros(max(16, (fb // L) // 2 // 16 * 16), dtype=torch.uint8, device="cuda")
+        with pytest.raises(K.KvlError) as e:       # a chunk smaller than one Layer Block
+            K.kvl_h2d_fullblocks_layer(s, buf, 0, tiny_stage, tiny_stage.numel(), planes_to_dev(W.sentinel_pool(w, "dst")),
+                                       st, st)
+        assert e.value.code == K.KVL_ESPACE
     # errors: merged plan, short buffer, layer out of range
     merged = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables, K.KVL_SCATTER | flag)
     pool = planes_to_dev(W.sentinel_pool(w, "dst"))
@@ -447,7 +466,7 @@ def test_stream_layers_observables(S, H, chunk):
 
 
 @pytest.mark.parametrize("S", [1, 2])
-@pytest.mark.parametrize("where", ["device", "pinned"])
+@pytest.mark.parametrize("where", ["device", "pinned", "pinned-staged"])
 def test_stream_layers_from_full_blocks(S, where):
     """Layer-wise load straight from the storage layout: what each layer's compute sees."""
     L = 5
@@ -466,9 +485,12 @@ def test_stream_layers_from_full_blocks(S, where):
     buf = to_dev(blocks) if where == "device" else pinned_from(blocks)
     slots = [planes_to_dev(W.sentinel_pool(w, "dst", 0xEE)) for _ in range(S)]
     snaps = [[torch.zeros_like(pl) for pl in slots[0]] for _ in range(L)]
+    # staged: the copy engine brings 5 Layer Blocks at a time into each of 3 staging slots
+    chunk = 5 * (fb // L) if where == "pinned-staged" else 0
+    staging = torch.zeros(3 * chunk, dtype=torch.uint8, device="cuda") if chunk else None
     torch.cuda.synchronize()
     cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
-    st = K.kvl_stream_layers(s, None, slots, None, 0, 50, cs, ks, ms, n_layers=L, snapshots=snaps,
+    st = K.kvl_stream_layers(s, None, slots, staging, chunk, 50, cs, ks, ms, n_layers=L, snapshots=snaps,
                              per_layer_times=True, full_blocks=buf)
     for l in range(L):
         for p in range(len(rows)):
