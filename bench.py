@@ -550,8 +550,17 @@ def host_link_legs(args) -> dict:
         K.kvl_pack_layer(gplan, slots[0], host[1], stream=ks)
         ks.synchronize()
         d2h.append(time.perf_counter() - t0)
-    gplan.destroy()
     d2h_gbps = payload / min(d2h) / 1e9
+    d2h = []
+    for _ in range(3):                 # the same gather staged: pack kernels into HBM slots, copy engine out
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        K.kvl_d2h_pack_layer(gplan, slots[0], staging, chunk, host[1], ks, cs)
+        ks.synchronize()
+        cs.synchronize()
+        d2h.append(time.perf_counter() - t0)
+    gplan.destroy()
+    d2h_staged_gbps = payload / min(d2h) / 1e9
     # the same 61 layers with the zero-copy form (scatter kernel reads the pinned buffers itself)
     zc = K.kvl_stream_layers(plan, host, slots, None, 0, w.notes["compute_us"], cs, ks, ms, n_layers=L)
     plan.destroy()
@@ -568,6 +577,7 @@ def host_link_legs(args) -> dict:
         "stream_gbps": round(st["link_gbps"], 2), "stream_frac_of_link": round(st["link_gbps"] / peak, 4),
         "stream_exposed_ms": round(st["exposed_ms"], 2),
         "pack_to_host_layer_gbps": round(d2h_gbps, 2),
+        "pack_to_host_staged_layer_gbps": round(d2h_staged_gbps, 2),
         "stream_zero_copy_gbps": round(zc["link_gbps"], 2),
         "stream_zero_copy_frac_of_link": round(zc["link_gbps"] / peak, 4),
         "payload_bytes_per_layer": payload,

@@ -220,6 +220,19 @@ int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
                          void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
                          void *const *pool_planes, void *copy_stream, void *kernel_stream);
 
+/* The way out of the prefill engine (Section 4.1: as a layer is computed its cache is
+ * sent on to the decode engine's buffer in host memory): the staged form of
+ * kvl_pack_layer with a pinned host destination.  The gather runs chunk by chunk
+ * into the slots of dev_staging and every packed chunk is copied to its place in
+ * pinned_host_xfer by the copy engine (hipMemcpyAsync), on the library's lanes; no
+ * wavefront waits on the host link.  Ordered after everything enqueued on both
+ * streams; the host buffer is complete when kernel_stream reaches the end of the
+ * enqueued work.  Chunking, slots and errors as in kvl_h2d_unpack_layer
+ * (chunk_bytes must not be 0); needs a KVL_GATHER plan. */
+int kvl_d2h_pack_layer(const kvl_plan_t *plan, const void *const *pool_planes, void *dev_staging,
+                       uint64_t staging_bytes, uint64_t chunk_bytes, void *pinned_host_xfer,
+                       uint64_t host_capacity, void *kernel_stream, void *copy_stream);
+
 /* Storage layout (Section 4.1 "Different Block Layouts", Appendix A.5).  All
  * traffic with storage uses Full Blocks, byte tensors [layer, tokens, bytes] that
  * are the concatenation of one block's Layer Blocks; with several planes a Layer

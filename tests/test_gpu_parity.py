@@ -835,3 +835,46 @@ def test_stream_layers_with_the_callers_own_compute(S, chunk):
                             probes=[(0, 0)], probe_out=torch.zeros(L * 16, dtype=torch.uint8, device="cuda"),
                             compute=compute)
     assert e.value.code == K.KVL_EINVAL
+
+
+@pytest.mark.parametrize("name,make", H2D_CASES, ids=[c[0] for c in H2D_CASES])
+@pytest.mark.parametrize("chunk_kb,slots", [(64, 1), (64, 3), (1024, 2), (16, 8)])
+def test_d2h_pack_staged(name, make, chunk_kb, slots):
+    """The gather into a pinned host buffer, staged: pack kernels into HBM slots, copy engine out."""
+    w = make()
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    g = dev_plan(w, "src", K.KVL_GATHER, unit_bytes=16384)
+    n = g.payload_bytes
+    chunk = chunk_kb * 1024
+    staging = torch.zeros(chunk * slots, dtype=torch.uint8, device="cuda")
+    cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+    hosts, wants = [], []
+    torch.cuda.synchronize()
+    for layer in (0, 1):                      # two layers through the same slots, queued at once
+        src = W.fill_pool(w, layer, "src")
+        wants.append(oracle.pack(bs, rows, w.hit, w.src.tables, src))
+        host = torch.full((n + 64,), 0x3C, dtype=torch.uint8).pin_memory()
+        d_src = planes_to_dev(src)
+        torch.cuda.synchronize()
+        K.kvl_d2h_pack_layer(g, d_src, staging, chunk, host, ks, cs)
+        hosts.append((host, d_src))
+    ks.synchronize()
+    cs.synchronize()
+    for (host, _), want in zip(hosts, wants):
+        got = host.numpy()
+        assert same_bytes(got[:n], want), "staged gather into host memory differs from the oracle"
+        assert np.all(got[n:] == 0x3C), "wrote past the payload"
+    # a scatter plan, a chunk of 0 and a short host buffer are refused
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    d_src = hosts[0][1]
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_d2h_pack_layer(s, planes_to_dev(W.sentinel_pool(w, "dst")), staging, chunk, hosts[0][0], ks, cs)
+    assert e.value.code == K.KVL_EINVAL
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_d2h_pack_layer(g, d_src, staging, 0, hosts[0][0], ks, cs)
+    assert e.value.code == K.KVL_EINVAL
+    if n > 16:
+        short = torch.zeros(n - 16, dtype=torch.uint8).pin_memory()
+        with pytest.raises(K.KvlError) as e:
+            K.kvl_d2h_pack_layer(g, d_src, staging, chunk, short, ks, cs)
+        assert e.value.code == K.KVL_ESPACE
