@@ -676,6 +676,18 @@ def full_block_leg(pinned: "torch.Tensor", h2d_peak: float) -> dict:
         best = max(best, per_layer * L / (e0.elapsed_time(e1) * 1e-3) / 1e9)
     out["h2d_staged_gbps"] = round(best, 2)
     out["h2d_staged_frac_of_link"] = round(best / h2d_peak, 4)
+    best = 0.0
+    for rep in range(3):               # and the persist direction, staged
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(st)
+        for l in range(L):
+            K.kvl_d2h_fullblocks_layer(s, pool, l, staging, chunk, buf, st, cs)
+        e1.record(st)
+        e1.synchronize()
+        cs.synchronize()
+        best = max(best, per_layer * L / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    out["d2h_staged_gbps"] = round(best, 2)
     # the streamed load with the storage layout as its source: 61 layers under 200 us of compute each
     slots = [pool, [torch.full_like(p, 0xA5) for p in pool]]
     cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()

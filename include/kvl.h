@@ -269,6 +269,18 @@ int kvl_h2d_fullblocks_layer(const kvl_plan_t *plan, const void *full_blocks, ui
                              uint32_t layer, void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
                              void *const *pool_planes, void *copy_stream, void *kernel_stream);
 
+/* Staged form of kvl_pool_to_fullblocks_layer (persisting a layer beside a busy
+ * GPU): a kernel per chunk of blocks lays the rows out as Layer Blocks in a staging
+ * slot, and the copy engine writes them into the buffer: runs of wholly covered
+ * blocks with one strided copy each, the rows of a partly covered block (the ends
+ * of a request's range) with one copy per plane.  As with the one-kernel form no
+ * byte outside the plan's rows is written.  Streams, slots and errors as in
+ * kvl_h2d_fullblocks_layer; needs a KVL_GATHER | KVL_NO_MERGE plan. */
+int kvl_d2h_fullblocks_layer(const kvl_plan_t *plan, const void *const *pool_planes, uint32_t layer,
+                             void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
+                             void *full_blocks, uint64_t full_blocks_bytes, void *kernel_stream,
+                             void *copy_stream);
+
 /* Confine the scatter kernels of the host-buffer path to some compute units.
  * The paper isolates cache traffic from the model's own traffic with network QoS
  * (Section 5.1); on the GPU the matching question is how many compute units the

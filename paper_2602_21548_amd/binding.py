@@ -115,6 +115,8 @@ _SIGNATURES = {
                                                C.POINTER(C.c_void_p), C.c_void_p]),
     "kvl_pool_to_fullblocks_layer": (C.c_int, [_PLAN_P, C.POINTER(C.c_void_p), C.c_uint32, C.c_void_p,
                                                C.c_uint64, C.c_void_p]),
+    "kvl_d2h_fullblocks_layer": (C.c_int, [_PLAN_P, C.POINTER(C.c_void_p), C.c_uint32, C.c_void_p, C.c_uint64,
+                                           C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
     "kvl_d2h_pack_layer": (C.c_int, [_PLAN_P, C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_uint64,
                                      C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]),
     "kvl_h2d_fullblocks_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p, C.c_uint64,
@@ -396,6 +398,18 @@ def kvl_fullblocks_to_pool_layer(plan: Plan, full_blocks: torch.Tensor, layer: i
     _check(_lib.kvl_fullblocks_to_pool_layer(plan.handle, _dev_or_pinned(full_blocks, "full_blocks"),
                                              _nbytes(full_blocks), layer, arr, _stream_handle(stream)),
            "kvl_fullblocks_to_pool_layer")
+
+
+def kvl_d2h_fullblocks_layer(plan: Plan, pool_planes: Sequence[torch.Tensor], layer: int,
+                             dev_staging: torch.Tensor, chunk_bytes: int, full_blocks: torch.Tensor,
+                             kernel_stream, copy_stream) -> None:
+    """Staged persist of one layer: converting kernels into dev_staging, copy engine into the Full Blocks."""
+    arr = _plane_ptrs(plan, pool_planes, "kvl_d2h_fullblocks_layer pool")
+    _check(_lib.kvl_d2h_fullblocks_layer(plan.handle, arr, layer, _dev(dev_staging, "staging"),
+                                         _nbytes(dev_staging), chunk_bytes,
+                                         _dev_or_pinned(full_blocks, "full_blocks"), _nbytes(full_blocks),
+                                         _stream_handle(kernel_stream), _stream_handle(copy_stream)),
+           "kvl_d2h_fullblocks_layer")
 
 
 def kvl_d2h_pack_layer(plan: Plan, pool_planes: Sequence[torch.Tensor], dev_staging: torch.Tensor,

@@ -110,6 +110,24 @@ int check_fullblock_staging(const kvl_plan_t *plan, const void *staging, uint64_
     return KVL_OK;
 }
 
+// Per block of a KVL_NO_MERGE plan: its first descriptor and the rows it moves.
+// Descriptors of such a plan are in block order and every block has at least one.
+static void block_index(kvl_plan_t *plan) {
+    const uint64_t nb = plan->blocks_touched;
+    if (plan->block_first_unit.size() == nb + 1) return;
+    const uint32_t bs = plan->layout.block_tokens;
+    plan->block_first_unit.assign(nb + 1, (uint32_t)plan->units.size());
+    plan->block_row_lo.assign(nb, bs);
+    plan->block_row_hi.assign(nb, 0);
+    for (size_t i = plan->units.size(); i-- > 0;) {
+        const kvl_unit_t &u = plan->units[i];
+        const uint32_t lo = u.pool_row % bs;
+        plan->block_first_unit[u.block_index] = (uint32_t)i;
+        plan->block_row_lo[u.block_index] = std::min(plan->block_row_lo[u.block_index], lo);
+        plan->block_row_hi[u.block_index] = std::max(plan->block_row_hi[u.block_index], lo + u.n_rows);
+    }
+}
+
 // One layer from a buffer of Full Blocks through the staging slots: per chunk of
 // blocks one strided copy (rows of one Layer Block at a pitch of one Full Block)
 // and one converting kernel, on the lanes as in enqueue_h2d_layer.
@@ -118,11 +136,7 @@ int enqueue_h2d_fullblocks_layer(kvl_plan_t *plan, const void *full_blocks, uint
                                  void *const *pool_planes, hipStream_t kern_s, hipEvent_t wait_before_scatter) {
     const uint64_t lb = layer_block_bytes(plan), fb = lb * plan->layout.n_layers;
     const uint64_t nb = plan->blocks_touched, per_chunk = chunk_bytes / lb;
-    if (plan->block_first_unit.size() != nb + 1) {
-        // descriptors of a KVL_NO_MERGE plan are in block order and every block has at least one
-        plan->block_first_unit.assign(nb + 1, (uint32_t)plan->units.size());
-        for (size_t i = plan->units.size(); i-- > 0;) plan->block_first_unit[plan->units[i].block_index] = (uint32_t)i;
-    }
+    block_index(plan);
     const char *src = static_cast<const char *>(full_blocks) + (uint64_t)layer * lb;
     char *stage = static_cast<char *>(dev_staging);
     size_t i = 0;
@@ -242,6 +256,80 @@ static int d2h_pack_layer(const kvl_plan_t *plan_c, const void *const *pool_plan
     return KVL_OK;
 }
 
+// Persist direction: one layer of the pool into a buffer of Full Blocks through the
+// staging slots.  The kernel lays the blocks' rows out as Layer Blocks in a slot; the
+// copy engine then writes runs of whole blocks with one strided copy each, and the
+// rows of partly covered blocks (the ends of a request's range) with one plain copy
+// per plane, so that no byte outside the plan's rows is written.
+static int d2h_fullblocks_layer(const kvl_plan_t *plan_c, const void *const *pool_planes, uint32_t layer,
+                                void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
+                                void *full_blocks, uint64_t full_blocks_bytes, void *kernel_stream,
+                                void *copy_stream) {
+    using namespace kvl;
+    kvl_plan_t *plan = const_cast<kvl_plan_t *>(plan_c);
+    if (!pool_planes) return KVL_EINVAL;
+    int rc = check_fullblock_args(plan, false, full_blocks_bytes, layer);
+    if (rc != KVL_OK) return rc;
+    size_t slots = 0;
+    rc = check_fullblock_staging(plan, dev_staging, staging_bytes, chunk_bytes, &slots);
+    if (rc != KVL_OK) return rc;
+    if (plan->units.empty()) return KVL_OK;
+    if (!full_blocks) return KVL_EINVAL;
+    const uint32_t P = plan->layout.n_planes, bs = plan->layout.block_tokens;
+    const uint64_t lb = layer_block_bytes(plan), fb = lb * plan->layout.n_layers;
+    const uint64_t nb = plan->blocks_touched, per_chunk = chunk_bytes / lb;
+    rc = check_device(plan);
+    if (rc == KVL_OK) rc = check_pool(plan, pool_planes, plan->layout.pool_blocks);
+    if (rc == KVL_OK) rc = check_buffer(plan, full_blocks, nb * fb, true);
+    if (rc == KVL_OK) rc = check_buffer(plan, dev_staging, slots * chunk_bytes, false);
+    if (rc != KVL_OK) return rc;
+    rc = ensure_lanes(plan, slots);
+    if (rc != KVL_OK) return rc;
+    hipStream_t cs = (hipStream_t)copy_stream, ks = (hipStream_t)kernel_stream;
+    rc = lanes_follow(plan, slots, cs, ks);
+    if (rc != KVL_OK) return rc;
+    block_index(plan);
+    char *out = static_cast<char *>(full_blocks) + (uint64_t)layer * lb;
+    char *stage = static_cast<char *>(dev_staging);
+    size_t i = 0;
+    for (uint64_t b0 = 0; b0 < nb; b0 += per_chunk, ++i) {
+        const uint64_t b1 = std::min(nb, b0 + per_chunk);
+        const size_t lane = i % slots;
+        hipStream_t ls = plan->lanes[lane];
+        char *slot = stage + lane * chunk_bytes;
+        rc = fullblock_launch(plan, false, reinterpret_cast<uintptr_t>(slot) - b0 * lb, lb, 0,
+                              plan->block_first_unit[b0], plan->block_first_unit[b1],
+                              const_cast<void *const *>(pool_planes), ls);
+        if (rc != KVL_OK) return rc;
+        uint64_t b = b0;
+        while (b < b1) {
+            const bool whole = plan->block_row_lo[b] == 0 && plan->block_row_hi[b] == bs;
+            if (whole) {
+                uint64_t e = b + 1;
+                while (e < b1 && plan->block_row_lo[e] == 0 && plan->block_row_hi[e] == bs) ++e;
+                KVL_HIP(hipMemcpy2DAsync(out + b * fb, fb, slot + (b - b0) * lb, lb, lb, e - b, hipMemcpyDefault, ls));
+                b = e;
+            } else {
+                const uint64_t lo = plan->block_row_lo[b], hi = plan->block_row_hi[b];
+                uint64_t plane_off = 0;
+                for (uint32_t p = 0; p < P; ++p) {
+                    const uint64_t row = plan->layout.row_bytes[p], at = plane_off + lo * row;
+                    KVL_HIP(hipMemcpyAsync(out + b * fb + at, slot + (b - b0) * lb + at, (hi - lo) * row,
+                                           hipMemcpyDefault, ls));
+                    plane_off += (uint64_t)bs * row;
+                }
+                ++b;
+            }
+        }
+    }
+    const size_t used = std::min(i, slots);
+    for (size_t j = 0; j < used; ++j) {
+        KVL_HIP(hipEventRecord(plan->ev_lane_done[j], plan->lanes[j]));
+        KVL_HIP(hipStreamWaitEvent(ks, plan->ev_lane_done[j], 0));
+    }
+    return KVL_OK;
+}
+
 static int h2d_fullblocks_layer(const kvl_plan_t *plan_c, const void *full_blocks, uint64_t full_blocks_bytes,
                                 uint32_t layer, void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
                                 void *const *pool_planes, void *copy_stream, void *kernel_stream) {
@@ -278,6 +366,18 @@ int kvl_h2d_fullblocks_layer(const kvl_plan_t *plan, const void *full_blocks, ui
     try {
         return h2d_fullblocks_layer(plan, full_blocks, full_blocks_bytes, layer, dev_staging, staging_bytes,
                                     chunk_bytes, pool_planes, copy_stream, kernel_stream);
+    } catch (const std::bad_alloc &) {
+        return KVL_ENOMEM;
+    }
+}
+
+int kvl_d2h_fullblocks_layer(const kvl_plan_t *plan, const void *const *pool_planes, uint32_t layer,
+                             void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
+                             void *full_blocks, uint64_t full_blocks_bytes, void *kernel_stream,
+                             void *copy_stream) {
+    try {
+        return d2h_fullblocks_layer(plan, pool_planes, layer, dev_staging, staging_bytes, chunk_bytes,
+                                    full_blocks, full_blocks_bytes, kernel_stream, copy_stream);
     } catch (const std::bad_alloc &) {
         return KVL_ENOMEM;
     }

@@ -347,6 +347,20 @@ def test_full_block_layout(name, make, where, flag):
     st.synchronize()
     got_buf = to_host(buf) if where == "device" else buf.numpy()
     assert same_bytes(got_buf, want_buf), "Full-Block buffer differs from the oracle"
+    # the same persist staged through HBM (kernel into a slot, copy engine out), 2 Layer Blocks per chunk
+    if fb * nfb:
+        buf2 = torch.full((nbytes + 64,), 0x5A, dtype=torch.uint8, device="cuda") if where == "device" else \
+            torch.full((nbytes + 64,), 0x5A, dtype=torch.uint8).pin_memory()
+        chunk = -(-2 * (fb // L) // 16) * 16
+        staging = torch.zeros(3 * chunk, dtype=torch.uint8, device="cuda")
+        cs2 = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        for l in range(L):
+            K.kvl_d2h_fullblocks_layer(g, srcs[l], l, staging, chunk, buf2, st, cs2)
+        st.synchronize()
+        cs2.synchronize()
+        got2 = to_host(buf2) if where == "device" else buf2.numpy()
+        assert same_bytes(got2, want_buf), "staged Full-Block buffer differs from the oracle"
     for l in (L - 1, 0):
         want = W.sentinel_pool(w, "dst")
         oracle.fullblocks_to_pool(bs, L, rows, first, count, w.dst.tables, l, want_buf, want)
