@@ -561,6 +561,7 @@ def host_link_legs(args) -> dict:
         d2h.append(time.perf_counter() - t0)
     gplan.destroy()
     d2h_staged_gbps = payload / min(d2h) / 1e9
+    duplex = duplex_leg(w, lay, plan, host, slots, staging, chunk, cs, ks, ms, min(L, 16), peak)
     # the same 61 layers with the zero-copy form (scatter kernel reads the pinned buffers itself)
     zc = K.kvl_stream_layers(plan, host, slots, None, 0, w.notes["compute_us"], cs, ks, ms, n_layers=L)
     plan.destroy()
@@ -568,7 +569,7 @@ def host_link_legs(args) -> dict:
     torch.cuda.empty_cache()
     fullblocks = full_block_leg(host[0], peak)
     return {
-        "full_blocks": fullblocks, "stream_under_hbm_bound_compute": busy,
+        "full_blocks": fullblocks, "stream_under_hbm_bound_compute": busy, "stream_with_outflow": duplex,
         "workload": "cfg5 streamed MLA: 61 layers x 1152 B rows, 128 req, pinned host buffer -> paged HBM, "
                     "200 us synthetic compute per layer",
         "h2d_peak_gbps": round(peak, 2), "chunk_bytes": chunk, "staging_slots": 4,
@@ -582,6 +583,29 @@ def host_link_legs(args) -> dict:
         "stream_zero_copy_frac_of_link": round(zc["link_gbps"] / peak, 4),
         "payload_bytes_per_layer": payload,
     }
+
+
+def duplex_leg(w, lay, plan, host, slots, staging, chunk, cs, ks, ms, layers, peak) -> dict:
+    """The whole loop of layer-wise prefill: while layer l+1 is loaded and layer l computed
+    (200 us stand-in), layer l-1 -- hit and appended rows -- is gathered out to pinned host
+    memory.  Both directions of the host link carry a layer at a time."""
+    import torch
+    import paper_2602_21548_amd as K
+    out = K.kvl_plan(lay, w.hit, w.app, w.dst.tables, K.KVL_GATHER | K.KVL_TOKENS_ALL)
+    out_host = [torch.empty(out.payload_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+    out_staging = torch.empty(4 * chunk, dtype=torch.uint8, device="cuda")
+    res = {"layers": layers, "out_payload_bytes_per_layer": out.payload_bytes,
+           "note": "rates over the whole run; the outflow of the last layer runs after the last load"}
+    for name, stg, ostg, ch in (("staged_both_ways", staging, out_staging, chunk), ("zero_copy_both_ways", None, None, 0)):
+        st = K.kvl_stream_layers(plan, host, slots, stg, ch, w.notes["compute_us"], cs, ks, ms, n_layers=layers,
+                                 out_plan=out, out_host_layers=out_host, out_staging=ostg, out_chunk_bytes=ch)
+        res[name] = {"total_ms": round(st["total_ms"], 2), "h2d_gbps": round(st["link_gbps"], 2),
+                     "d2h_gbps": round(st["out_gbps"], 2),
+                     "both_ways_gbps": round(st["link_gbps"] + st["out_gbps"], 2)}
+    out.destroy()
+    del out_host, out_staging
+    torch.cuda.empty_cache()
+    return res
 
 
 def stream_under_busy_compute(plan, host, slots, staging, chunk, cs, ks, ms, layers, peak) -> dict:

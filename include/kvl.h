@@ -356,10 +356,30 @@ typedef struct {
      * and the probes are then unused; snapshots are still taken after it). */
     kvl_compute_fn compute;
     void *compute_user;
+    /* Optional outflow (Section 4.1: once a layer has been computed its cache, hit and
+     * appended tokens alike, leaves for the decode engine's buffer while the next
+     * layers are loaded and computed).  After the compute of layer l, out_plan (a
+     * KVL_GATHER plan over the same pool geometry, typically KVL_TOKENS_ALL) gathers
+     * slot l % S into out_host_layers[l % n_out_host_slots] (pinned host memory of
+     * out_plan's payload size): staged through out_staging as kvl_d2h_pack_layer does
+     * (out_chunk_bytes != 0) or by a kernel that writes the host buffer itself
+     * (out_chunk_bytes == 0).  The load of layer l + S then waits for that gather
+     * rather than for the compute alone.  host_drain, if given, is called on the
+     * calling thread with (user, l, buffer, payload bytes of out_plan) once layer l
+     * has arrived in its buffer and before the buffer is reused: the place where the
+     * send to the decode engine would go. */
+    const kvl_plan_t *out_plan;
+    uint32_t n_out_host_slots;
+    void *const *out_host_layers;
+    void *out_staging;
+    uint64_t out_staging_bytes;
+    uint64_t out_chunk_bytes;
+    kvl_host_fill_fn host_drain;
+    void *host_drain_user;
 } kvl_stream_cfg_t;
 
 typedef struct {
-    double total_ms;         /* first copy enqueued .. last compute finished (device clock) */
+    double total_ms;         /* first copy enqueued .. last compute (or outflow) finished (device clock) */
     double h2d_bytes;        /* bytes that crossed the host link */
     double link_gbps;        /* h2d_bytes / total_ms, GB/s */
     double exposed_ms;       /* total_ms minus the compute time (n_layers * compute_us, or the measured
@@ -368,6 +388,9 @@ typedef struct {
     float *t_loaded;         /* layer's scatter finished */
     float *t_compute_begin;
     float *t_compute_end;
+    float *t_out_done;       /* layer's outflow arrived in host memory (with out_plan) */
+    double d2h_bytes;        /* bytes the outflow sent over the host link */
+    double out_gbps;         /* d2h_bytes / total_ms */
 } kvl_stream_stats_t;
 
 /* Layer-wise load of all layers (Section 4.1: the load of a layer overlaps the

@@ -79,13 +79,18 @@ class kvl_stream_cfg_t(C.Structure):
                 ("host_fill", HOST_FILL_FN), ("host_fill_user", C.c_void_p),
                 ("copy_stream", C.c_void_p), ("kernel_stream", C.c_void_p), ("compute_stream", C.c_void_p),
                 ("full_blocks", C.c_void_p), ("full_blocks_bytes", C.c_uint64),
-                ("compute", COMPUTE_FN), ("compute_user", C.c_void_p)]
+                ("compute", COMPUTE_FN), ("compute_user", C.c_void_p),
+                ("out_plan", C.c_void_p), ("n_out_host_slots", C.c_uint32),
+                ("out_host_layers", C.POINTER(C.c_void_p)), ("out_staging", C.c_void_p),
+                ("out_staging_bytes", C.c_uint64), ("out_chunk_bytes", C.c_uint64),
+                ("host_drain", HOST_FILL_FN), ("host_drain_user", C.c_void_p)]
 
 
 class kvl_stream_stats_t(C.Structure):
     _fields_ = [("total_ms", C.c_double), ("h2d_bytes", C.c_double), ("link_gbps", C.c_double),
                 ("exposed_ms", C.c_double), ("t_loaded", C.POINTER(C.c_float)),
-                ("t_compute_begin", C.POINTER(C.c_float)), ("t_compute_end", C.POINTER(C.c_float))]
+                ("t_compute_begin", C.POINTER(C.c_float)), ("t_compute_end", C.POINTER(C.c_float)),
+                ("t_out_done", C.POINTER(C.c_float)), ("d2h_bytes", C.c_double), ("out_gbps", C.c_double)]
 
 
 # every symbol include/kvl.h declares, with its C signature
@@ -459,12 +464,19 @@ def kvl_stream_layers(plan: Plan, host_layers: Sequence[torch.Tensor],
                       probe_out: Optional[torch.Tensor] = None,
                       snapshots: Optional[Sequence[Sequence[torch.Tensor]]] = None,
                       host_fill=None, per_layer_times: bool = False,
-                      full_blocks: Optional[torch.Tensor] = None, compute=None) -> dict:
+                      full_blocks: Optional[torch.Tensor] = None, compute=None,
+                      out_plan: Optional[Plan] = None, out_host_layers: Optional[Sequence[torch.Tensor]] = None,
+                      out_staging: Optional[torch.Tensor] = None, out_chunk_bytes: int = 0,
+                      host_drain=None) -> dict:
     """kvl_stream_layers; returns the stats as a dict.  host_fill(layer, slot_index) is an
     optional Python callable run where the storage read of that layer would deliver.
     compute(layer, slot_index, stream_handle) is an optional Python callable that enqueues
     the caller's own work for that layer on the compute stream (given as a raw handle; wrap
     it in torch.cuda.ExternalStream to use it from torch) in place of the synthetic kernel.
+    out_plan (a gather plan over the same pool geometry) with out_host_layers (pinned tensors)
+    adds the outflow: after each layer's compute its slot is gathered into a host buffer, staged
+    through out_staging (out_chunk_bytes != 0) or written by the kernel itself;
+    host_drain(layer, slot_index) is called when a layer has arrived in its buffer.
     With full_blocks (device or pinned host tensor) the layers are loaded from the storage
     layout instead; host_layers, dev_staging and chunk_bytes may then be None / 0."""
     L = n_layers or int(plan.layout.n_layers)
@@ -538,21 +550,47 @@ def kvl_stream_layers(plan: Plan, host_layers: Sequence[torch.Tensor],
         ccb = COMPUTE_FN(_ctramp)
         cfg.compute = ccb
         keep.append(ccb)
+    if out_plan is not None:
+        out_host_layers = list(out_host_layers or [])
+        Ho = len(out_host_layers)
+        oh = (C.c_void_p * max(1, Ho))()
+        for i, t in enumerate(out_host_layers):
+            oh[i] = _pinned(t, f"out_host_layers[{i}]", out_plan.payload_bytes)
+        cfg.out_plan, cfg.n_out_host_slots, cfg.out_host_layers = out_plan.handle, Ho, oh
+        keep.append(oh)
+        if out_staging is not None:
+            cfg.out_staging = _dev(out_staging, "out_staging")
+            cfg.out_staging_bytes = _nbytes(out_staging)
+        cfg.out_chunk_bytes = out_chunk_bytes
+        if host_drain is not None:
+            def _dtramp(_user, layer, _slot_ptr, _bytes):
+                try:
+                    host_drain(int(layer), int(layer) % Ho)
+                    return 0
+                except Exception:  # surfaces as KVL_EINVAL from the call
+                    import traceback
+                    traceback.print_exc()
+                    return 1
+            dcb = HOST_FILL_FN(_dtramp)
+            cfg.host_drain = dcb
+            keep.append(dcb)
     cfg.copy_stream = _stream_handle(copy_stream)
     cfg.kernel_stream = _stream_handle(kernel_stream)
     cfg.compute_stream = _stream_handle(compute_stream)
     st = kvl_stream_stats_t()
     times = None
     if per_layer_times:
-        times = np.zeros((3, L), dtype=np.float32)
+        times = np.zeros((4, L), dtype=np.float32)
         fp = C.POINTER(C.c_float)
         st.t_loaded = times[0].ctypes.data_as(fp)
         st.t_compute_begin = times[1].ctypes.data_as(fp)
         st.t_compute_end = times[2].ctypes.data_as(fp)
+        st.t_out_done = times[3].ctypes.data_as(fp)
     _check(_lib.kvl_stream_layers(plan.handle, C.byref(cfg), C.byref(st)), "kvl_stream_layers")
-    out = dict(total_ms=st.total_ms, h2d_bytes=st.h2d_bytes, link_gbps=st.link_gbps, exposed_ms=st.exposed_ms)
+    out = dict(total_ms=st.total_ms, h2d_bytes=st.h2d_bytes, link_gbps=st.link_gbps, exposed_ms=st.exposed_ms,
+               d2h_bytes=st.d2h_bytes, out_gbps=st.out_gbps)
     if times is not None:
-        out.update(t_loaded=times[0], t_compute_begin=times[1], t_compute_end=times[2])
+        out.update(t_loaded=times[0], t_compute_begin=times[1], t_compute_end=times[2], t_out_done=times[3])
     return out
 
 

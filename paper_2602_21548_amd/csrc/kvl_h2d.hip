@@ -205,21 +205,66 @@ static int h2d_unpack_layer(const kvl_plan_t *plan_c, const void *pinned_host_xf
                                   pool_planes, ks, nullptr);
 }
 
+namespace kvl {
+
 // The other direction: gather into the staging slots, copy each landed chunk to
 // the pinned host buffer.  On a lane the order is kernel, copy, kernel, copy, ...
+// `wait_first`, if not null, is an event every lane passes before its first kernel
+// of this layer reads the pool; `collector` is made to wait for the layer's end.
+int enqueue_d2h_pack_layer(kvl_plan_t *plan, const std::vector<kvl_chunk_t> &chunks,
+                           const void *const *pool_planes, void *dev_staging, uint64_t chunk_bytes,
+                           size_t lanes, void *host_xfer, hipEvent_t wait_first, hipStream_t collector) {
+    char *host = static_cast<char *>(host_xfer);
+    char *stage = static_cast<char *>(dev_staging);
+    size_t i = 0;
+    for (const kvl_chunk_t &c : chunks) {
+        if (c.bytes == 0) continue;
+        const size_t lane = i % lanes;
+        hipStream_t ls = plan->lanes[lane];
+        char *slot = stage + lane * chunk_bytes;
+        if (i < lanes && wait_first) KVL_HIP(hipStreamWaitEvent(ls, wait_first, 0));
+        const uint64_t first_row_off = (uint64_t)plan->units[c.unit_begin].xfer_row * plan->layout.row_bytes[c.plane];
+        uintptr_t xp[KVL_MAX_PLANES] = {};
+        xp[c.plane] = reinterpret_cast<uintptr_t>(slot) - first_row_off;
+        int rc = launch_units(plan, true, c.unit_begin, c.unit_end, c.plane, c.plane + 1,
+                              const_cast<void *const *>(pool_planes), xp, ls);
+        if (rc != KVL_OK) return rc;
+        KVL_HIP(hipMemcpyAsync(host + c.host_offset, slot, c.bytes, hipMemcpyDeviceToHost, ls));
+        ++i;
+    }
+    const size_t used = std::min(i, lanes);
+    for (size_t j = 0; j < used; ++j) {
+        KVL_HIP(hipEventRecord(plan->ev_lane_done[j], plan->lanes[j]));
+        KVL_HIP(hipStreamWaitEvent(collector, plan->ev_lane_done[j], 0));
+    }
+    return KVL_OK;
+}
+
+// Arguments of a staged gather into host memory; *slots gets the number of lanes.
+int check_d2h_args(const kvl_plan_t *plan, const void *staging, uint64_t staging_bytes, uint64_t chunk_bytes,
+                   const void *host, uint64_t host_capacity, size_t *slots) {
+    if (!plan) return KVL_EINVAL;
+    if (!(plan->flags & KVL_GATHER) || (plan->flags & KVL_HOST_ONLY) || plan->paired) return KVL_EINVAL;
+    if (chunk_bytes == 0 || chunk_bytes % 16 || reinterpret_cast<uintptr_t>(staging) % 16) return KVL_EINVAL;
+    if (staging_bytes < chunk_bytes || host_capacity < plan->payload_bytes) return KVL_ESPACE;
+    if (!plan->units.empty() && (!staging || !host)) return KVL_EINVAL;
+    *slots = (size_t)std::min<uint64_t>(staging_bytes / chunk_bytes, 8);
+    return KVL_OK;
+}
+
+}  // namespace kvl
+
 static int d2h_pack_layer(const kvl_plan_t *plan_c, const void *const *pool_planes, void *dev_staging,
                           uint64_t staging_bytes, uint64_t chunk_bytes, void *pinned_host_xfer,
                           uint64_t host_capacity, void *kernel_stream, void *copy_stream) {
     using namespace kvl;
     kvl_plan_t *plan = const_cast<kvl_plan_t *>(plan_c);
-    if (!plan || !pool_planes) return KVL_EINVAL;
-    if (!(plan->flags & KVL_GATHER) || (plan->flags & KVL_HOST_ONLY) || plan->paired) return KVL_EINVAL;
-    if (chunk_bytes == 0 || chunk_bytes % 16 || reinterpret_cast<uintptr_t>(dev_staging) % 16) return KVL_EINVAL;
-    if (staging_bytes < chunk_bytes || host_capacity < plan->payload_bytes) return KVL_ESPACE;
+    if (!pool_planes) return KVL_EINVAL;
+    size_t slots = 0;
+    int rc = check_d2h_args(plan, dev_staging, staging_bytes, chunk_bytes, pinned_host_xfer, host_capacity, &slots);
+    if (rc != KVL_OK) return rc;
     if (plan->units.empty()) return KVL_OK;
-    if (!dev_staging || !pinned_host_xfer) return KVL_EINVAL;
-    const size_t slots = (size_t)std::min<uint64_t>(staging_bytes / chunk_bytes, 8);
-    int rc = check_pool(plan, pool_planes, plan->layout.pool_blocks);
+    rc = check_pool(plan, pool_planes, plan->layout.pool_blocks);
     if (rc == KVL_OK) rc = check_buffer(plan, pinned_host_xfer, plan->payload_bytes, true);
     if (rc == KVL_OK) rc = check_buffer(plan, dev_staging, slots * chunk_bytes, false);
     if (rc != KVL_OK) return rc;
@@ -231,29 +276,8 @@ static int d2h_pack_layer(const kvl_plan_t *plan_c, const void *const *pool_plan
     hipStream_t cs = (hipStream_t)copy_stream, ks = (hipStream_t)kernel_stream;
     rc = lanes_follow(plan, slots, cs, ks);
     if (rc != KVL_OK) return rc;
-    char *host = static_cast<char *>(pinned_host_xfer);
-    char *stage = static_cast<char *>(dev_staging);
-    size_t i = 0;
-    for (const kvl_chunk_t &c : chunks) {
-        if (c.bytes == 0) continue;
-        const size_t lane = i % slots;
-        hipStream_t ls = plan->lanes[lane];
-        char *slot = stage + lane * chunk_bytes;
-        const uint64_t first_row_off = (uint64_t)plan->units[c.unit_begin].xfer_row * plan->layout.row_bytes[c.plane];
-        uintptr_t xp[KVL_MAX_PLANES] = {};
-        xp[c.plane] = reinterpret_cast<uintptr_t>(slot) - first_row_off;
-        rc = launch_units(plan, true, c.unit_begin, c.unit_end, c.plane, c.plane + 1,
-                          const_cast<void *const *>(pool_planes), xp, ls);
-        if (rc != KVL_OK) return rc;
-        KVL_HIP(hipMemcpyAsync(host + c.host_offset, slot, c.bytes, hipMemcpyDeviceToHost, ls));
-        ++i;
-    }
-    const size_t used = std::min(i, slots);
-    for (size_t j = 0; j < used; ++j) {
-        KVL_HIP(hipEventRecord(plan->ev_lane_done[j], plan->lanes[j]));
-        KVL_HIP(hipStreamWaitEvent(ks, plan->ev_lane_done[j], 0));
-    }
-    return KVL_OK;
+    return enqueue_d2h_pack_layer(plan, chunks, pool_planes, dev_staging, chunk_bytes, slots, pinned_host_xfer,
+                                  nullptr, ks);
 }
 
 // Persist direction: one layer of the pool into a buffer of Full Blocks through the

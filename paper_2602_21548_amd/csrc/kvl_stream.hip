@@ -26,6 +26,11 @@ int check_h2d_args(const kvl_plan_t *plan, const void *host, const void *staging
                    uint64_t staging_bytes, uint64_t chunk_bytes, size_t *slots);
 int enqueue_zero_copy_layer(const kvl_plan_t *plan, const void *host_xfer, void *const *pool_planes,
                             hipStream_t kern_s, hipEvent_t wait_before_scatter);
+int enqueue_d2h_pack_layer(kvl_plan_t *plan, const std::vector<kvl_chunk_t> &chunks,
+                           const void *const *pool_planes, void *dev_staging, uint64_t chunk_bytes,
+                           size_t lanes, void *host_xfer, hipEvent_t wait_first, hipStream_t collector);
+int check_d2h_args(const kvl_plan_t *plan, const void *staging, uint64_t staging_bytes, uint64_t chunk_bytes,
+                   const void *host, uint64_t host_capacity, size_t *slots);
 int check_fullblock_staging(const kvl_plan_t *plan, const void *staging, uint64_t staging_bytes,
                             uint64_t chunk_bytes, size_t *slots);
 int enqueue_h2d_fullblocks_layer(kvl_plan_t *plan, const void *full_blocks, uint32_t layer,
@@ -61,6 +66,7 @@ struct RunState {
     kvl_probe_t *d_probes = nullptr;
     hipStream_t streams[3] = {nullptr, nullptr, nullptr};
     const std::vector<hipStream_t> *lanes = nullptr;
+    const std::vector<hipStream_t> *out_lanes = nullptr;
 
     int make(hipEvent_t *e, bool timing) {
         KVL_HIP(hipEventCreateWithFlags(e, timing ? hipEventDefault : hipEventDisableTiming));
@@ -71,6 +77,8 @@ struct RunState {
         // nothing enqueued by the run may outlive what it refers to
         if (lanes)
             for (hipStream_t s : *lanes) (void)hipStreamSynchronize(s);
+        if (out_lanes)
+            for (hipStream_t s : *out_lanes) (void)hipStreamSynchronize(s);
         for (hipStream_t s : streams) (void)hipStreamSynchronize(s);
         for (hipEvent_t e : events) (void)hipEventDestroy(e);
         if (d_probes) (void)hipFree(d_probes);
@@ -143,6 +151,39 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
         if (pr.plane >= P || pr.byte_offset % 16 || pr.byte_offset + 16 > plane_bytes) return KVL_EINVAL;
     }
 
+    // outflow
+    kvl_plan_t *oplan = const_cast<kvl_plan_t *>(cfg->out_plan);
+    const uint32_t Ho = cfg->n_out_host_slots;
+    size_t oslots = 0;
+    std::vector<kvl_chunk_t> ochunks;
+    if (oplan) {
+        if (oplan == plan || Ho == 0 || !cfg->out_host_layers) return KVL_EINVAL;
+        if (!(oplan->flags & KVL_GATHER) || (oplan->flags & KVL_HOST_ONLY) || oplan->paired) return KVL_EINVAL;
+        const kvl_layout_t &a = plan->layout, &b = oplan->layout;
+        if (a.block_tokens != b.block_tokens || a.n_planes != b.n_planes || a.pool_blocks != b.pool_blocks ||
+            oplan->device != plan->device)
+            return KVL_EINVAL;
+        for (uint32_t p = 0; p < P; ++p)
+            if (a.row_bytes[p] != b.row_bytes[p]) return KVL_EINVAL;
+        for (uint32_t h = 0; h < Ho; ++h) {
+            if (!cfg->out_host_layers[h] && !oplan->units.empty()) return KVL_EINVAL;
+            if (!oplan->units.empty()) {
+                rc = check_buffer(oplan, cfg->out_host_layers[h], oplan->payload_bytes, true);
+                if (rc != KVL_OK) return rc;
+            }
+        }
+        if (cfg->out_chunk_bytes) {
+            rc = check_d2h_args(oplan, cfg->out_staging, cfg->out_staging_bytes, cfg->out_chunk_bytes,
+                                cfg->out_host_layers[0], oplan->payload_bytes, &oslots);
+            if (rc == KVL_OK && !oplan->units.empty())
+                rc = check_buffer(oplan, cfg->out_staging, oslots * cfg->out_chunk_bytes, false);
+            if (rc == KVL_OK) rc = make_chunks(oplan, cfg->out_chunk_bytes, ochunks);
+            if (rc != KVL_OK) return rc;
+        }
+        rc = ensure_lanes(oplan, oslots ? oslots : 1);
+        if (rc != KVL_OK) return rc;
+    }
+
     std::vector<kvl_chunk_t> chunks;
     const bool zero_copy = !from_blocks && cfg->chunk_bytes == 0;
     if (!from_blocks && !zero_copy) {
@@ -164,9 +205,10 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
     RunState st;
     st.streams[0] = cs; st.streams[1] = ks; st.streams[2] = ms;
     st.lanes = &plan->lanes;
+    if (oplan) st.out_lanes = &oplan->lanes;
     hipEvent_t ev_start = nullptr, ev_sync = nullptr;
-    std::vector<hipEvent_t> loaded(L), cbeg(L), cend(L), h2d_done(L);
-    st.events.reserve(4 * (size_t)L + 2);
+    std::vector<hipEvent_t> loaded(L), cbeg(L), cend(L), h2d_done(L), out_done(oplan ? L : 0);
+    st.events.reserve(5 * (size_t)L + 2);
     if ((rc = st.make(&ev_start, true)) != KVL_OK) return rc;
     if ((rc = st.make(&ev_sync, false)) != KVL_OK) return rc;
     for (uint32_t l = 0; l < L; ++l) {
@@ -174,6 +216,7 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
         if ((rc = st.make(&cbeg[l], true)) != KVL_OK) return rc;
         if ((rc = st.make(&cend[l], true)) != KVL_OK) return rc;
         if ((rc = st.make(&h2d_done[l], false)) != KVL_OK) return rc;
+        if (oplan && (rc = st.make(&out_done[l], true)) != KVL_OK) return rc;
     }
     if (cfg->n_probes) {
         const size_t bytes = cfg->n_probes * sizeof(kvl_probe_t);
@@ -199,14 +242,17 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
     for (uint32_t l = 0; l < L; ++l) {
         const uint32_t s = l % S;
         void *const *slot_planes = cfg->dev_slot_planes + (size_t)s * P;
+        // the slot may be overwritten once what read it last has finished: the compute of
+        // layer l - S, or, with an outflow, that layer's gather
+        hipEvent_t slot_free = l >= S ? (oplan ? out_done[l - S] : cend[l - S]) : nullptr;
         if (staged_blocks) {
             rc = plan->units.empty() ? KVL_OK
                                      : enqueue_h2d_fullblocks_layer(plan, cfg->full_blocks, l, cfg->dev_staging,
                                                                     cfg->chunk_bytes, slots, slot_planes, ks,
-                                                                    l >= S ? cend[l - S] : nullptr);
+                                                                    slot_free);
         } else if (from_blocks) {
             // the slot may be overwritten once the compute that read it has finished
-            if (l >= S) KVL_HIP(hipStreamWaitEvent(ks, cend[l - S], 0));
+            if (slot_free) KVL_HIP(hipStreamWaitEvent(ks, slot_free, 0));
             rc = fullblock_layer(plan, true, reinterpret_cast<uintptr_t>(cfg->full_blocks),
                                  cfg->full_blocks_bytes, l, slot_planes, ks);
         } else {
@@ -219,12 +265,12 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
             if (zero_copy) {
                 rc = plan->units.empty() ? KVL_OK
                                          : enqueue_zero_copy_layer(plan, host_slot, slot_planes, ks,
-                                                                   l >= S ? cend[l - S] : nullptr);
+                                                                   slot_free);
                 // the host slot is free again once this kernel has read it
                 if (rc == KVL_OK) KVL_HIP(hipEventRecord(h2d_done[l], ks));
             } else {
                 rc = enqueue_h2d_layer(plan, chunks, host_slot, cfg->dev_staging, cfg->chunk_bytes, slots,
-                                       slot_planes, ks, l >= S ? cend[l - S] : nullptr);
+                                       slot_planes, ks, slot_free);
                 // every copy of the layer has been scattered by then: the host slot is free again
                 if (rc == KVL_OK) KVL_HIP(hipEventRecord(h2d_done[l], ks));
             }
@@ -256,14 +302,54 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
             }
         }
         KVL_HIP(hipEventRecord(cend[l], ms));
+
+        if (oplan) {
+            void *out_host = cfg->out_host_layers[l % Ho];
+            if (l >= Ho) {          // the buffer still holds layer l - Ho: let the caller have it first
+                KVL_HIP(hipEventSynchronize(out_done[l - Ho]));
+                if (cfg->host_drain &&
+                    cfg->host_drain(cfg->host_drain_user, l - Ho, out_host, oplan->payload_bytes) != 0)
+                    return KVL_EINVAL;
+            }
+            if (oplan->units.empty()) {
+                KVL_HIP(hipStreamWaitEvent(cs, cend[l], 0));
+            } else if (cfg->out_chunk_bytes) {
+                rc = enqueue_d2h_pack_layer(oplan, ochunks, const_cast<const void *const *>(slot_planes),
+                                            cfg->out_staging, cfg->out_chunk_bytes, oslots, out_host, cend[l], cs);
+                if (rc != KVL_OK) return rc;
+            } else {                // the gather writes the host buffer itself
+                KVL_HIP(hipStreamWaitEvent(cs, cend[l], 0));
+                uintptr_t xp[KVL_MAX_PLANES];
+                for (uint32_t p = 0; p < P; ++p)
+                    xp[p] = reinterpret_cast<uintptr_t>(out_host) + oplan->plane_base[p];
+                rc = launch_units(oplan, true, 0, (uint32_t)oplan->units.size(), 0, P, slot_planes, xp, cs);
+                if (rc != KVL_OK) return rc;
+            }
+            KVL_HIP(hipEventRecord(out_done[l], cs));
+        }
     }
     KVL_HIP(hipEventSynchronize(cend[L - 1]));
+    if (oplan) {
+        for (uint32_t l = L > Ho ? L - Ho : 0; l < L; ++l) {
+            KVL_HIP(hipEventSynchronize(out_done[l]));
+            if (cfg->host_drain &&
+                cfg->host_drain(cfg->host_drain_user, l, cfg->out_host_layers[l % Ho], oplan->payload_bytes) != 0)
+                return KVL_EINVAL;
+        }
+    }
     KVL_HIP(hipStreamSynchronize(ks));
     KVL_HIP(hipStreamSynchronize(cs));
 
     if (stats) {
         float total = 0.f;
         KVL_HIP(hipEventElapsedTime(&total, ev_start, cend[L - 1]));
+        if (oplan) {
+            float t = 0.f;
+            KVL_HIP(hipEventElapsedTime(&t, ev_start, out_done[L - 1]));
+            total = std::max(total, t);
+        }
+        stats->d2h_bytes = oplan ? (double)oplan->payload_bytes * L : 0.0;
+        stats->out_gbps = (oplan && total > 0.f) ? stats->d2h_bytes / (total * 1e-3) / 1e9 : 0.0;
         stats->total_ms = total;
         stats->h2d_bytes = (double)plan->payload_bytes * L;
         stats->link_gbps = total > 0.f ? stats->h2d_bytes / (total * 1e-3) / 1e9 : 0.0;
@@ -290,6 +376,10 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
             if (stats->t_compute_end) {
                 KVL_HIP(hipEventElapsedTime(&t, ev_start, cend[l]));
                 stats->t_compute_end[l] = t;
+            }
+            if (stats->t_out_done && oplan) {
+                KVL_HIP(hipEventElapsedTime(&t, ev_start, out_done[l]));
+                stats->t_out_done[l] = t;
             }
         }
     }

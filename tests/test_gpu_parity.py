@@ -892,3 +892,70 @@ def test_d2h_pack_staged(name, make, chunk_kb, slots):
         with pytest.raises(K.KvlError) as e:
             K.kvl_d2h_pack_layer(g, d_src, staging, chunk, short, ks, cs)
         assert e.value.code == K.KVL_ESPACE
+
+
+@pytest.mark.parametrize("S,Ho", [(1, 1), (2, 1), (2, 3)])
+@pytest.mark.parametrize("out_chunk", [8192, 0], ids=["out-staged", "out-zerocopy"])
+def test_stream_layers_with_outflow(S, Ho, out_chunk):
+    """The whole loop of layer-wise prefill: layer l+1 is loaded while layer l is computed and
+    layer l-1 (hit and appended rows, as the compute left them) leaves for host memory.  The
+    compute here adds 1 to every byte of the slot; the oracle does the same to its slots."""
+    L, H = 5, 2
+    w = W.tiny(262, 5, 16, (64, 32), 96, 180, n_layers=L)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    n = oracle.payload_bytes(w.hit, rows)
+    total = (w.hit + w.app).astype(np.uint32)
+    n_out = oracle.payload_bytes(total, rows)
+    payloads = [W.random_payload(w, l, n) for l in range(L)]
+    o_slots = [W.sentinel_pool(w, "dst", 0xEE) for _ in range(S)]
+    o_host = [np.zeros(n, np.uint8) for _ in range(H)]
+    want_out = []
+    gen = oracle.stream_layers(bs, rows, w.hit, w.dst.tables, o_host, L, o_slots)
+    for l in range(L):
+        o_host[l % H][:] = payloads[l]
+        _, s_idx, planes = next(gen)
+        for p in planes:                       # the compute of layer l
+            p += 1
+        want_out.append(oracle.pack_range(bs, rows, None, total, w.dst.tables, planes))
+
+    load = dev_plan(w, "dst", K.KVL_SCATTER, unit_bytes=4096)
+    out = dev_plan(w, "dst", K.KVL_GATHER | K.KVL_TOKENS_ALL, unit_bytes=4096)
+    assert out.payload_bytes == n_out
+    host = [torch.zeros(n, dtype=torch.uint8, pin_memory=True) for _ in range(H)]
+    out_host = [torch.zeros(n_out, dtype=torch.uint8, pin_memory=True) for _ in range(Ho)]
+    slots = [planes_to_dev(W.sentinel_pool(w, "dst", 0xEE)) for _ in range(S)]
+    staging = torch.zeros(3 * 8192, dtype=torch.uint8, device="cuda")
+    out_staging = torch.zeros(2 * 8192, dtype=torch.uint8, device="cuda") if out_chunk else None
+    cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    got_out, drained = [], []
+
+    def fill(layer, slot):
+        host[slot].numpy()[:] = payloads[layer]
+
+    def compute(layer, slot, stream_handle):
+        with torch.cuda.stream(ms):
+            for pl in slots[slot]:
+                pl.add_(1)
+
+    def drain(layer, slot):
+        drained.append((layer, slot))
+        got_out.append(out_host[slot].numpy().copy())
+
+    torch.cuda.synchronize()
+    st = K.kvl_stream_layers(load, host, slots, staging, 8192, 0, cs, ks, ms, n_layers=L, host_fill=fill,
+                             compute=compute, out_plan=out, out_host_layers=out_host, out_staging=out_staging,
+                             out_chunk_bytes=out_chunk, host_drain=drain, per_layer_times=True)
+    assert drained == [(l, l % Ho) for l in range(L)]
+    for l in range(L):
+        assert same_bytes(got_out[l], want_out[l]), f"layer {l}: what left for host memory differs from the oracle"
+    assert st["d2h_bytes"] == n_out * L and st["h2d_bytes"] == n * L
+    # a layer leaves after its compute, and its slot is loaded again only after it has left
+    assert np.all(st["t_out_done"] >= st["t_compute_end"] - 1e-3)
+    assert np.all(st["t_loaded"][S:] >= st["t_out_done"][:-S] - 1e-3)
+    # an outflow plan over another pool geometry is refused
+    other = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks + 1), w.hit, w.app, w.dst.tables,
+                       K.KVL_GATHER | K.KVL_TOKENS_ALL)
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_stream_layers(load, host, slots, staging, 8192, 0, cs, ks, ms, n_layers=L, out_plan=other,
+                            out_host_layers=out_host, out_staging=out_staging, out_chunk_bytes=out_chunk)
+    assert e.value.code == K.KVL_EINVAL
