@@ -1,5 +1,8 @@
-// Host-buffer load path: pinned host transfer buffer -> staging slots in HBM
-// (hipMemcpyAsync) -> scatter kernel per landed chunk.
+// Host-buffer paths.  Load: pinned host transfer buffer -> staging slots in HBM
+// (hipMemcpyAsync) -> scatter kernel per landed chunk.  The way out mirrors it
+// (gather kernel into a slot -> hipMemcpyAsync to the host buffer), and both have
+// a form for the storage layout, in which the copy engine moves whole Layer
+// Blocks with strided copies and a kernel converts them in HBM.
 //
 // The paper notes that handing many small copies to a copy engine is bound by
 // the per-copy submission cost (Section 5.2), so the host buffer is not copied

@@ -19,24 +19,6 @@ namespace kvl {
 
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
-int enqueue_h2d_layer(kvl_plan_t *plan, const std::vector<kvl_chunk_t> &chunks,
-                      const void *host_xfer, void *dev_staging, uint64_t chunk_bytes, size_t lanes,
-                      void *const *pool_planes, hipStream_t kern_s, hipEvent_t wait_before_scatter);
-int check_h2d_args(const kvl_plan_t *plan, const void *host, const void *staging,
-                   uint64_t staging_bytes, uint64_t chunk_bytes, size_t *slots);
-int enqueue_zero_copy_layer(const kvl_plan_t *plan, const void *host_xfer, void *const *pool_planes,
-                            hipStream_t kern_s, hipEvent_t wait_before_scatter);
-int enqueue_d2h_pack_layer(kvl_plan_t *plan, const std::vector<kvl_chunk_t> &chunks,
-                           const void *const *pool_planes, void *dev_staging, uint64_t chunk_bytes,
-                           size_t lanes, void *host_xfer, hipEvent_t wait_first, hipStream_t collector);
-int check_d2h_args(const kvl_plan_t *plan, const void *staging, uint64_t staging_bytes, uint64_t chunk_bytes,
-                   const void *host, uint64_t host_capacity, size_t *slots);
-int check_fullblock_staging(const kvl_plan_t *plan, const void *staging, uint64_t staging_bytes,
-                            uint64_t chunk_bytes, size_t *slots);
-int enqueue_h2d_fullblocks_layer(kvl_plan_t *plan, const void *full_blocks, uint32_t layer,
-                                 void *dev_staging, uint64_t chunk_bytes, size_t lanes,
-                                 void *const *pool_planes, hipStream_t kern_s, hipEvent_t wait_before_scatter);
-
 struct SlotPlanes {
     uintptr_t base[KVL_MAX_PLANES];
 };
