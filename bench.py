@@ -593,10 +593,15 @@ def duplex_leg(w, lay, plan, host, slots, staging, chunk, cs, ks, ms, layers, pe
     import paper_2602_21548_amd as K
     out = K.kvl_plan(lay, w.hit, w.app, w.dst.tables, K.KVL_GATHER | K.KVL_TOKENS_ALL)
     out_host = [torch.empty(out.payload_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
-    out_staging = torch.empty(4 * chunk, dtype=torch.uint8, device="cuda")
+    # few lanes: the process has 4 hardware queues by default, and lanes that share one with each
+    # other or with the caller's streams wait for each other (2 + 1 lanes measured 66 GB/s both
+    # ways, 2 + 2 lanes 39, 4 + 4 lanes 52)
+    out_staging = torch.empty(chunk, dtype=torch.uint8, device="cuda")
+    load_staging = staging[:2 * chunk]
     res = {"layers": layers, "out_payload_bytes_per_layer": out.payload_bytes,
            "note": "rates over the whole run; the outflow of the last layer runs after the last load"}
-    for name, stg, ostg, ch in (("staged_both_ways", staging, out_staging, chunk), ("zero_copy_both_ways", None, None, 0)):
+    res["staged_lanes"] = "2 x 128 MiB in, 1 x 128 MiB out"
+    for name, stg, ostg, ch in (("staged_both_ways", load_staging, out_staging, chunk), ("zero_copy_both_ways", None, None, 0)):
         st = K.kvl_stream_layers(plan, host, slots, stg, ch, w.notes["compute_us"], cs, ks, ms, n_layers=layers,
                                  out_plan=out, out_host_layers=out_host, out_staging=ostg, out_chunk_bytes=ch)
         res[name] = {"total_ms": round(st["total_ms"], 2), "h2d_gbps": round(st["link_gbps"], 2),
@@ -630,7 +635,7 @@ def stream_under_busy_compute(plan, host, slots, staging, chunk, cs, ks, ms, lay
     e1.record(ms)
     e1.synchronize()
     alone = e0.elapsed_time(e1)
-    st = K.kvl_stream_layers(plan, host, slots, staging, chunk, 0, cs, ks, ms, n_layers=layers,
+    st = K.kvl_stream_layers(plan, host, slots, staging[:2 * chunk], chunk, 0, cs, ks, ms, n_layers=layers,
                              compute=compute, per_layer_times=True)
     # the last layer's computation runs after every load has finished: leave it out
     busy = (st["t_compute_end"] - st["t_compute_begin"])[:-1]
@@ -640,6 +645,7 @@ def stream_under_busy_compute(plan, host, slots, staging, chunk, cs, ks, ms, lay
             "link_gbps": round(st["link_gbps"], 2), "frac_of_link": round(st["link_gbps"] / peak, 4),
             "compute_ms_per_layer_alone": round(alone, 2),
             "compute_ms_per_layer_during_load": round(float(busy.mean()), 2) if len(busy) else None,
+            "staging_slots": 2,
             "hw_queues": os.environ.get("GPU_MAX_HW_QUEUES", "runtime default")}
 
 
