@@ -67,6 +67,7 @@ extern "C" {
 #define KVL_ESPACE  -4   /* buffer, staging area or chunk too small */
 #define KVL_EHIP    -5   /* a HIP call failed: see kvl_last_hip_error */
 #define KVL_ENOMEM  -6   /* host allocation failed */
+#define KVL_ENOSYS  -7   /* the HIP runtime in this process lacks a call the function is built on */
 
 /* plan flags */
 #define KVL_GATHER     1u  /* plan may be used with kvl_pack_layer */
@@ -302,6 +303,11 @@ int kvl_plan_set_lane_cu_mask(kvl_plan_t *plan, const uint32_t *mask, uint32_t n
  * enqueued on stream. */
 int kvl_h2d_blockwise_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
                             void *const *pool_planes, void *stream, uint64_t *n_copies);
+/* The same copies handed to the runtime in one call (hipMemcpyBatchAsync, which newer
+ * HIP runtimes have): what batching the submission buys on this platform, for the
+ * same study.  KVL_ENOSYS if the runtime loaded in this process has no such call. */
+int kvl_h2d_blockwise_batched_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
+                                    void *const *pool_planes, void *stream, uint64_t *n_copies);
 
 /* A 16-byte sample of what the compute of a layer sees. */
 typedef struct {

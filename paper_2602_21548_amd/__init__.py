@@ -10,7 +10,7 @@ _EXPORTS = (
     "kvl_h2d_unpack_layer", "kvl_h2d_blockwise_layer", "kvl_stream_layers",
     "kvl_fullblocks_to_pool_layer", "kvl_h2d_fullblocks_layer", "kvl_d2h_pack_layer", "kvl_d2h_fullblocks_layer", "kvl_pool_to_fullblocks_layer", "kvl_plan_pair", "kvl_move_layer", "kvl_measure_h2d_peak", "kvl_copy_linear",
     "kvl_strerror", "kvl_release_cached_memory", "kvl_variant_name", "kvl_version", "LIB_PATH",
-    "KVL_OK", "KVL_EINVAL", "KVL_ERANGE", "KVL_EALIAS", "KVL_ESPACE", "KVL_EHIP", "KVL_ENOMEM",
+    "KVL_OK", "KVL_EINVAL", "KVL_ERANGE", "KVL_EALIAS", "KVL_ESPACE", "KVL_EHIP", "KVL_ENOMEM", "KVL_ENOSYS", "kvl_h2d_blockwise_batched_layer",
     "KVL_GATHER", "KVL_SCATTER", "KVL_HOST_ONLY", "KVL_NO_MERGE", "KVL_MAX_PLANES",
     "KVL_TOKENS_APPEND", "KVL_TOKENS_ALL", "KVL_NO_POINTER_CHECKS", "kvl_check_buffer",
 )

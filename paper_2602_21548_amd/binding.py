@@ -20,6 +20,7 @@ from . import build as _build
 
 KVL_MAX_PLANES = 4
 KVL_OK, KVL_EINVAL, KVL_ERANGE, KVL_EALIAS, KVL_ESPACE, KVL_EHIP, KVL_ENOMEM = 0, -1, -2, -3, -4, -5, -6
+KVL_ENOSYS = -7
 KVL_GATHER, KVL_SCATTER, KVL_HOST_ONLY, KVL_NO_MERGE = 1, 2, 4, 8
 KVL_TOKENS_APPEND, KVL_TOKENS_ALL = 16, 32
 KVL_NO_POINTER_CHECKS = 64
@@ -129,6 +130,8 @@ _SIGNATURES = {
     "kvl_plan_set_lane_cu_mask": (C.c_int, [_PLAN_P, C.POINTER(C.c_uint32), C.c_uint32]),
     "kvl_h2d_blockwise_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
                                           C.POINTER(C.c_uint64)]),
+    "kvl_h2d_blockwise_batched_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p,
+                                                  C.POINTER(C.c_uint64)]),
     "kvl_stream_layers": (C.c_int, [_PLAN_P, C.POINTER(kvl_stream_cfg_t), C.POINTER(kvl_stream_stats_t)]),
     "kvl_measure_h2d_peak": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p,
                                        C.POINTER(C.c_double)]),
@@ -454,6 +457,17 @@ def kvl_h2d_blockwise_layer(plan: Plan, pinned_host_xfer: torch.Tensor, pool_pla
     n = C.c_uint64()
     _check(_lib.kvl_h2d_blockwise_layer(plan.handle, host, arr, _stream_handle(stream), C.byref(n)),
            "kvl_h2d_blockwise_layer")
+    return int(n.value)
+
+
+def kvl_h2d_blockwise_batched_layer(plan: Plan, pinned_host_xfer: torch.Tensor,
+                                    pool_planes: Sequence[torch.Tensor], stream=None) -> int:
+    """The same copies in one hipMemcpyBatchAsync; raises KvlError(KVL_ENOSYS) if the runtime lacks it."""
+    arr = _plane_ptrs(plan, pool_planes, "kvl_h2d_blockwise_batched_layer pool")
+    host = _pinned(pinned_host_xfer, "pinned_host_xfer", plan.payload_bytes)
+    n = C.c_uint64()
+    _check(_lib.kvl_h2d_blockwise_batched_layer(plan.handle, host, arr, _stream_handle(stream), C.byref(n)),
+           "kvl_h2d_blockwise_batched_layer")
     return int(n.value)
 
 

@@ -18,6 +18,8 @@
 // layer's start and end touch the caller's streams (a handful of event waits per
 // layer).  An earlier form with one copy stream, one kernel stream and two
 // events per chunk lost 15-25 % of the link at 8-16 MiB chunks to those events.
+#include <dlfcn.h>
+
 #include <algorithm>
 #include <new>
 #include <vector>
@@ -482,6 +484,45 @@ int kvl_h2d_blockwise_layer(const kvl_plan_t *plan, const void *pinned_host_xfer
         }
     }
     if (n_copies) *n_copies = copies;
+    return KVL_OK;
+}
+
+int kvl_h2d_blockwise_batched_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
+                                    void *const *pool_planes, void *stream, uint64_t *n_copies) {
+    // looked up at run time: the library also has to load under runtimes that predate the call
+    typedef hipError_t (*batch_fn)(void **, void **, size_t *, size_t, void *, size_t *, size_t, size_t *, hipStream_t);
+    static const batch_fn batch = reinterpret_cast<batch_fn>(dlsym(RTLD_DEFAULT, "hipMemcpyBatchAsync"));
+    if (!plan || !pool_planes) return KVL_EINVAL;
+    if (!(plan->flags & KVL_SCATTER) || (plan->flags & KVL_HOST_ONLY)) return KVL_EINVAL;
+    if (n_copies) *n_copies = 0;
+    if (!batch) return KVL_ENOSYS;
+    if (plan->units.empty()) return KVL_OK;
+    if (!pinned_host_xfer) return KVL_EINVAL;
+    int rc = kvl::check_pool(plan, pool_planes, plan->layout.pool_blocks);
+    if (rc == KVL_OK) rc = kvl::check_buffer(plan, pinned_host_xfer, plan->payload_bytes, true);
+    if (rc != KVL_OK) return rc;
+    try {
+        const size_t n = plan->units.size() * plan->layout.n_planes;
+        std::vector<void *> dsts(n), srcs(n);
+        std::vector<size_t> sizes(n);
+        char *host = static_cast<char *>(const_cast<void *>(pinned_host_xfer));
+        size_t k = 0;
+        for (uint32_t p = 0; p < plan->layout.n_planes; ++p) {
+            const uint64_t row = plan->layout.row_bytes[p];
+            char *pool = static_cast<char *>(pool_planes[p]);
+            for (const kvl_unit_t &u : plan->units) {
+                dsts[k] = pool + (uint64_t)u.pool_row * row;
+                srcs[k] = host + plan->plane_base[p] + (uint64_t)u.xfer_row * row;
+                sizes[k] = (size_t)u.n_rows * row;
+                ++k;
+            }
+        }
+        size_t fail = 0;
+        KVL_HIP(batch(dsts.data(), srcs.data(), sizes.data(), n, nullptr, nullptr, 0, &fail, (hipStream_t)stream));
+        if (n_copies) *n_copies = n;
+    } catch (const std::bad_alloc &) {
+        return KVL_ENOMEM;
+    }
     return KVL_OK;
 }
 

@@ -470,6 +470,7 @@ const char *kvl_strerror(int code) {
         case KVL_ESPACE: return "buffer, staging area or chunk too small";
         case KVL_EHIP: return "HIP call failed";
         case KVL_ENOMEM: return "out of host memory";
+        case KVL_ENOSYS: return "not available in the HIP runtime of this process";
         default: return "unknown kvl error";
     }
 }

@@ -11,11 +11,21 @@
  *
  * Prints one line per check and "c parity ok" at the end; exit status 0 only
  * if every check passed.
+ *
+ * With the argument "submission" it runs the submission-cost study instead
+ * (Section 5.2 of the paper: handing a copy engine many small copies is bound by
+ * the cost of submitting each): 2048 Layer Blocks of 72 KiB in random pool
+ * order, host buffer -> pool, by one hipMemcpyAsync per block, by one
+ * hipMemcpyBatchAsync for all of them (this program links the system's HIP
+ * runtime, which has that call), by the staged path and by the zero-copy kernel;
+ * every result is compared with the oracle's.
  */
+#define _POSIX_C_SOURCE 199309L
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <time.h>
 
 #include <hip/hip_runtime_api.h>
 
@@ -58,7 +68,112 @@ static uint64_t rnd(void) {
 
 enum { R = 5, BS = 16, P = 2, POOL_BLOCKS = 96 };
 
-int main(void) {
+static double now_ms(void) {
+    struct timespec t;
+    clock_gettime(CLOCK_MONOTONIC, &t);
+    return t.tv_sec * 1e3 + t.tv_nsec * 1e-6;
+}
+
+static int submission_study(void) {
+    enum { SR = 8, SBS = 64, BLOCKS_PER_REQ = 256, SPOOL = 2304 };
+    const uint32_t row[1] = {1152};
+    const size_t blk = (size_t)SBS * row[0];
+    static int32_t tab[SR][BLOCKS_PER_REQ];
+    static int32_t perm[SPOOL];
+    const int32_t *tabs[SR];
+    kvl_request_t req[SR];
+    uint32_t hit[SR];
+    for (int i = 0; i < SPOOL; ++i) perm[i] = i;
+    for (int i = SPOOL - 1; i > 0; --i) {
+        int j = (int)(rnd() % (uint64_t)(i + 1));
+        int32_t t = perm[i]; perm[i] = perm[j]; perm[j] = t;
+    }
+    for (int r = 0; r < SR; ++r) {
+        for (int b = 0; b < BLOCKS_PER_REQ; ++b) tab[r][b] = perm[r * BLOCKS_PER_REQ + b];
+        tabs[r] = tab[r];
+        hit[r] = BLOCKS_PER_REQ * SBS;
+        req[r].hit_tokens = hit[r];
+        req[r].append_tokens = 0;
+        req[r].n_blocks = BLOCKS_PER_REQ;
+        req[r].block_table = tab[r];
+    }
+    kvl_layout_t lay;
+    memset(&lay, 0, sizeof lay);
+    lay.n_layers = 1; lay.block_tokens = SBS; lay.n_planes = 1; lay.row_bytes[0] = row[0]; lay.pool_blocks = SPOOL;
+    kvl_plan_t *s = NULL;
+    expect(kvl_plan(&lay, req, SR, KVL_SCATTER | KVL_NO_MERGE, &s), KVL_OK, "kvl_plan (2048 blocks, unmerged)");
+    if (failures) return 1;
+    uint64_t payload = 0, n_units = 0;
+    kvl_plan_payload_bytes(s, &payload);
+    kvl_plan_n_units(s, &n_units);
+    const size_t pool_bytes = (size_t)SPOOL * blk;
+    uint8_t *want = malloc(pool_bytes), *got = malloc(pool_bytes);
+    void *pinned = NULL, *d_pool = NULL, *d_stage = NULL;
+    HIP_OK(hipHostMalloc(&pinned, payload, hipHostMallocDefault));
+    for (uint64_t i = 0; i < payload; ++i) ((uint8_t *)pinned)[i] = (uint8_t)rnd();
+    HIP_OK(hipMalloc(&d_pool, pool_bytes));
+    const uint64_t chunk = 16u << 20, stage_bytes = 3 * chunk;
+    HIP_OK(hipMalloc(&d_stage, stage_bytes));
+    memset(want, 0xA5, pool_bytes);
+    uint8_t *wantp[1] = {want};
+    if (kvo_unpack(SBS, 1, row, SR, hit, tabs, pinned, wantp, 0, SR) != 0) return 2;
+    hipStream_t cs, ks;
+    HIP_OK(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
+    HIP_OK(hipStreamCreateWithFlags(&ks, hipStreamNonBlocking));
+    void *planes[1] = {d_pool};
+    printf("%llu descriptors of %zu bytes, payload %.1f MB\n", (unsigned long long)n_units, blk, payload / 1e6);
+    for (int mode = 0; mode < 4; ++mode) {
+        static const char *names[4] = {"one hipMemcpyAsync per block", "one hipMemcpyBatchAsync for all blocks",
+                                       "staged: 16 MiB chunks, 3 slots, scatter kernels", "zero-copy scatter kernel"};
+        double best_submit = 1e30, best_total = 1e30;
+        int rc = KVL_OK;
+        for (int rep = 0; rep < 4 && rc == KVL_OK; ++rep) {
+            HIP_OK(hipMemset(d_pool, 0xA5, pool_bytes));
+            HIP_OK(hipDeviceSynchronize());
+            uint64_t copies = 0;
+            const double t0 = now_ms();
+            if (mode == 0) rc = kvl_h2d_blockwise_layer(s, pinned, planes, ks, &copies);
+            else if (mode == 1) rc = kvl_h2d_blockwise_batched_layer(s, pinned, planes, ks, &copies);
+            else if (mode == 2) rc = kvl_h2d_unpack_layer(s, pinned, d_stage, stage_bytes, chunk, planes, cs, ks);
+            else rc = kvl_h2d_unpack_layer(s, pinned, NULL, 0, 0, planes, cs, ks);
+            const double t1 = now_ms();
+            HIP_OK(hipStreamSynchronize(ks));
+            HIP_OK(hipStreamSynchronize(cs));
+            const double t2 = now_ms();
+            if (rep) {      /* the first round warms up */
+                if (t1 - t0 < best_submit) best_submit = t1 - t0;
+                if (t2 - t0 < best_total) best_total = t2 - t0;
+            }
+        }
+        if (rc == KVL_ENOSYS) {
+            printf("%-52s not available in this HIP runtime\n", names[mode]);
+            continue;
+        }
+        expect(rc, KVL_OK, names[mode]);
+        HIP_OK(hipMemcpy(got, d_pool, pool_bytes, hipMemcpyDeviceToHost));
+        expect(memcmp(got, want, pool_bytes) == 0, 1, "  pool equals the oracle's");
+        printf("  host time in the call %.3f ms (%.2f us per block), until done %.3f ms = %.2f GB/s\n", best_submit,
+               best_submit * 1e3 / (double)n_units, best_total, payload / best_total / 1e6);
+        fflush(stdout);
+    }
+    kvl_plan_destroy(s);
+    kvl_release_cached_memory();
+    HIP_OK(hipStreamDestroy(cs));
+    HIP_OK(hipStreamDestroy(ks));
+    HIP_OK(hipFree(d_stage));
+    HIP_OK(hipFree(d_pool));
+    HIP_OK(hipHostFree(pinned));
+    free(want); free(got);
+    if (failures) {
+        printf("submission study: %d check(s) FAILED\n", failures);
+        return 1;
+    }
+    printf("submission study ok\n");
+    return 0;
+}
+
+int main(int argc, char **argv) {
+    if (argc > 1 && strcmp(argv[1], "submission") == 0) return submission_study();
     const uint32_t rows[P] = {656, 256};
     const uint32_t hit[R] = {100, 16, 0, 333, 47}, app[R] = {9, 0, 20, 3, 1};
     int32_t src_tab[R][32], dst_tab[R][32];

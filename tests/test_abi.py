@@ -37,7 +37,7 @@ def test_library_exports_every_declared_symbol():
 def test_strerror_and_versions():
     import paper_2602_21548_amd as K
     assert K.kvl_strerror(0) == "ok"
-    for code in (K.KVL_EINVAL, K.KVL_ERANGE, K.KVL_EALIAS, K.KVL_ESPACE, K.KVL_EHIP, K.KVL_ENOMEM):
+    for code in (K.KVL_EINVAL, K.KVL_ERANGE, K.KVL_EALIAS, K.KVL_ESPACE, K.KVL_EHIP, K.KVL_ENOMEM, K.KVL_ENOSYS):
         assert K.kvl_strerror(code) not in ("ok", "unknown kvl error")
     assert K.kvl_strerror(-99) == "unknown kvl error"
     assert "gfx950" in K.kvl_version()

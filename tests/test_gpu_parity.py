@@ -306,6 +306,18 @@ def test_h2d_zero_copy_and_blockwise(name, make):
     assert copies == s.n_units * len(rows)
     for got_a, got_b, ref in zip(a, b, want):
         assert same_bytes(to_host(got_a), ref) and same_bytes(to_host(got_b), ref)
+    # the same copies submitted as one batch, where the loaded HIP runtime has the call
+    c = planes_to_dev(W.sentinel_pool(w, "dst"))
+    torch.cuda.synchronize()
+    try:
+        copies = K.kvl_h2d_blockwise_batched_layer(s, host, c, stream=st)
+    except K.KvlError as e:
+        assert e.code == K.KVL_ENOSYS
+    else:
+        st.synchronize()
+        assert copies == s.n_units * len(rows)
+        for got_c, ref in zip(c, want):
+            assert same_bytes(to_host(got_c), ref)
 
 
 FB_CASES = [c for c in CASES if c[0] in ("tiny-random", "tiny-runs-2planes", "tiny-oddrow", "tiny-3planes",
