@@ -908,7 +908,8 @@ def test_d2h_pack_staged(name, make, chunk_kb, slots):
 
 @pytest.mark.parametrize("S,Ho", [(1, 1), (2, 1), (2, 3)])
 @pytest.mark.parametrize("out_chunk", [8192, 0], ids=["out-staged", "out-zerocopy"])
-def test_stream_layers_with_outflow(S, Ho, out_chunk):
+@pytest.mark.parametrize("in_chunk", [8192, 0], ids=["in-staged", "in-zerocopy"])
+def test_stream_layers_with_outflow(S, Ho, out_chunk, in_chunk):
     """The whole loop of layer-wise prefill: layer l+1 is loaded while layer l is computed and
     layer l-1 (hit and appended rows, as the compute left them) leaves for host memory.  The
     compute here adds 1 to every byte of the slot; the oracle does the same to its slots."""
@@ -954,9 +955,10 @@ def test_stream_layers_with_outflow(S, Ho, out_chunk):
         got_out.append(out_host[slot].numpy().copy())
 
     torch.cuda.synchronize()
-    st = K.kvl_stream_layers(load, host, slots, staging, 8192, 0, cs, ks, ms, n_layers=L, host_fill=fill,
-                             compute=compute, out_plan=out, out_host_layers=out_host, out_staging=out_staging,
-                             out_chunk_bytes=out_chunk, host_drain=drain, per_layer_times=True)
+    st = K.kvl_stream_layers(load, host, slots, staging if in_chunk else None, in_chunk, 0, cs, ks, ms, n_layers=L,
+                             host_fill=fill, compute=compute, out_plan=out, out_host_layers=out_host,
+                             out_staging=out_staging, out_chunk_bytes=out_chunk, host_drain=drain,
+                             per_layer_times=True)
     assert drained == [(l, l % Ho) for l in range(L)]
     for l in range(L):
         assert same_bytes(got_out[l], want_out[l]), f"layer {l}: what left for host memory differs from the oracle"
