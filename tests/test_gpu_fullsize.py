@@ -311,3 +311,92 @@ def test_row_indices_at_the_32_bit_limit():
         p.destroy()
     del d_src, d_dst, d_x
     torch.cuda.empty_cache()
+
+
+def test_full_size_streamed_layers_with_outflow():
+    """Six layers of the streamed workload at full size, with every computed layer (hit and
+    appended rows) leaving for pinned host memory while the next ones are loaded.  The oracle
+    works on the first 16 bytes of every row, as above; whole rows are checked on a sample."""
+    t0 = time.perf_counter()
+    w = W.config(5)
+    L, bs, rows = 6, w.layout.block_tokens, w.layout.row_bytes
+    row = rows[0]
+    H = S = Ho = 2
+    lay = K.make_layout(w.layout.n_layers, bs, rows, w.dst.pool_blocks)
+    s = K.kvl_plan(lay, w.hit, w.app, w.dst.tables, K.KVL_SCATTER)
+    out = K.kvl_plan(lay, w.hit, w.app, w.dst.tables, K.KVL_GATHER | K.KVL_TOKENS_ALL)
+    n, T = s.payload_bytes, s.hit_tokens
+    total = (w.hit + w.app).astype(np.uint32)
+    T_all = int(total.astype(np.int64).sum())
+    assert out.payload_bytes == T_all * row
+    pool_rows = w.dst.pool_blocks * bs
+    rng = np.random.Generator(np.random.PCG64(W.BASE_SEED + 206))
+    tile = rng.integers(0, 256, size=1 << 24, dtype=np.uint8)
+    host = [torch.empty(n, dtype=torch.uint8, pin_memory=True) for _ in range(H)]
+    for h in host:
+        a = h.numpy()
+        for pos in range(0, n, tile.size):
+            k = min(tile.size, n - pos)
+            a[pos:pos + k] = tile[:k]
+    out_host = [torch.zeros(T_all * row, dtype=torch.uint8, pin_memory=True) for _ in range(Ho)]
+    g_idx = np.arange(T, dtype=np.uint64)
+
+    def tags_of(layer):
+        t = np.empty((T, 2), dtype=np.uint64)
+        t[:, 0] = layer
+        t[:, 1] = g_idx
+        return t
+
+    def fill(layer, slot):
+        host[slot].numpy().reshape(T, row)[:, :16] = tags_of(layer).view(np.uint8).reshape(T, 16)
+
+    o_slots = [[np.full(pool_rows * 16, 0xA5, dtype=np.uint8)] for _ in range(S)]
+    o_host = [np.zeros(T * 16, dtype=np.uint8) for _ in range(H)]
+    want_heads = []
+    gen = oracle.stream_layers(bs, (16,), w.hit, w.dst.tables, o_host, L, o_slots)
+    for l in range(L):
+        o_host[l % H][:] = tags_of(l).view(np.uint8).reshape(-1)
+        _, _, planes = next(gen)
+        want_heads.append(oracle.pack_range(bs, (16,), None, total, w.dst.tables, planes, threads=THREADS))
+    print(f"[cfg5 outflow] oracle done after {time.perf_counter() - t0:.1f} s", flush=True)
+
+    slots = [[torch.full((pool_rows * row,), 0xA5, dtype=torch.uint8, device="cuda")] for _ in range(S)]
+    chunk = 128 << 20
+    staging = torch.empty(2 * chunk, dtype=torch.uint8, device="cuda")
+    out_staging = torch.empty(chunk, dtype=torch.uint8, device="cuda")
+    cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    rs = np.random.Generator(np.random.PCG64(W.BASE_SEED + 306))
+    sample = np.sort(rs.choice(T_all, size=256, replace=False))
+    # where out-row j comes from: request r, token t; a hit token's row is the host buffer's
+    ends = np.cumsum(total.astype(np.int64))
+    hit_starts = np.concatenate(([0], np.cumsum(w.hit.astype(np.int64))))
+    seen = []
+
+    def drain(layer, slot):
+        got = out_host[slot].numpy().reshape(T_all, row)
+        heads = np.ascontiguousarray(got[:, :16]).reshape(-1)
+        assert same_bytes(heads, want_heads[layer]), f"layer {layer}: outflow heads differ from the oracle"
+        for j in sample:
+            r = int(np.searchsorted(ends, j, side="right"))
+            t = int(j - (ends[r] - total[r]))
+            if t < w.hit[r]:
+                assert got[j, 16:].tobytes() == tile_row(int(hit_starts[r]) + t), f"layer {layer} out-row {j}"
+            else:
+                assert np.all(got[j] == 0xA5), f"layer {layer} out-row {j}: an appended row nobody wrote"
+        seen.append(layer)
+
+    def tile_row(g):
+        # bytes 16.. of host row g: the repeated tile, whatever the layer
+        pos = g * row + 16
+        idx = (pos + np.arange(row - 16)) % tile.size
+        return tile[idx].tobytes()
+
+    torch.cuda.synchronize()
+    st = K.kvl_stream_layers(s, host, slots, staging, chunk, w.notes["compute_us"], cs, ks, ms, n_layers=L,
+                             host_fill=fill, out_plan=out, out_host_layers=out_host, out_staging=out_staging,
+                             out_chunk_bytes=chunk, host_drain=drain)
+    assert seen == list(range(L))
+    print(f"[cfg5 outflow] {L} layers in {st['total_ms']:.0f} ms: in {st['link_gbps']:.1f} GB/s, "
+          f"out {st['out_gbps']:.1f} GB/s, after {time.perf_counter() - t0:.1f} s", flush=True)
+    s.destroy()
+    out.destroy()
