@@ -25,7 +25,7 @@ BASE_SEED = 20260221
 __all__ = [
     "BASE_SEED", "Layout", "Side", "Workload", "config", "tiny",
     "make_tables", "fill_pool", "fill_pool_fast", "random_payload",
-    "sentinel_pool", "N_CONFIGS",
+    "sentinel_pool", "N_CONFIGS", "agent_trace", "AgentTrace", "PUBLISHED_TRACE_STATS", "from_trace",
 ]
 
 N_CONFIGS = 5
@@ -260,6 +260,25 @@ def tiny(seed: int, n_requests: int, block_tokens: int, row_bytes: Sequence[int]
     return Workload(f"tiny_{seed}", 0, lay, hit, app, src, dst, "bytes", seed)
 
 
+def from_trace(max_len_k: int = 64, n_requests: int = 16, seed: int = 0,
+               layout: Optional[Layout] = None, kind: str = "random") -> Workload:
+    """A batch of concurrent requests taken from the synthetic agent trace: one turn each of
+    ``n_requests`` different trajectories.  The turn's context is the request's hit prefix,
+    its appended tokens the tail.  Default layout: the 61-layer MLA cache of config 3."""
+    t = agent_trace(max_len_k, seed=seed)
+    rng = np.random.Generator(np.random.PCG64(BASE_SEED + 600 + seed))
+    trajs = rng.choice(t.n_traj, size=n_requests, replace=False)
+    rows = []
+    for i in trajs:
+        idx = np.flatnonzero(t.traj == i)
+        rows.append(int(rng.choice(idx[1:] if idx.size > 1 else idx)))      # not the first turn: nothing cached there
+    hit = t.context[rows].astype(np.uint32)
+    app = t.append[rows].astype(np.uint32)
+    lay = layout or Layout(61, 64, (1152,))
+    src, dst = _sides(hit, app, lay.block_tokens, kind, 1.1, None, BASE_SEED + 600 + seed)
+    return Workload(f"trace{max_len_k}k_{n_requests}req", 0, lay, hit, app, src, dst, "bytes", BASE_SEED + 600 + seed)
+
+
 # --------------------------------------------------------------------------
 # pool fills
 # --------------------------------------------------------------------------
@@ -339,3 +358,7 @@ def random_payload(w: Workload, layer: int, n_bytes: int) -> np.ndarray:
     """An arbitrary byte string of a given length (a transfer buffer's content)."""
     rng = _fill_rng(w, layer, 0, "payload")
     return rng.integers(0, 256, size=n_bytes, dtype=np.uint8)
+
+
+from .agent_trace import PUBLISHED as PUBLISHED_TRACE_STATS  # noqa: E402  (needs BASE_SEED above)
+from .agent_trace import AgentTrace, agent_trace  # noqa: E402

@@ -28,6 +28,7 @@ CASES = [
     ("cfg2-small", lambda: W.config(2, n_requests=7, token_scale=1 / 32)),
     ("cfg3-small", lambda: W.config(3, n_requests=12, token_scale=1 / 16)),
     ("cfg4-small", lambda: W.config(4, n_requests=12, token_scale=1 / 32)),
+    ("trace32k-6req", lambda: W.from_trace(32, 6)),                          # a batch of the synthetic agent trace
 ]
 
 

@@ -181,3 +181,70 @@ def test_read_side():
         want = O.read_side(a, b)
         assert want == (1 if b < a else 0)
         assert S.kvl_sched_read_side(a, b) == want
+
+
+# --------------------------------------------------------------------------
+# the rules driven by a request stream of the published shape
+# --------------------------------------------------------------------------
+
+def test_trace_driven_replay_library_follows_the_oracle():
+    """Requests of the 64K agent trace arrive in waves; prefill engines fetch with Algorithm 1,
+    decode groups and engines with the two decode phases; work drains between waves.  At every
+    step the library decides as the oracle does, and load stays balanced."""
+    import kvl_workloads as W
+    t = W.agent_trace(64, n_traj=120)
+    rng = np.random.Generator(np.random.PCG64(4242))
+    order = rng.permutation(t.traj.size)[:6000]
+    lens = (t.context + t.append)[order].tolist()                 # tokens(r): the request's total length
+    n_pe, n_groups, per_group = 8, 2, 4
+    alpha, beta = 150_000, 600_000
+    pe_tok, pe_read = [0] * n_pe, [0] * n_pe
+    g_tok = [0] * n_groups
+    de_tok = [[0] * per_group for _ in range(n_groups)]
+    de_seq = [[0] * per_group for _ in range(n_groups)]
+    de_free = [[3_000_000] * per_group for _ in range(n_groups)]
+    pos, steps = 0, 0
+    while pos < len(lens):
+        wave = lens[pos:pos + int(rng.integers(1, 40))]
+        pos += len(wave)
+        # prefill side
+        o_tok = list(pe_tok)
+        want = O.pe_fetch(o_tok, pe_read, wave, alpha, beta)
+        got, l_tok = S.kvl_sched_pe_fetch(pe_tok, pe_read, wave, alpha, beta)
+        assert got == want and l_tok.tolist() == o_tok
+        placed = [(e, n) for e, n in zip(want, wave) if e >= 0]
+        pe_tok = o_tok
+        for e, n in placed:                                       # reads queue on the engine's node (2 engines per node)
+            pe_read[e] += n
+            pe_read[e ^ 1] = pe_read[e]
+        # decode side: groups, then engines inside each group
+        done = [n for _, n in placed]
+        og = list(g_tok)
+        want_g = O.de_groups(og, done)
+        got_g, lg = S.kvl_sched_de_groups(g_tok, done)
+        assert got_g == want_g and lg.tolist() == og
+        g_tok = og
+        for g in range(n_groups):
+            q = [n for n, gg in zip(done, want_g) if gg == g]
+            ot, os_, of = list(de_tok[g]), list(de_seq[g]), list(de_free[g])
+            want_d, z = O.de_fetch(ot, os_, of, q)
+            got_d, lz, lt, ls, lf = S.kvl_sched_de_fetch(de_tok[g], de_seq[g], de_free[g], q)
+            assert got_d == want_d and lz == pytest.approx(z, rel=1e-15)
+            assert (lt.tolist(), ls.tolist(), lf.tolist()) == (ot, os_, of)
+            de_tok[g], de_seq[g], de_free[g] = ot, os_, of
+        # drain: engines work off a share of what they hold
+        for e in range(n_pe):
+            d = int(pe_tok[e] * rng.uniform(0.2, 0.9))
+            pe_tok[e] -= d
+            pe_read[e] = int(pe_read[e] * rng.uniform(0.1, 0.8))
+        for e in range(0, n_pe, 2):
+            pe_read[e + 1] = pe_read[e]
+        for g in range(n_groups):
+            for e in range(per_group):
+                d = int(de_tok[g][e] * rng.uniform(0.3, 0.9))
+                de_tok[g][e] -= d
+                de_free[g][e] += d
+                de_seq[g][e] = int(de_seq[g][e] * 0.5)
+            g_tok[g] = sum(de_tok[g])
+        steps += 1
+    assert steps > 100

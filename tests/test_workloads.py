@@ -87,3 +87,45 @@ def test_fills():
     tags = fast.view(np.uint64).reshape(-1, 1152 // 8)[:, 0]
     assert np.array_equal(tags & np.uint64(0xFFFFFFFFFFFF), np.arange(512 * 16, dtype=np.uint64))
     assert np.all(tags >> np.uint64(56) == 1)
+
+
+# --------------------------------------------------------------------------
+# agent trajectories shaped like the paper's trace datasets (Section 7.1, table of
+# agent trace statistics)
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("max_len_k", [32, 48, 64])
+def test_agent_trace_reproduces_the_published_averages(max_len_k):
+    pub = W.PUBLISHED_TRACE_STATS[max_len_k]
+    big = W.agent_trace(max_len_k, n_traj=4000).stats()          # little sampling noise: within 5 %
+    for k, v in pub.items():
+        assert big[k] == pytest.approx(v, rel=0.05), (k, big[k], v)
+    t = W.agent_trace(max_len_k)                                 # the datasets' own size: 500 trajectories
+    s = t.stats()
+    for k, v in pub.items():
+        assert s[k] == pytest.approx(v, rel=0.10), (k, s[k], v)
+    assert t.n_traj == 500 and int(t.traj.max()) == 499
+    # every request stays within MaxLen, and the cached prefix dominates it (Section 3: hit rates of 95 % and more)
+    assert int((t.context + t.append + t.gen).max()) <= max_len_k * 1024
+    assert s["hit_rate"] > 0.95
+    # a trajectory's context at a turn is everything before it
+    a = np.flatnonzero(t.traj == 7)
+    assert np.array_equal(t.context[a][1:], t.context[a][0] + np.cumsum(t.append[a] + t.gen[a])[:-1])
+    # seeded
+    u = W.agent_trace(max_len_k)
+    assert np.array_equal(t.context, u.context) and np.array_equal(t.append, u.append)
+    assert not np.array_equal(W.agent_trace(max_len_k, seed=1).context[:100], t.context[:100])
+
+
+def test_batch_drawn_from_the_trace_is_a_valid_workload():
+    w = W.from_trace(64, 16)
+    assert w.n_requests == 16 and w.layout.block_tokens == 64 and w.layout.row_bytes == (1152,)
+    for side in (w.src, w.dst):
+        ids = np.concatenate(side.tables)
+        assert ids.min() >= 0 and ids.max() < side.pool_blocks and np.unique(ids).size == ids.size
+        for r, t in enumerate(side.tables):
+            assert t.size == -(-(int(w.hit[r]) + int(w.app[r])) // 64)
+    assert np.all(w.hit > 0) and np.all(w.hit.astype(np.int64) + w.app <= 64 * 1024)
+    assert float(w.hit.sum()) / float(w.hit.sum() + w.app.sum()) > 0.95
+    v = W.from_trace(64, 16)
+    assert np.array_equal(v.hit, w.hit) and all(np.array_equal(a, b) for a, b in zip(v.src.tables, w.src.tables))
