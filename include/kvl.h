@@ -119,7 +119,7 @@ typedef struct {
 typedef struct {
     uint32_t unit_bytes;     /* target bytes of one descriptor (runs are split evenly to stay at or below it) */
     uint32_t block_threads;  /* threads per workgroup: 64, 128, 256, 512 or 1024 */
-    uint32_t variant;        /* 0: default; 1..128: an explicit kernel variant, see kvl_variant_name */
+    uint32_t variant;        /* 0: default; 1..256: an explicit kernel variant, see kvl_variant_name */
     uint32_t reserved;
 } kvl_tuning_t;
 

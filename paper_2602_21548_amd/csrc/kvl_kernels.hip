@@ -83,6 +83,22 @@ static void launch_tile_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const
     else launch_tile_sp<PACK, VPT, false>(v, g, b, s, a, tpu, al);
 }
 
+template <bool PACK, bool NTL>
+static void launch_flat_sp(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t mur) {
+    switch ((v >> 3) & 3u) {
+        case 0: hipLaunchKernelGGL((kvl_flat_kernel<PACK, NTL, 0>), g, b, 0, s, a, mur); break;
+        case 1: hipLaunchKernelGGL((kvl_flat_kernel<PACK, NTL, 1>), g, b, 0, s, a, mur); break;
+        case 2: hipLaunchKernelGGL((kvl_flat_kernel<PACK, NTL, 2>), g, b, 0, s, a, mur); break;
+        default: hipLaunchKernelGGL((kvl_flat_kernel<PACK, NTL, 3>), g, b, 0, s, a, mur); break;
+    }
+}
+
+template <bool PACK>
+static void launch_flat_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t mur) {
+    if (v & 4u) launch_flat_sp<PACK, true>(v, g, b, s, a, mur);
+    else launch_flat_sp<PACK, false>(v, g, b, s, a, mur);
+}
+
 int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_t unit_end,
                  uint32_t plane_begin, uint32_t plane_end,
                  void *const *pool_planes, const uintptr_t *xfer_plane, hipStream_t stream) {
@@ -119,10 +135,27 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
         else v = rows_128 ? kDefaultUnpackCode : kDefaultUnpackCodeOddRows;
     }
     dim3 block(threads);
+    uint32_t widest = 0;        // vectors of the largest descriptor, over the planes of this launch
+    for (uint32_t p = plane_begin; p < plane_end; ++p) widest = std::max(widest, a.row_elems[p]);
+    const uint64_t unit_vecs = (uint64_t)plan->max_unit_rows * widest;
+    // descriptors that fill less than half a workgroup: deal the lanes out without tiles
+    if (vec && !plan->tuning.variant && unit_vecs * 2 <= threads) v = pack ? kFlatPackCode : kFlatUnpackCode;
     if (!vec) {
         dim3 grid(a.n_units, plane_end - plane_begin);
         if (pack) hipLaunchKernelGGL(kvl_bytes_kernel<true>, grid, block, 0, stream, a);
         else hipLaunchKernelGGL(kvl_bytes_kernel<false>, grid, block, 0, stream, a);
+    } else if (v & 128u) {
+        // lane indices are 32 bits: split the descriptors over launches where they would not fit
+        const uint64_t per_launch = std::max<uint64_t>(1, ((1ull << 32) - threads) / std::max<uint64_t>(1, unit_vecs));
+        for (uint64_t first = 0; first < a.n_units; first += per_launch) {
+            CopyArgs part = a;
+            part.unit_begin = a.unit_begin + (uint32_t)first;
+            part.n_units = (uint32_t)std::min<uint64_t>(per_launch, a.n_units - first);
+            const uint64_t lanes = (uint64_t)part.n_units * unit_vecs;
+            dim3 grid((uint32_t)((lanes + threads - 1) / threads), plane_end - plane_begin);
+            if (pack) launch_flat_variant<true>(v, grid, block, stream, part, plan->max_unit_rows);
+            else launch_flat_variant<false>(v, grid, block, stream, part, plan->max_unit_rows);
+        }
     } else if ((v & 3u) >= 2u) {
         const uint32_t vpt = (v & 3u) == 3u ? 2 : 1;
         uint32_t max_row = 0;
@@ -334,8 +367,11 @@ const char *kvl_variant_name(uint32_t v) {
     v -= 1;
     static const char *modes[4] = {"wg/unit", "wave/unit", "tile x1", "tile x2"};
     static const char *sp[4] = {"", " st:nt", " st:sc1", " st:sc1+nt"};
-    std::snprintf(name, sizeof name, "%s%s%s%s%s", modes[v & 3u], (v & 4u) ? " ld:nt" : "",
-                  sp[(v >> 3) & 3u], (v & 32u) ? " deep" : "", (v & 64u) ? " noalign" : "");
+    if (v & 128u)
+        std::snprintf(name, sizeof name, "flat%s%s", (v & 4u) ? " ld:nt" : "", sp[(v >> 3) & 3u]);
+    else
+        std::snprintf(name, sizeof name, "%s%s%s%s%s", modes[v & 3u], (v & 4u) ? " ld:nt" : "",
+                      sp[(v >> 3) & 3u], (v & 32u) ? " deep" : "", (v & 64u) ? " noalign" : "");
     return name;
 }
 

@@ -29,6 +29,8 @@ CASES = [
     ("cfg3-small", lambda: W.config(3, n_requests=12, token_scale=1 / 16)),
     ("cfg4-small", lambda: W.config(4, n_requests=12, token_scale=1 / 32)),
     ("trace32k-6req", lambda: W.from_trace(32, 6)),                          # a batch of the synthetic agent trace
+    ("token-granular", lambda: W.tiny(215, 9, 1, (1152,), 3000, 300)),       # bs = 1: every token its own block (flat kernel)
+    ("token-granular-2planes", lambda: W.tiny(216, 7, 2, (256, 64), 2000, 250, kind="fragmented")),
 ]
 
 
@@ -107,7 +109,7 @@ def test_token_ranges(name, make, flag):
     run_range_hop(w, flag, unit_bytes=2048, variant=2)
 
 
-@pytest.mark.parametrize("variant", range(129))
+@pytest.mark.parametrize("variant", list(range(129)) + [1 + (128 | n << 2 | sp << 3) for n in (0, 1) for sp in range(4)])
 @pytest.mark.parametrize("threads", [64, 256, 1024])
 def test_every_variant(variant, threads):
     # units of 5 KiB against 64..1024 threads x 4..8 vectors: full steps, ragged tails and idle lanes
