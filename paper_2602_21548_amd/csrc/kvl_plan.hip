@@ -192,14 +192,17 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
                 *t1 = q.hit_tokens;
             }
         };
-        uint64_t T = 0;
+        uint64_t T = 0, touched = 0;
         for (uint32_t r = 0; r < n_req; ++r) {
             uint64_t t0, t1;
             range(req[r], &t0, &t1);
             T += t1 - t0;
+            if (t1 > t0) touched += (t1 + bs - 1) / bs - t0 / bs;
         }
         if (T > UINT32_MAX) { delete plan; return KVL_ERANGE; }
         plan->hit_tokens = T;
+        // one descriptor per touched block at most, unless blocks are larger than unit_bytes
+        plan->units.reserve((size_t)std::min<uint64_t>(touched, (uint64_t)INT32_MAX));
 
         uint64_t xfer_row = 0;
         uint64_t block_base = 0;          // touched blocks of the requests before r
