@@ -497,11 +497,54 @@ def short_hop(index: int, reps: int = 8, check: bool = True) -> dict:
         out["hop_us_eager"], out["hop_us_hip_graph"] = round(res["eager"], 2), round(res["graph"], 2)
         out["hops_per_graph"] = HOPS
         del graph
+        out["host_buffer_load"] = small_host_buffer_load(s, dst, payload, stream)
     g.destroy()
     s.destroy()
     del src, dst, xfer
     torch.cuda.empty_cache()
     return out
+
+
+def small_host_buffer_load(s, dst, payload, stream) -> dict:
+    """The host-buffer load of a layer that is small (a few MB): the time goes into enqueueing,
+    not into the link.  The staged form eager, the same captured in a HIP graph, and the
+    zero-copy form (one kernel that reads the pinned buffer itself)."""
+    import torch
+    import paper_2602_21548_amd as K
+    host = torch.zeros(payload, dtype=torch.uint8, pin_memory=True)
+    chunk = 1 << 20
+    staging = torch.empty(2 * chunk, dtype=torch.uint8, device="cuda")
+
+    def staged():
+        K.kvl_h2d_unpack_layer(s, host, staging, chunk, dst, stream, stream)
+
+    def zero_copy():
+        K.kvl_h2d_unpack_layer(s, host, None, 0, dst, stream, stream)
+
+    staged()
+    stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            staged()
+
+    def replay():
+        with torch.cuda.stream(stream):
+            graph.replay()
+
+    res = {"payload_bytes": payload, "staged": "2 slots of 1 MiB"}
+    for name, fn in (("staged_eager", staged), ("staged_hip_graph", replay), ("zero_copy_eager", zero_copy)):
+        fn()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(30):
+            fn()
+        stream.synchronize()
+        us = (time.perf_counter() - t0) / 30 * 1e6
+        res[name + "_us_per_layer"] = round(us, 1)
+        res[name + "_gbps"] = round(payload / us / 1e3, 2)
+    del graph
+    return res
 
 
 def host_link_legs(args) -> dict:

@@ -216,7 +216,13 @@ int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_byt
  * 8 MiB or more keep the per-copy submission cost (Section 5.2) negligible.
  * chunk_bytes == 0 selects the zero-copy form: no staging, no copies; one scatter
  * kernel on kernel_stream reads the pinned buffer across the host link itself
- * (dev_staging, staging_bytes and copy_stream are then unused). */
+ * (dev_staging, staging_bytes and copy_stream are then unused).  Which to take:
+ * every copy-then-kernel turn of a lane costs on the order of 100 us whatever the
+ * chunk's size, so the staged form pays off for layers of a gigabyte and more, or
+ * beside heavy compute (no wavefront waits on the link); for small layers the
+ * zero-copy form is several times faster.  The call only enqueues work and joins
+ * its lanes by events, so it can be captured in a HIP graph (pass the capturing
+ * stream for both stream arguments, after one eager call has made the lanes). */
 int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,
                          void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
                          void *const *pool_planes, void *copy_stream, void *kernel_stream);

@@ -569,6 +569,42 @@ def test_hip_graph_capture_and_replay():
             assert same_bytes(to_host(dst[l][0]), want[0]), f"replay {rep} layer {l}: pool"
 
 
+@pytest.mark.parametrize("chunk", [1 << 20, 0], ids=["staged", "zerocopy"])
+def test_hip_graph_capture_of_the_host_buffer_load(chunk):
+    """The host-buffer load forks onto the library's lanes and joins again, all by events, so a
+    caller may capture it too (both stream arguments the capturing stream; the lanes are made
+    by an eager call first).  Every replay, with a fresh host buffer and eager work in between,
+    must equal the oracle."""
+    w = W.config(1)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    n = s.payload_bytes
+    host = torch.zeros(n, dtype=torch.uint8, pin_memory=True)
+    staging = torch.zeros(2 * chunk, dtype=torch.uint8, device="cuda") if chunk else None
+    dst = planes_to_dev(W.sentinel_pool(w, "dst"))
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    K.kvl_h2d_unpack_layer(s, host, staging, chunk, dst, st, st)       # eager: creates the lanes
+    st.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(graph, stream=st):
+            K.kvl_h2d_unpack_layer(s, host, staging, chunk, dst, st, st)
+    for rep in range(3):
+        x = W.random_payload(w, 20 + rep, n)
+        host.numpy()[:] = x
+        for d in dst:
+            d.fill_(0xA5)                                              # eager work between replays
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            graph.replay()
+        st.synchronize()
+        want = W.sentinel_pool(w, "dst")
+        oracle.unpack(bs, rows, w.hit, w.dst.tables, x, want)
+        for a, b in zip(dst, want):
+            assert same_bytes(to_host(a), b), f"replay {rep}"
+
+
 @pytest.mark.parametrize("name,make", H2D_CASES, ids=[c[0] for c in H2D_CASES])
 def test_host_buffers_both_ways_whole_prompt(name, make):
     """The prefill-engine read path after a layer's compute (Section 4.1, steps 5-9): hit and miss
