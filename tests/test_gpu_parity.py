@@ -126,7 +126,7 @@ def test_unit_sizes(unit_bytes):
     run_hop(w, unit_bytes=unit_bytes, variant=4)
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(64))
 def test_random_batches(seed):
     """Random small batches: all table kinds, ragged hits, 1-3 planes, rows that take the vector
     path with and without line alignment and rows that take the byte path."""
