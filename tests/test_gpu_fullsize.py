@@ -126,10 +126,17 @@ def test_full_size_full_blocks_from_pinned_host():
     zero = np.zeros_like(w.hit)
     # 8-byte-row instance of the same definition for the row heads of every layer
     head_buf = np.ascontiguousarray(a.reshape(nfb, L, bs, row)[:, :, :, :8]).reshape(-1)
+    chunk = 32 << 20
+    staging = torch.empty(2 * chunk, dtype=torch.uint8, device="cuda")
+    cs = torch.cuda.Stream()
     for l in range(L):
         torch.cuda.synchronize()
-        K.kvl_fullblocks_to_pool_layer(s, host, l, pool, stream=st)
+        if l % 2:       # odd layers by the staged form: strided copies into HBM slots, converting kernels there
+            K.kvl_h2d_fullblocks_layer(s, host, l, staging, chunk, pool, cs, st)
+        else:           # even layers by the one kernel that reads the host buffer itself
+            K.kvl_fullblocks_to_pool_layer(s, host, l, pool, stream=st)
         st.synchronize()
+        cs.synchronize()
         want_h = [np.full(w.dst.pool_blocks * bs * 8, 0xA5, dtype=np.uint8)]
         oracle.fullblocks_to_pool(bs, L, (8,), zero, w.hit, w.dst.tables, l, head_buf, want_h)
         got_h = pool[0].view(-1, row)[:, :8].contiguous()
@@ -138,8 +145,19 @@ def test_full_size_full_blocks_from_pinned_host():
             want = [np.full(w.dst.pool_blocks * bs * row, 0xA5, dtype=np.uint8)]
             oracle.fullblocks_to_pool(bs, L, rows, zero, w.hit, w.dst.tables, l, a, want)
             assert np.array_equal(to_host(pool[0]), want[0]), f"layer {l} differs from the oracle"
+    # and back: the pool of the last layer persisted into a fresh buffer's layer 5 by the staged form
+    g = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables,
+                   K.KVL_GATHER | K.KVL_NO_MERGE)
+    last = [to_host(pool[0])]
+    want_back = a.copy()
+    oracle.pool_to_fullblocks(bs, L, rows, zero, w.hit, w.dst.tables, 5, last, want_back)
+    K.kvl_d2h_fullblocks_layer(g, pool, 5, staging, chunk, host, st, cs)
+    st.synchronize()
+    cs.synchronize()
+    assert np.array_equal(a, want_back), "staged persist differs from the oracle"
     print(f"[fullblocks] done after {time.perf_counter() - t0:.1f} s", flush=True)
     s.destroy()
+    g.destroy()
 
 
 @pytest.mark.parametrize("idx", [2, 4])
