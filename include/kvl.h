@@ -427,10 +427,10 @@ int kvl_measure_h2d_peak(const void *pinned_host, void *dev, uint64_t bytes, uin
 int kvl_copy_linear(const void *src, void *dst, uint64_t bytes, void *stream);
 
 /* What every entry point asks of a buffer before a kernel may touch it: is
- * [ptr, ptr + bytes) memory this device can address?  Device allocations are
- * checked against their extent (KVL_ESPACE if the span runs past it); host memory
- * passes only if allow_host is non-zero and it is pinned and mapped (pageable host
- * memory and stray pointers give KVL_EINVAL).  A wrong pointer thus comes back as
+ * [ptr, ptr + bytes) memory this device can address?  Host memory passes only if
+ * allow_host is non-zero and it is pinned and mapped (pageable host memory and
+ * stray pointers give KVL_EINVAL); device and pinned allocations are checked
+ * against their extent (KVL_ESPACE if the span runs past it).  A wrong pointer thus comes back as
  * an error code instead of a memory fault on the GPU.  Costs a few microseconds
  * per buffer; a plan made with KVL_NO_POINTER_CHECKS skips it. */
 int kvl_check_buffer(const void *ptr, uint64_t bytes, int allow_host);

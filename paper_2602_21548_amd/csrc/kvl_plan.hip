@@ -441,18 +441,19 @@ int kvl_check_buffer(const void *ptr, uint64_t bytes, int allow_host) {
         (void)hipGetLastError();                     // not an error of ours: the pointer is unknown to HIP
         return KVL_EINVAL;
     }
-    if (a.type == hipMemoryTypeDevice || a.type == hipMemoryTypeManaged) {
-        hipDeviceptr_t base = nullptr;
-        size_t size = 0;
-        if (hipMemGetAddressRange(&base, &size, const_cast<void *>(ptr)) != hipSuccess) {
-            (void)hipGetLastError();
-            return KVL_OK;                           // extent unknown: nothing more to check
-        }
-        const uintptr_t p = reinterpret_cast<uintptr_t>(ptr), b = reinterpret_cast<uintptr_t>(base);
-        return (p >= b && bytes <= size && p - b <= size - bytes) ? KVL_OK : KVL_ESPACE;
+    const bool on_device = a.type == hipMemoryTypeDevice || a.type == hipMemoryTypeManaged;
+    if (!on_device && a.type != hipMemoryTypeHost) return KVL_EINVAL;   // unregistered (pageable) host memory, arrays
+    if (a.type == hipMemoryTypeHost && !(allow_host && a.devicePointer)) return KVL_EINVAL;
+    // the extent of the allocation, where the runtime knows it (it does for its own device and
+    // pinned host allocations)
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(&base, &size, const_cast<void *>(ptr)) != hipSuccess) {
+        (void)hipGetLastError();
+        return KVL_OK;                               // extent unknown: nothing more to check
     }
-    if (a.type == hipMemoryTypeHost) return (allow_host && a.devicePointer) ? KVL_OK : KVL_EINVAL;
-    return KVL_EINVAL;                               // unregistered (pageable) host memory, arrays
+    const uintptr_t p = reinterpret_cast<uintptr_t>(ptr), b = reinterpret_cast<uintptr_t>(base);
+    return (p >= b && bytes <= size && p - b <= size - bytes) ? KVL_OK : KVL_ESPACE;
 }
 
 void kvl_release_cached_memory(void) {

@@ -257,6 +257,8 @@ int main(int argc, char **argv) {
     expect(kvl_check_buffer((char *)d_xfer + payload - 16, 16, 0), KVL_OK, "kvl_check_buffer: last 16 bytes");
     expect(kvl_check_buffer(pinned, payload, 1), KVL_OK, "kvl_check_buffer: pinned host memory where allowed");
     expect(kvl_check_buffer(pinned, payload, 0), KVL_EINVAL, "kvl_check_buffer: pinned host memory where not");
+    expect(kvl_check_buffer(pinned, payload + 1, 1), KVL_ESPACE, "kvl_check_buffer: one byte past a pinned allocation");
+    expect(kvl_check_buffer((char *)pinned + 64, payload - 64, 1), KVL_OK, "kvl_check_buffer: inside a pinned allocation");
 
     void *short_pool[P] = {d_src[0], NULL};
     HIP_OK(hipMalloc(&short_pool[1], plane_bytes[1] - (size_t)BS * rows[1]));
