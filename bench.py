@@ -688,18 +688,19 @@ def stream_under_busy_compute(plan, host, slots, staging, chunk, cs, ks, ms, lay
     e1.record(ms)
     e1.synchronize()
     alone = e0.elapsed_time(e1)
-    st = K.kvl_stream_layers(plan, host, slots, staging[:2 * chunk], chunk, 0, cs, ks, ms, n_layers=layers,
-                             compute=compute, per_layer_times=True)
-    # the last layer's computation runs after every load has finished: leave it out
-    busy = (st["t_compute_end"] - st["t_compute_begin"])[:-1]
+    res = {"layers": layers, "compute": f"{reps} x 4 GiB device copies per layer on the compute stream",
+           "compute_ms_per_layer_alone": round(alone, 2),
+           "hw_queues": os.environ.get("GPU_MAX_HW_QUEUES", "runtime default")}
+    for name, stg, ch in (("zero_copy", None, 0), ("staged_2_slots", staging[:2 * chunk], chunk)):
+        st = K.kvl_stream_layers(plan, host, slots, stg, ch, 0, cs, ks, ms, n_layers=layers,
+                                 compute=compute, per_layer_times=True)
+        # the last layer's computation runs after every load has finished: leave it out
+        busy = (st["t_compute_end"] - st["t_compute_begin"])[:-1]
+        res[name] = {"link_gbps": round(st["link_gbps"], 2), "frac_of_link": round(st["link_gbps"] / peak, 4),
+                     "compute_ms_per_layer_during_load": round(float(busy.mean()), 2) if len(busy) else None}
     del a, b
     torch.cuda.empty_cache()
-    return {"layers": layers, "compute": f"{reps} x 4 GiB device copies per layer on the compute stream",
-            "link_gbps": round(st["link_gbps"], 2), "frac_of_link": round(st["link_gbps"] / peak, 4),
-            "compute_ms_per_layer_alone": round(alone, 2),
-            "compute_ms_per_layer_during_load": round(float(busy.mean()), 2) if len(busy) else None,
-            "staging_slots": 2,
-            "hw_queues": os.environ.get("GPU_MAX_HW_QUEUES", "runtime default")}
+    return res
 
 
 def full_block_leg(pinned: "torch.Tensor", h2d_peak: float) -> dict:

@@ -120,7 +120,11 @@ typedef struct {
     uint32_t unit_bytes;     /* target bytes of one descriptor (runs are split evenly to stay at or below it) */
     uint32_t block_threads;  /* threads per workgroup: 64, 128, 256, 512 or 1024 */
     uint32_t variant;        /* 0: default; 1..256: an explicit kernel variant, see kvl_variant_name */
-    uint32_t reserved;
+    uint32_t max_groups;     /* tiled and Full-Block kernels: at most this many workgroups per launch and
+                                plane, each walking over several tiles.  0: one workgroup per tile, except
+                                that a kernel whose far side is host memory is kept to 96 (enough to fill
+                                the host link; the rest of the machine stays free for other kernels);
+                                UINT32_MAX: never walk */
 } kvl_tuning_t;
 
 /* Build a plan.  Validates the batch (KVL_ERANGE: a block id outside
@@ -143,8 +147,8 @@ int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, ui
 void kvl_plan_destroy(kvl_plan_t *plan);
 void kvl_release_cached_memory(void);
 
-/* Change launch tuning (block_threads, variant) of an existing plan;
- * unit_bytes is fixed at plan time and ignored here. */
+/* Change launch tuning (block_threads if not 0, variant, max_groups) of an existing
+ * plan; unit_bytes is fixed at plan time and ignored here. */
 int kvl_plan_set_tuning(kvl_plan_t *plan, const kvl_tuning_t *tuning);
 
 /* Plan inspection (host side, valid for any plan). */
@@ -216,11 +220,13 @@ int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_byt
  * 8 MiB or more keep the per-copy submission cost (Section 5.2) negligible.
  * chunk_bytes == 0 selects the zero-copy form: no staging, no copies; one scatter
  * kernel on kernel_stream reads the pinned buffer across the host link itself
- * (dev_staging, staging_bytes and copy_stream are then unused).  Which to take:
- * every copy-then-kernel turn of a lane costs on the order of 100 us whatever the
- * chunk's size, so the staged form pays off for layers of a gigabyte and more, or
- * beside heavy compute (no wavefront waits on the link); for small layers the
- * zero-copy form is several times faster.  The call only enqueues work and joins
+ * (dev_staging, staging_bytes and copy_stream are then unused); it runs with few
+ * workgroups (kvl_tuning_t::max_groups), enough to fill the link, so that it does
+ * not take the compute units from other kernels.  Which to take: every
+ * copy-then-kernel turn of a lane costs on the order of 100 us whatever the chunk's
+ * size, so the staged form pays off only for layers of gigabytes on an otherwise
+ * idle GPU (2-3 % more of the link); for small layers and beside heavy compute the
+ * zero-copy form is the faster one.  The call only enqueues work and joins
  * its lanes by events, so it can be captured in a HIP graph (pass the capturing
  * stream for both stream arguments, after one eager call has made the lanes). */
 int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,

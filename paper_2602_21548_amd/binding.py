@@ -52,7 +52,7 @@ class kvl_unit_t(C.Structure):
 
 class kvl_tuning_t(C.Structure):
     _fields_ = [("unit_bytes", C.c_uint32), ("block_threads", C.c_uint32), ("variant", C.c_uint32),
-                ("reserved", C.c_uint32)]
+                ("max_groups", C.c_uint32)]
 
 
 class kvl_chunk_t(C.Structure):
@@ -276,8 +276,8 @@ class Plan:
             arr[cu // 32] |= 1 << (cu % 32)
         _check(_lib.kvl_plan_set_lane_cu_mask(self.handle, arr, words), "kvl_plan_set_lane_cu_mask")
 
-    def set_tuning(self, block_threads: int = 0, variant: int = 0) -> None:
-        t = kvl_tuning_t(0, block_threads, variant, 0)
+    def set_tuning(self, block_threads: int = 0, variant: int = 0, max_groups: int = 0) -> None:
+        t = kvl_tuning_t(0, block_threads, variant, max_groups)
         _check(_lib.kvl_plan_set_tuning(self.handle, C.byref(t)), "kvl_plan_set_tuning")
 
 
@@ -292,7 +292,7 @@ def make_layout(n_layers: int, block_tokens: int, row_bytes: Sequence[int], pool
 
 
 def kvl_plan(layout: kvl_layout_t, hit, app, tables: Sequence[np.ndarray], flags: int,
-             unit_bytes: int = 0, block_threads: int = 0, variant: int = 0) -> Plan:
+             unit_bytes: int = 0, block_threads: int = 0, variant: int = 0, max_groups: int = 0) -> Plan:
     """kvl_plan / kvl_plan_tuned: block tables -> copy descriptors (host; device upload unless HOST_ONLY)."""
     hit = np.asarray(hit, dtype=np.uint32)
     app = np.asarray(app, dtype=np.uint32)
@@ -307,8 +307,8 @@ def kvl_plan(layout: kvl_layout_t, hit, app, tables: Sequence[np.ndarray], flags
         reqs[r].n_blocks = int(keep[r].size)
         reqs[r].block_table = keep[r].ctypes.data_as(C.POINTER(C.c_int32)) if keep[r].size else None
     out = C.c_void_p()
-    if unit_bytes or block_threads or variant:
-        t = kvl_tuning_t(unit_bytes, block_threads, variant, 0)
+    if unit_bytes or block_threads or variant or max_groups:
+        t = kvl_tuning_t(unit_bytes, block_threads, variant, max_groups)
         rc = _lib.kvl_plan_tuned(C.byref(layout), reqs, n, flags, C.byref(t), C.byref(out))
     else:
         rc = _lib.kvl_plan(C.byref(layout), reqs, n, flags, C.byref(out))

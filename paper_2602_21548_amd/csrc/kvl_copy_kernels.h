@@ -164,9 +164,10 @@ __global__ void __launch_bounds__(1024) kvl_unpack_kernel(const CopyArgs a) {
 // operations: the hardware keeps the memory system busy by the sheer number of
 // resident wavefronts rather than by unrolling.
 template <bool PACK, int VPT, bool NTL, int SP>
-__device__ __forceinline__ void tile_body(const CopyArgs &a, uint32_t tiles_per_unit, uint32_t align_dst) {
-    const uint32_t u_idx = blockIdx.x / tiles_per_unit;
-    const uint32_t tile = blockIdx.x - u_idx * tiles_per_unit;
+__device__ __forceinline__ void tile_body(const CopyArgs &a, uint32_t tiles_per_unit, uint32_t align_dst,
+                                          uint32_t tile_index) {
+    const uint32_t u_idx = tile_index / tiles_per_unit;
+    const uint32_t tile = tile_index - u_idx * tiles_per_unit;
     const kvl_unit_t u = a.units[a.unit_begin + u_idx];
     const uint32_t p = a.plane_begin + blockIdx.y;
     const uint32_t row = a.row_elems[p];
@@ -182,7 +183,7 @@ __device__ __forceinline__ void tile_body(const CopyArgs &a, uint32_t tiles_per_
     // `lead` lanes of the first tile idle.
     const uint32_t lead = align_dst ? ((uint32_t)((PACK ? xfer : pool) >> 4) & 7u) : 0u;
     const uint32_t first = tile * (blockDim.x * VPT);
-    if (first >= n + lead) return;
+    if (first >= n + lead) return;      // this tile lies beyond the descriptor's end
     v4u v[VPT];
 #pragma unroll
     for (int k = 0; k < VPT; ++k) {
@@ -199,13 +200,25 @@ __device__ __forceinline__ void tile_body(const CopyArgs &a, uint32_t tiles_per_
 template <int VPT, bool NTL, int SP>
 __global__ void __launch_bounds__(1024) kvl_pack_tile_kernel(const CopyArgs a, uint32_t tiles_per_unit,
                                                              uint32_t align_dst) {
-    tile_body<true, VPT, NTL, SP>(a, tiles_per_unit, align_dst);
+    tile_body<true, VPT, NTL, SP>(a, tiles_per_unit, align_dst, blockIdx.x);
 }
 
 template <int VPT, bool NTL, int SP>
 __global__ void __launch_bounds__(1024) kvl_unpack_tile_kernel(const CopyArgs a, uint32_t tiles_per_unit,
                                                                uint32_t align_dst) {
-    tile_body<false, VPT, NTL, SP>(a, tiles_per_unit, align_dst);
+    tile_body<false, VPT, NTL, SP>(a, tiles_per_unit, align_dst, blockIdx.x);
+}
+
+// Thin form of the tiled kernels: a fixed, small number of workgroups, each walking over
+// the tiles gridDim.x apart.  For buffers on the far side of the host link: a few hundred
+// wavefronts keep the link full (its rate times its latency is about 100 KB in flight),
+// so there is no reason to fill every compute unit with wavefronts that wait for it, and
+// kernels of other streams keep the machine.  The trip count is fixed at launch.
+template <bool PACK, int VPT, bool NTL, int SP>
+__global__ void __launch_bounds__(1024) kvl_tile_walk_kernel(const CopyArgs a, uint32_t tiles_per_unit,
+                                                             uint32_t align_dst, uint32_t n_tiles) {
+    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x)
+        tile_body<PACK, VPT, NTL, SP>(a, tiles_per_unit, align_dst, t);
 }
 
 // Flat form for descriptors much smaller than a workgroup: the lanes of the launch are
@@ -262,9 +275,9 @@ struct FullBlockArgs {
 };
 
 template <bool TO_POOL, bool VEC>
-__global__ void __launch_bounds__(256) kvl_fullblock_kernel(const FullBlockArgs a, uint32_t tiles_per_unit) {
-    const uint32_t u_idx = blockIdx.x / tiles_per_unit;
-    const uint32_t tile = blockIdx.x - u_idx * tiles_per_unit;
+__device__ __forceinline__ void fullblock_tile(const FullBlockArgs &a, uint32_t tiles_per_unit, uint32_t tile_index) {
+    const uint32_t u_idx = tile_index / tiles_per_unit;
+    const uint32_t tile = tile_index - u_idx * tiles_per_unit;
     const kvl_unit_t u = a.units[u_idx];
     const uint32_t p = blockIdx.y;
     const uint32_t row = a.row_elems[p];
@@ -284,6 +297,13 @@ __global__ void __launch_bounds__(256) kvl_fullblock_kernel(const FullBlockArgs 
         if (TO_POOL) pool[in_pool] = blocks[in_blocks];
         else blocks[in_blocks] = pool[in_pool];
     }
+}
+
+// gridDim.x workgroups walk over the n_tiles tiles (one tile each when there are as many).
+template <bool TO_POOL, bool VEC>
+__global__ void __launch_bounds__(256) kvl_fullblock_kernel(const FullBlockArgs a, uint32_t tiles_per_unit,
+                                                            uint32_t n_tiles) {
+    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) fullblock_tile<TO_POOL, VEC>(a, tiles_per_unit, t);
 }
 
 // Straight copy, one vector per lane: the tiled kernel without descriptors.

@@ -102,7 +102,7 @@ int enqueue_zero_copy_layer(const kvl_plan_t *plan, const void *host_xfer, void 
     for (uint32_t p = 0; p < plan->layout.n_planes; ++p)
         xp[p] = reinterpret_cast<uintptr_t>(host_xfer) + plan->plane_base[p];
     return launch_units(plan, false, 0, (uint32_t)plan->units.size(), 0, plan->layout.n_planes,
-                        pool_planes, xp, kern_s);
+                        pool_planes, xp, kern_s, is_host_memory(plan, host_xfer));
 }
 
 // Staging area of the staged Full-Block load: chunks hold whole Layer Blocks.

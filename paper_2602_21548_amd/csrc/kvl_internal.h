@@ -49,6 +49,7 @@ void set_hip_error(hipError_t e);
 
 constexpr uint32_t kDefaultUnitBytes = 128u << 10;
 constexpr uint32_t kDefaultBlockThreads = 256;
+constexpr uint32_t kHostSideGroups = 96;    // workgroups of a kernel whose far side is host memory (see kvl_tile_walk_kernel)
 constexpr uint32_t kNumVariants = 256;       // explicit variants are 1 .. kNumVariants
 bool valid_block_threads(uint32_t t);
 
@@ -59,9 +60,13 @@ int make_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, std::vector<kvl_ch
 // [plane_begin, plane_end).  xfer_plane[p] is the address at which transfer row
 // 0 of plane p would lie (it may point before a staging slot; only rows of the
 // given descriptors are touched).
+// far_host: the transfer side lies in host memory (the kernel crosses the host link).
 int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_t unit_end,
                  uint32_t plane_begin, uint32_t plane_end,
-                 void *const *pool_planes, const uintptr_t *xfer_plane, hipStream_t stream);
+                 void *const *pool_planes, const uintptr_t *xfer_plane, hipStream_t stream,
+                 bool far_host = false);
+// true if HIP knows ptr as pinned host memory (false when the plan skips pointer checks)
+bool is_host_memory(const kvl_plan_t *plan, const void *ptr);
 
 int upload_units(kvl_plan_t *plan);
 // kvl_check_buffer unless the plan opted out
@@ -75,7 +80,7 @@ uint64_t layer_block_bytes(const kvl_plan_t *plan);
 int check_fullblock_args(const kvl_plan_t *plan, bool to_pool, uint64_t blocks_bytes, uint32_t layer);
 int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint64_t block_pitch,
                      uint64_t layer_off, uint32_t unit_begin, uint32_t unit_end,
-                     void *const *pool_planes, hipStream_t stream);
+                     void *const *pool_planes, hipStream_t stream, bool far_host = false);
 // Enqueue the move of one layer between a buffer of Full Blocks and a paged pool.
 int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint64_t blocks_bytes,
                     uint32_t layer, void *const *pool_planes, hipStream_t stream);

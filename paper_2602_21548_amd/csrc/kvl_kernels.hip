@@ -59,28 +59,31 @@ static void launch_span_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const
     }
 }
 
+// n_tiles != 0: the launch has fewer workgroups than tiles and they walk over them
 template <bool PACK, int VPT, bool NTL, int SP>
-static void launch_tile_one(dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu, uint32_t al) {
-    if (PACK) hipLaunchKernelGGL((kvl_pack_tile_kernel<VPT, NTL, SP>), g, b, 0, s, a, tpu, al);
+static void launch_tile_one(dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu, uint32_t al,
+                            uint32_t n_tiles) {
+    if (n_tiles) hipLaunchKernelGGL((kvl_tile_walk_kernel<PACK, VPT, NTL, SP>), g, b, 0, s, a, tpu, al, n_tiles);
+    else if (PACK) hipLaunchKernelGGL((kvl_pack_tile_kernel<VPT, NTL, SP>), g, b, 0, s, a, tpu, al);
     else hipLaunchKernelGGL((kvl_unpack_tile_kernel<VPT, NTL, SP>), g, b, 0, s, a, tpu, al);
 }
 
 template <bool PACK, int VPT, bool NTL>
 static void launch_tile_sp(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu,
-                           uint32_t al) {
+                           uint32_t al, uint32_t n_tiles) {
     switch ((v >> 3) & 3u) {
-        case 0: launch_tile_one<PACK, VPT, NTL, 0>(g, b, s, a, tpu, al); break;
-        case 1: launch_tile_one<PACK, VPT, NTL, 1>(g, b, s, a, tpu, al); break;
-        case 2: launch_tile_one<PACK, VPT, NTL, 2>(g, b, s, a, tpu, al); break;
-        default: launch_tile_one<PACK, VPT, NTL, 3>(g, b, s, a, tpu, al); break;
+        case 0: launch_tile_one<PACK, VPT, NTL, 0>(g, b, s, a, tpu, al, n_tiles); break;
+        case 1: launch_tile_one<PACK, VPT, NTL, 1>(g, b, s, a, tpu, al, n_tiles); break;
+        case 2: launch_tile_one<PACK, VPT, NTL, 2>(g, b, s, a, tpu, al, n_tiles); break;
+        default: launch_tile_one<PACK, VPT, NTL, 3>(g, b, s, a, tpu, al, n_tiles); break;
     }
 }
 
 template <bool PACK, int VPT>
 static void launch_tile_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu,
-                                uint32_t al) {
-    if (v & 4u) launch_tile_sp<PACK, VPT, true>(v, g, b, s, a, tpu, al);
-    else launch_tile_sp<PACK, VPT, false>(v, g, b, s, a, tpu, al);
+                                uint32_t al, uint32_t n_tiles) {
+    if (v & 4u) launch_tile_sp<PACK, VPT, true>(v, g, b, s, a, tpu, al, n_tiles);
+    else launch_tile_sp<PACK, VPT, false>(v, g, b, s, a, tpu, al, n_tiles);
 }
 
 template <bool PACK, bool NTL>
@@ -101,7 +104,7 @@ static void launch_flat_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const
 
 int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_t unit_end,
                  uint32_t plane_begin, uint32_t plane_end,
-                 void *const *pool_planes, const uintptr_t *xfer_plane, hipStream_t stream) {
+                 void *const *pool_planes, const uintptr_t *xfer_plane, hipStream_t stream, bool far_host) {
     if (unit_end <= unit_begin || plane_end <= plane_begin) return KVL_OK;
     if (!plan->d_units || unit_end > plan->units.size() || plane_end > plan->layout.n_planes)
         return KVL_EINVAL;
@@ -170,13 +173,17 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
         const uint64_t tpu = ((uint64_t)plan->max_unit_rows * max_row + (al ? 7 : 0) + per_tile - 1) / per_tile;
         const uint64_t blocks = (uint64_t)a.n_units * tpu;
         if (tpu == 0 || blocks > (uint64_t)INT32_MAX) return KVL_ERANGE;
-        dim3 grid((uint32_t)blocks, plane_end - plane_begin);
+        // fewer workgroups than tiles, each walking over several: on request, or because the
+        // far side is host memory
+        const uint32_t cap = plan->tuning.max_groups ? plan->tuning.max_groups : (far_host ? kHostSideGroups : 0u);
+        const uint32_t n_tiles = (cap && blocks > cap) ? (uint32_t)blocks : 0u;
+        dim3 grid(n_tiles ? cap : (uint32_t)blocks, plane_end - plane_begin);
         if (pack) {
-            if (vpt == 2) launch_tile_variant<true, 2>(v, grid, block, stream, a, (uint32_t)tpu, al);
-            else launch_tile_variant<true, 1>(v, grid, block, stream, a, (uint32_t)tpu, al);
+            if (vpt == 2) launch_tile_variant<true, 2>(v, grid, block, stream, a, (uint32_t)tpu, al, n_tiles);
+            else launch_tile_variant<true, 1>(v, grid, block, stream, a, (uint32_t)tpu, al, n_tiles);
         } else {
-            if (vpt == 2) launch_tile_variant<false, 2>(v, grid, block, stream, a, (uint32_t)tpu, al);
-            else launch_tile_variant<false, 1>(v, grid, block, stream, a, (uint32_t)tpu, al);
+            if (vpt == 2) launch_tile_variant<false, 2>(v, grid, block, stream, a, (uint32_t)tpu, al, n_tiles);
+            else launch_tile_variant<false, 1>(v, grid, block, stream, a, (uint32_t)tpu, al, n_tiles);
         }
     } else {
         const uint32_t per_wg = (v & 3u) == 1u ? threads / 64 : 1;
@@ -196,7 +203,7 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
 // Layer-Block size and layer_off is 0 (base may then lie before the area).
 int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint64_t block_pitch,
                      uint64_t layer_off, uint32_t unit_begin, uint32_t unit_end,
-                     void *const *pool_planes, hipStream_t stream) {
+                     void *const *pool_planes, hipStream_t stream, bool far_host) {
     if (unit_end <= unit_begin) return KVL_OK;
     if (!plan->d_units || unit_end > plan->units.size()) return KVL_EINVAL;
     const uint32_t P = plan->layout.n_planes;
@@ -226,13 +233,15 @@ int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint6
     const uint64_t tpu = ((uint64_t)plan->max_unit_rows * max_row + threads - 1) / threads;
     const uint64_t wgs = (uint64_t)a.n_units * tpu;
     if (tpu == 0 || wgs > (uint64_t)INT32_MAX) return KVL_ERANGE;
-    dim3 grid((uint32_t)wgs, P), block(threads);
+    const uint32_t cap = plan->tuning.max_groups ? plan->tuning.max_groups : (far_host ? kHostSideGroups : 0u);
+    const uint32_t n_tiles = (uint32_t)wgs;
+    dim3 grid((cap && wgs > cap) ? cap : (uint32_t)wgs, P), block(threads);
     if (to_pool) {
-        if (vec) hipLaunchKernelGGL((kvl_fullblock_kernel<true, true>), grid, block, 0, stream, a, (uint32_t)tpu);
-        else hipLaunchKernelGGL((kvl_fullblock_kernel<true, false>), grid, block, 0, stream, a, (uint32_t)tpu);
+        if (vec) hipLaunchKernelGGL((kvl_fullblock_kernel<true, true>), grid, block, 0, stream, a, (uint32_t)tpu, n_tiles);
+        else hipLaunchKernelGGL((kvl_fullblock_kernel<true, false>), grid, block, 0, stream, a, (uint32_t)tpu, n_tiles);
     } else {
-        if (vec) hipLaunchKernelGGL((kvl_fullblock_kernel<false, true>), grid, block, 0, stream, a, (uint32_t)tpu);
-        else hipLaunchKernelGGL((kvl_fullblock_kernel<false, false>), grid, block, 0, stream, a, (uint32_t)tpu);
+        if (vec) hipLaunchKernelGGL((kvl_fullblock_kernel<false, true>), grid, block, 0, stream, a, (uint32_t)tpu, n_tiles);
+        else hipLaunchKernelGGL((kvl_fullblock_kernel<false, false>), grid, block, 0, stream, a, (uint32_t)tpu, n_tiles);
     }
     KVL_HIP(hipGetLastError());
     return KVL_OK;
@@ -271,7 +280,7 @@ int fullblock_layer(const kvl_plan_t *plan, bool to_pool, uintptr_t blocks, uint
         rc = check_buffer(plan, reinterpret_cast<const void *>(blocks), plan->blocks_touched * fb, true);
     if (rc != KVL_OK) return rc;
     return fullblock_launch(plan, to_pool, blocks, fb, (uint64_t)layer * lb, 0, (uint32_t)plan->units.size(),
-                            pool_planes, stream);
+                            pool_planes, stream, is_host_memory(plan, reinterpret_cast<const void *>(blocks)));
 }
 
 }  // namespace kvl
@@ -323,7 +332,8 @@ int kvl_pack_layer(const kvl_plan_t *plan, const void *const *pool_planes, void 
     for (uint32_t p = 0; p < plan->layout.n_planes; ++p)
         xp[p] = reinterpret_cast<uintptr_t>(xfer) + plan->plane_base[p];
     return kvl::launch_units(plan, true, 0, (uint32_t)plan->units.size(), 0, plan->layout.n_planes,
-                             const_cast<void *const *>(pool_planes), xp, (hipStream_t)stream);
+                             const_cast<void *const *>(pool_planes), xp, (hipStream_t)stream,
+                             kvl::is_host_memory(plan, xfer));
 }
 
 int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_bytes,
@@ -340,7 +350,7 @@ int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_byt
     for (uint32_t p = 0; p < plan->layout.n_planes; ++p)
         xp[p] = reinterpret_cast<uintptr_t>(xfer) + plan->plane_base[p];
     return kvl::launch_units(plan, false, 0, (uint32_t)plan->units.size(), 0, plan->layout.n_planes,
-                             pool_planes, xp, (hipStream_t)stream);
+                             pool_planes, xp, (hipStream_t)stream, kvl::is_host_memory(plan, xfer));
 }
 
 int kvl_copy_linear(const void *src, void *dst, uint64_t bytes, void *stream) {

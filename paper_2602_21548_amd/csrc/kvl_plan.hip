@@ -111,6 +111,16 @@ int check_buffer(const kvl_plan_t *plan, const void *ptr, uint64_t bytes, bool a
     return kvl_check_buffer(ptr, bytes, allow_host ? 1 : 0);
 }
 
+bool is_host_memory(const kvl_plan_t *plan, const void *ptr) {
+    if (!ptr || (plan->flags & KVL_NO_POINTER_CHECKS)) return false;
+    hipPointerAttribute_t a{};
+    if (hipPointerGetAttributes(&a, ptr) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return a.type == hipMemoryTypeHost;
+}
+
 int upload_units(kvl_plan_t *plan) {
     hipError_t e = hipGetDevice(&plan->device);
     if (e == hipSuccess && !plan->units.empty()) {
@@ -134,7 +144,6 @@ static int resolve_tuning(const kvl_tuning_t *in, kvl_tuning_t *out) {
     if (!valid_block_threads(t.block_threads)) return KVL_EINVAL;
     if (t.variant > kNumVariants) return KVL_EINVAL;
     if (t.unit_bytes > (1u << 30)) t.unit_bytes = 1u << 30;
-    t.reserved = 0;
     *out = t;
     return KVL_OK;
 }
@@ -377,6 +386,7 @@ int kvl_plan_set_tuning(kvl_plan_t *plan, const kvl_tuning_t *tuning) {
     }
     if (tuning->variant > kvl::kNumVariants) return KVL_EINVAL;
     t.variant = tuning->variant;
+    t.max_groups = tuning->max_groups;
     plan->tuning = t;
     return KVL_OK;
 }

@@ -304,7 +304,8 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
                 uintptr_t xp[KVL_MAX_PLANES];
                 for (uint32_t p = 0; p < P; ++p)
                     xp[p] = reinterpret_cast<uintptr_t>(out_host) + oplan->plane_base[p];
-                rc = launch_units(oplan, true, 0, (uint32_t)oplan->units.size(), 0, P, slot_planes, xp, cs);
+                rc = launch_units(oplan, true, 0, (uint32_t)oplan->units.size(), 0, P, slot_planes, xp, cs,
+                                  is_host_memory(oplan, out_host));
                 if (rc != KVL_OK) return rc;
             }
             KVL_HIP(hipEventRecord(out_done[l], cs));

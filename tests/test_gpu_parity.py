@@ -1012,3 +1012,42 @@ def test_stream_layers_with_outflow(S, Ho, out_chunk, in_chunk):
         K.kvl_stream_layers(load, host, slots, staging, 8192, 0, cs, ks, ms, n_layers=L, out_plan=other,
                             out_host_layers=out_host, out_staging=out_staging, out_chunk_bytes=out_chunk)
     assert e.value.code == K.KVL_EINVAL
+
+
+@pytest.mark.parametrize("name,make", [c for c in CASES if c[0] in ("tiny-random", "tiny-3planes", "cfg1", "cfg2-small",
+                                                                      "cfg4-small", "token-granular")],
+                         ids=lambda v: v if isinstance(v, str) else "")
+@pytest.mark.parametrize("groups", [1, 3, 64])
+def test_few_workgroups_walking_over_the_tiles(name, make, groups):
+    """max_groups: the tiled kernels with fewer workgroups than tiles, each walking over several."""
+    w = make()
+    run_hop(w, max_groups=groups)
+    run_hop(w, max_groups=groups, variant=1 + (3 | 4 | 8), block_threads=128)          # two vectors per lane
+    run_range_hop(w, K.KVL_TOKENS_ALL, max_groups=groups, unit_bytes=3000)
+
+
+def test_pinned_buffers_take_the_thin_kernels_by_default():
+    """A transfer buffer or Full-Block buffer in pinned host memory: the kernels that cross the
+    host link run with at most 96 workgroups (more tiles than that here), and say the same."""
+    w = W.config(3, n_requests=12, token_scale=1 / 16)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    src = W.fill_pool(w, 0, "src")
+    want_x = oracle.pack(bs, rows, w.hit, w.src.tables, src)
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    s = dev_plan(w, "dst", K.KVL_SCATTER)
+    assert g.payload_bytes > 96 * 4096 * 4                       # far more tiles than workgroups
+    host = torch.zeros(g.payload_bytes, dtype=torch.uint8).pin_memory()
+    d_src = planes_to_dev(src)
+    torch.cuda.synchronize()
+    K.kvl_pack_layer(g, d_src, host)
+    torch.cuda.synchronize()
+    assert same_bytes(host.numpy(), want_x)
+    want = W.sentinel_pool(w, "dst")
+    oracle.unpack(bs, rows, w.hit, w.dst.tables, want_x, want)
+    for forced in (0, 0xFFFFFFFF):                               # default (thin) and "never walk"
+        s.set_tuning(max_groups=forced)
+        d_dst = planes_to_dev(W.sentinel_pool(w, "dst"))
+        K.kvl_unpack_layer(s, host, d_dst)
+        torch.cuda.synchronize()
+        for a, b in zip(d_dst, want):
+            assert same_bytes(to_host(a), b)
