@@ -122,7 +122,7 @@ typedef struct {
     uint32_t variant;        /* 0: default; 1..256: an explicit kernel variant, see kvl_variant_name */
     uint32_t max_groups;     /* tiled and Full-Block kernels: at most this many workgroups per launch and
                                 plane, each walking over several tiles.  0: one workgroup per tile, except
-                                that a kernel whose far side is host memory is kept to 96 (enough to fill
+                                that a kernel whose far side is host memory is kept to 64 (enough to fill
                                 the host link; the rest of the machine stays free for other kernels);
                                 UINT32_MAX: never walk */
 } kvl_tuning_t;
@@ -224,9 +224,9 @@ int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_byt
  * workgroups (kvl_tuning_t::max_groups), enough to fill the link, so that it does
  * not take the compute units from other kernels.  Which to take: every
  * copy-then-kernel turn of a lane costs on the order of 100 us whatever the chunk's
- * size, so the staged form pays off only for layers of gigabytes on an otherwise
- * idle GPU (2-3 % more of the link); for small layers and beside heavy compute the
- * zero-copy form is the faster one.  The call only enqueues work and joins
+ * size, so the staged form only draws level for layers of gigabytes on an otherwise
+ * idle GPU; for small layers and beside heavy compute the zero-copy form is the
+ * faster one.  The call only enqueues work and joins
  * its lanes by events, so it can be captured in a HIP graph (pass the capturing
  * stream for both stream arguments, after one eager call has made the lanes). */
 int kvl_h2d_unpack_layer(const kvl_plan_t *plan, const void *pinned_host_xfer,

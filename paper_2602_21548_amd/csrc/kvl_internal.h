@@ -49,7 +49,7 @@ void set_hip_error(hipError_t e);
 
 constexpr uint32_t kDefaultUnitBytes = 128u << 10;
 constexpr uint32_t kDefaultBlockThreads = 256;
-constexpr uint32_t kHostSideGroups = 96;    // workgroups of a kernel whose far side is host memory (see kvl_tile_walk_kernel)
+constexpr uint32_t kHostSideGroups = 64;    // workgroups of a kernel whose far side is host memory (see kvl_tile_walk_kernel)
 constexpr uint32_t kNumVariants = 256;       // explicit variants are 1 .. kNumVariants
 bool valid_block_threads(uint32_t t);
 

@@ -136,6 +136,9 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
             rows_128 = rows_128 && plan->layout.row_bytes[p] % 128 == 0;
         if (pack) v = kDefaultPackCode;
         else v = rows_128 ? kDefaultUnpackCode : kDefaultUnpackCodeOddRows;
+        // across the host link: two vectors per lane, so that the few workgroups of the thin
+        // form (kHostSideGroups) keep enough bytes in flight
+        if (far_host) v |= 3u;
     }
     dim3 block(threads);
     uint32_t widest = 0;        // vectors of the largest descriptor, over the planes of this launch
@@ -233,7 +236,9 @@ int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint6
     const uint64_t tpu = ((uint64_t)plan->max_unit_rows * max_row + threads - 1) / threads;
     const uint64_t wgs = (uint64_t)a.n_units * tpu;
     if (tpu == 0 || wgs > (uint64_t)INT32_MAX) return KVL_ERANGE;
-    const uint32_t cap = plan->tuning.max_groups ? plan->tuning.max_groups : (far_host ? kHostSideGroups : 0u);
+    // one vector per lane here, so half as many again as the two-vector copy kernels get (measured, host
+    // buffer / beside a busy GPU: 64 workgroups 50 GB/s; 96: 54.3 GB/s, computation + 3 %; 128: 56.0, + 14 %)
+    const uint32_t cap = plan->tuning.max_groups ? plan->tuning.max_groups : (far_host ? kHostSideGroups * 3 / 2 : 0u);
     const uint32_t n_tiles = (uint32_t)wgs;
     dim3 grid((cap && wgs > cap) ? cap : (uint32_t)wgs, P), block(threads);
     if (to_pool) {

@@ -1028,14 +1028,14 @@ def test_few_workgroups_walking_over_the_tiles(name, make, groups):
 
 def test_pinned_buffers_take_the_thin_kernels_by_default():
     """A transfer buffer or Full-Block buffer in pinned host memory: the kernels that cross the
-    host link run with at most 96 workgroups (more tiles than that here), and say the same."""
+    host link run with at most 64 workgroups (more tiles than that here), and say the same."""
     w = W.config(3, n_requests=12, token_scale=1 / 16)
     bs, rows = w.layout.block_tokens, w.layout.row_bytes
     src = W.fill_pool(w, 0, "src")
     want_x = oracle.pack(bs, rows, w.hit, w.src.tables, src)
     g = dev_plan(w, "src", K.KVL_GATHER)
     s = dev_plan(w, "dst", K.KVL_SCATTER)
-    assert g.payload_bytes > 96 * 4096 * 4                       # far more tiles than workgroups
+    assert g.payload_bytes > 64 * 8192 * 4                       # far more tiles than workgroups
     host = torch.zeros(g.payload_bytes, dtype=torch.uint8).pin_memory()
     d_src = planes_to_dev(src)
     torch.cuda.synchronize()
