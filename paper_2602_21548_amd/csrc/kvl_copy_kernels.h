@@ -274,7 +274,9 @@ struct FullBlockArgs {
     uint64_t layer_plane_off[KVL_MAX_PLANES];  // element offset of (layer, plane) inside a Full Block
 };
 
-template <bool TO_POOL, bool VEC>
+// A tile is VPT * blockDim elements of a descriptor; lane t takes elements t, t + blockDim, ...
+// of it, all loads before the first store.
+template <bool TO_POOL, bool VEC, int VPT>
 __device__ __forceinline__ void fullblock_tile(const FullBlockArgs &a, uint32_t tiles_per_unit, uint32_t tile_index) {
     const uint32_t u_idx = tile_index / tiles_per_unit;
     const uint32_t tile = tile_index - u_idx * tiles_per_unit;
@@ -282,28 +284,46 @@ __device__ __forceinline__ void fullblock_tile(const FullBlockArgs &a, uint32_t 
     const uint32_t p = blockIdx.y;
     const uint32_t row = a.row_elems[p];
     const uint32_t n = u.n_rows * row;
-    const uint32_t i = tile * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+    const uint32_t first = tile * (blockDim.x * VPT) + threadIdx.x;
+    if (first >= n) return;
     const uint32_t within = u.pool_row % a.block_tokens;
-    const uint64_t in_pool = (uint64_t)u.pool_row * row + i;
-    const uint64_t in_blocks = (uint64_t)u.block_index * a.fb_elems + a.layer_plane_off[p] +
-                               (uint64_t)within * row + i;
+    const uint64_t in_pool = (uint64_t)u.pool_row * row;
+    const uint64_t in_blocks = (uint64_t)u.block_index * a.fb_elems + a.layer_plane_off[p] + (uint64_t)within * row;
     if (VEC) {
-        if (TO_POOL) store16<3>((gdst_t)a.pool[p] + in_pool, load16<false>((gsrc_t)a.blocks + in_blocks));
-        else store16<0>((gdst_t)a.blocks + in_blocks, load16<true>((gsrc_t)a.pool[p] + in_pool));
+        gsrc_t src = TO_POOL ? (gsrc_t)a.blocks + in_blocks : (gsrc_t)a.pool[p] + in_pool;
+        gdst_t dst = TO_POOL ? (gdst_t)a.pool[p] + in_pool : (gdst_t)a.blocks + in_blocks;
+        v4u v[VPT];
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const uint32_t i = first + k * blockDim.x;
+            if (i < n) v[k] = TO_POOL ? load16<false>(src + i) : load16<true>(src + i);
+        }
+#pragma unroll
+        for (int k = 0; k < VPT; ++k) {
+            const uint32_t i = first + k * blockDim.x;
+            if (i < n) {
+                if (TO_POOL) store16<3>(dst + i, v[k]);
+                else store16<0>(dst + i, v[k]);
+            }
+        }
     } else {
-        uint8_t *pool = reinterpret_cast<uint8_t *>(a.pool[p]);
-        uint8_t *blocks = reinterpret_cast<uint8_t *>(a.blocks);
-        if (TO_POOL) pool[in_pool] = blocks[in_blocks];
-        else blocks[in_blocks] = pool[in_pool];
+        uint8_t *pool = reinterpret_cast<uint8_t *>(a.pool[p]) + in_pool;
+        uint8_t *blocks = reinterpret_cast<uint8_t *>(a.blocks) + in_blocks;
+        for (int k = 0; k < VPT; ++k) {
+            const uint32_t i = first + k * blockDim.x;
+            if (i >= n) break;
+            if (TO_POOL) pool[i] = blocks[i];
+            else blocks[i] = pool[i];
+        }
     }
 }
 
 // gridDim.x workgroups walk over the n_tiles tiles (one tile each when there are as many).
-template <bool TO_POOL, bool VEC>
+template <bool TO_POOL, bool VEC, int VPT>
 __global__ void __launch_bounds__(256) kvl_fullblock_kernel(const FullBlockArgs a, uint32_t tiles_per_unit,
                                                             uint32_t n_tiles) {
-    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) fullblock_tile<TO_POOL, VEC>(a, tiles_per_unit, t);
+    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x)
+        fullblock_tile<TO_POOL, VEC, VPT>(a, tiles_per_unit, t);
 }
 
 // Straight copy, one vector per lane: the tiled kernel without descriptors.

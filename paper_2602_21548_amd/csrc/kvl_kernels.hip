@@ -233,21 +233,25 @@ int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint6
         max_row = std::max(max_row, a.row_elems[p]);
     }
     const uint32_t threads = 256;
-    const uint64_t tpu = ((uint64_t)plan->max_unit_rows * max_row + threads - 1) / threads;
+    // across the host link: two elements per lane on few workgroups (as the copy kernels do, see launch_units)
+    const uint32_t vpt = far_host ? 2 : 1;
+    const uint64_t per_tile = (uint64_t)threads * vpt;
+    const uint64_t tpu = ((uint64_t)plan->max_unit_rows * max_row + per_tile - 1) / per_tile;
     const uint64_t wgs = (uint64_t)a.n_units * tpu;
     if (tpu == 0 || wgs > (uint64_t)INT32_MAX) return KVL_ERANGE;
-    // one vector per lane here, so half as many again as the two-vector copy kernels get (measured, host
-    // buffer / beside a busy GPU: 64 workgroups 50 GB/s; 96: 54.3 GB/s, computation + 3 %; 128: 56.0, + 14 %)
-    const uint32_t cap = plan->tuning.max_groups ? plan->tuning.max_groups : (far_host ? kHostSideGroups * 3 / 2 : 0u);
+    const uint32_t cap = plan->tuning.max_groups ? plan->tuning.max_groups : (far_host ? kHostSideGroups : 0u);
     const uint32_t n_tiles = (uint32_t)wgs;
     dim3 grid((cap && wgs > cap) ? cap : (uint32_t)wgs, P), block(threads);
+#define KVL_FB_LAUNCH(TP, VE, VP) \
+    hipLaunchKernelGGL((kvl_fullblock_kernel<TP, VE, VP>), grid, block, 0, stream, a, (uint32_t)tpu, n_tiles)
     if (to_pool) {
-        if (vec) hipLaunchKernelGGL((kvl_fullblock_kernel<true, true>), grid, block, 0, stream, a, (uint32_t)tpu, n_tiles);
-        else hipLaunchKernelGGL((kvl_fullblock_kernel<true, false>), grid, block, 0, stream, a, (uint32_t)tpu, n_tiles);
+        if (vec) { if (vpt == 2) KVL_FB_LAUNCH(true, true, 2); else KVL_FB_LAUNCH(true, true, 1); }
+        else { if (vpt == 2) KVL_FB_LAUNCH(true, false, 2); else KVL_FB_LAUNCH(true, false, 1); }
     } else {
-        if (vec) hipLaunchKernelGGL((kvl_fullblock_kernel<false, true>), grid, block, 0, stream, a, (uint32_t)tpu, n_tiles);
-        else hipLaunchKernelGGL((kvl_fullblock_kernel<false, false>), grid, block, 0, stream, a, (uint32_t)tpu, n_tiles);
+        if (vec) { if (vpt == 2) KVL_FB_LAUNCH(false, true, 2); else KVL_FB_LAUNCH(false, true, 1); }
+        else { if (vpt == 2) KVL_FB_LAUNCH(false, false, 2); else KVL_FB_LAUNCH(false, false, 1); }
     }
+#undef KVL_FB_LAUNCH
     KVL_HIP(hipGetLastError());
     return KVL_OK;
 }
