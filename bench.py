@@ -743,7 +743,7 @@ def full_block_leg(pinned: "torch.Tensor", h2d_peak: float) -> dict:
             best = max(best, per_layer * L / (e0.elapsed_time(e1) * 1e-3) / 1e9)
         out[f"{name}_gbps"] = round(best, 2)
     out["h2d_frac_of_link"] = round(out["h2d_gbps"] / h2d_peak, 4)
-    # the same load staged by the copy engine (strided copies into 2 slots of 64 MiB, converting kernels there)
+    # the same load staged (the runtime's strided copies into 2 slots of 64 MiB, converting kernels there)
     chunk = 64 << 20
     staging = torch.empty(2 * chunk, dtype=torch.uint8, device=dev)
     cs = torch.cuda.Stream()

@@ -270,21 +270,21 @@ int kvl_fullblocks_to_pool_layer(const kvl_plan_t *plan, const void *full_blocks
  * belong to other layers or to rows outside the ranges are left as they are */
 int kvl_pool_to_fullblocks_layer(const kvl_plan_t *plan, const void *const *pool_planes, uint32_t layer,
                                  void *full_blocks, uint64_t full_blocks_bytes, void *stream);
-/* Staged form of kvl_fullblocks_to_pool_layer for a buffer the copy engine should
- * read (pinned host memory above all): layer `layer` of the blocks is brought into
- * the slots of dev_staging by strided copies (hipMemcpy2DAsync: per chunk of
- * floor(chunk_bytes / LB) blocks, rows of LB bytes at a pitch of FB) and converted
- * into the pool from there by a kernel per chunk, on the library's lanes and with
- * the stream semantics of kvl_h2d_unpack_layer.  No wavefront waits on the host
- * link, so the load does not hold compute units that other kernels need.
+/* Staged form of kvl_fullblocks_to_pool_layer: layer `layer` of the blocks is
+ * brought into the slots of dev_staging by the runtime's strided copies
+ * (hipMemcpy2DAsync: per chunk of floor(chunk_bytes / LB) blocks, rows of LB bytes
+ * at a pitch of FB) and converted into the pool from there by a kernel per chunk,
+ * on the library's lanes and with the stream semantics of kvl_h2d_unpack_layer.
+ * How the copies cross the link is the runtime's business (on the machine this was
+ * written on it uses a copy kernel of its own for them).
  * KVL_ESPACE also if chunk_bytes < LB or staging_bytes < chunk_bytes. */
 int kvl_h2d_fullblocks_layer(const kvl_plan_t *plan, const void *full_blocks, uint64_t full_blocks_bytes,
                              uint32_t layer, void *dev_staging, uint64_t staging_bytes, uint64_t chunk_bytes,
                              void *const *pool_planes, void *copy_stream, void *kernel_stream);
 
-/* Staged form of kvl_pool_to_fullblocks_layer (persisting a layer beside a busy
- * GPU): a kernel per chunk of blocks lays the rows out as Layer Blocks in a staging
- * slot, and the copy engine writes them into the buffer: runs of wholly covered
+/* Staged form of kvl_pool_to_fullblocks_layer: a kernel per chunk of blocks lays
+ * the rows out as Layer Blocks in a staging slot, and copies of the runtime
+ * (hipMemcpy2DAsync, hipMemcpyAsync) write them into the buffer: runs of wholly covered
  * blocks with one strided copy each, the rows of a partly covered block (the ends
  * of a request's range) with one copy per plane.  As with the one-kernel form no
  * byte outside the plan's rows is written.  Streams, slots and errors as in

@@ -411,7 +411,7 @@ def kvl_fullblocks_to_pool_layer(plan: Plan, full_blocks: torch.Tensor, layer: i
 def kvl_d2h_fullblocks_layer(plan: Plan, pool_planes: Sequence[torch.Tensor], layer: int,
                              dev_staging: torch.Tensor, chunk_bytes: int, full_blocks: torch.Tensor,
                              kernel_stream, copy_stream) -> None:
-    """Staged persist of one layer: converting kernels into dev_staging, copy engine into the Full Blocks."""
+    """Staged persist of one layer: converting kernels into dev_staging, runtime copies into the Full Blocks."""
     arr = _plane_ptrs(plan, pool_planes, "kvl_d2h_fullblocks_layer pool")
     _check(_lib.kvl_d2h_fullblocks_layer(plan.handle, arr, layer, _dev(dev_staging, "staging"),
                                          _nbytes(dev_staging), chunk_bytes,

@@ -1,7 +1,7 @@
 // Host-buffer paths.  Load: pinned host transfer buffer -> staging slots in HBM
 // (hipMemcpyAsync) -> scatter kernel per landed chunk.  The way out mirrors it
 // (gather kernel into a slot -> hipMemcpyAsync to the host buffer), and both have
-// a form for the storage layout, in which the copy engine moves whole Layer
+// a form for the storage layout, in which strided copies of the runtime move whole Layer
 // Blocks with strided copies and a kernel converts them in HBM.
 //
 // The paper notes that handing many small copies to a copy engine is bound by
@@ -287,7 +287,7 @@ static int d2h_pack_layer(const kvl_plan_t *plan_c, const void *const *pool_plan
 
 // Persist direction: one layer of the pool into a buffer of Full Blocks through the
 // staging slots.  The kernel lays the blocks' rows out as Layer Blocks in a slot; the
-// copy engine then writes runs of whole blocks with one strided copy each, and the
+// runtime's copies then write runs of whole blocks with one strided copy each, and the
 // rows of partly covered blocks (the ends of a request's range) with one plain copy
 // per plane, so that no byte outside the plan's rows is written.
 static int d2h_fullblocks_layer(const kvl_plan_t *plan_c, const void *const *pool_planes, uint32_t layer,

@@ -89,7 +89,7 @@ static int stream_layers(const kvl_plan_t *plan_c, const kvl_stream_cfg_t *cfg, 
         if (L > plan->layout.n_layers) return KVL_EINVAL;
         rc = check_fullblock_args(plan, true, cfg->full_blocks_bytes, L - 1);
         if (rc != KVL_OK) return rc;
-        if (cfg->chunk_bytes) {         // staged form: the copy engine brings the Layer Blocks in
+        if (cfg->chunk_bytes) {         // staged form: strided copies bring the Layer Blocks in
             rc = check_fullblock_staging(plan, cfg->dev_staging, cfg->staging_bytes, cfg->chunk_bytes, &slots);
             if (rc != KVL_OK) return rc;
         }

@@ -362,7 +362,7 @@ def test_full_block_layout(name, make, where, flag):
     st.synchronize()
     got_buf = to_host(buf) if where == "device" else buf.numpy()
     assert same_bytes(got_buf, want_buf), "Full-Block buffer differs from the oracle"
-    # the same persist staged through HBM (kernel into a slot, copy engine out), 2 Layer Blocks per chunk
+    # the same persist staged through HBM (kernel into a slot, runtime copies out), 2 Layer Blocks per chunk
     if fb * nfb:
         buf2 = torch.full((nbytes + 64,), 0x5A, dtype=torch.uint8, device="cuda") if where == "device" else \
             torch.full((nbytes + 64,), 0x5A, dtype=torch.uint8).pin_memory()
@@ -385,7 +385,7 @@ def test_full_block_layout(name, make, where, flag):
         st.synchronize()
         for a, b in zip(got, want):
             assert same_bytes(to_host(a), b), f"layer {l} loaded from Full Blocks differs from the oracle"
-        # the same load staged through HBM by the copy engine: 1 or 3 Layer Blocks per chunk, 1 or 2 slots
+        # the same load staged through HBM by strided copies: 1 or 3 Layer Blocks per chunk, 1 or 2 slots
         lb = fb // L
         for blocks_per_chunk, n_slots in ((1, 1), (3, 2)):
             chunk = -(-blocks_per_chunk * lb // 16) * 16
@@ -514,7 +514,7 @@ def test_stream_layers_from_full_blocks(S, where):
     buf = to_dev(blocks) if where == "device" else pinned_from(blocks)
     slots = [planes_to_dev(W.sentinel_pool(w, "dst", 0xEE)) for _ in range(S)]
     snaps = [[torch.zeros_like(pl) for pl in slots[0]] for _ in range(L)]
-    # staged: the copy engine brings 5 Layer Blocks at a time into each of 3 staging slots
+    # staged: strided copies bring 5 Layer Blocks at a time into each of 3 staging slots
     chunk = 5 * (fb // L) if where == "pinned-staged" else 0
     staging = torch.zeros(3 * chunk, dtype=torch.uint8, device="cuda") if chunk else None
     torch.cuda.synchronize()
