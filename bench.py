@@ -470,6 +470,22 @@ def short_hop(index: int, reps: int = 8, check: bool = True) -> dict:
            "unpack_frac_of_hbm_peak": round(2 * payload / um / 1e6 / HBM_PEAK_GBPS, 4),
            "tokens_layers_per_s": round(T / ((pm + um) * 1e-3), 1), "verified_rows_vs_oracle": verified,
            "plan_ms": round(plan_ms, 3), "descriptors": g.n_units}
+    # pool to pool in one kernel (paired plan), after the hop above has been checked
+    m = K.kvl_plan_pair(g, s)
+    mv = []
+    for i in range(reps + 2):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        K.kvl_move_layer(m, src, dst, stream=stream)
+        e1.record(stream)
+        e1.synchronize()
+        if i >= 2:
+            mv.append(e0.elapsed_time(e1))
+    m.destroy()
+    mm = float(np.mean(mv))
+    out["move_ms"] = round(mm, 4)
+    out["move_delivered_gbps"] = round(payload / mm / 1e6, 1)
+    out["move_frac_of_hbm_peak"] = round(2 * payload / mm / 1e6 / HBM_PEAK_GBPS, 4)
     if payload < (64 << 20):
         out["note"] = "launch- and cache-bound: the payload fits the on-die cache and a launch costs more than the copy"
         # in this regime the host's launch cost is what a HIP graph removes: capture a run of

@@ -195,6 +195,8 @@ int kvl_pack_layer(const kvl_plan_t *plan, const void *const *pool_planes,
  * of pack followed by unpack, with half the memory traffic.  The two pools must
  * not overlap.  The paired plan is independent of the two it was made from. */
 int kvl_plan_pair(const kvl_plan_t *gather, const kvl_plan_t *scatter, kvl_plan_t **out);
+/* (A paired plan keeps its descriptors in the order of their destination rows, so that the
+ * writes of a move run forward through the destination pool.) */
 int kvl_move_layer(const kvl_plan_t *paired, const void *const *src_pool_planes,
                    void *const *dst_pool_planes, void *stream);
 

