@@ -401,3 +401,31 @@ def test_pairing_refuses_mismatched_plans():
     m = K.kvl_plan_pair(g, s)
     with pytest.raises(K.KvlError):
         K.kvl_plan_pair(m, s)                                          # a paired plan is not a gather plan
+
+
+def test_piece_size_follows_the_batch_not_the_rare_adjacent_pair():
+    """Descriptors of one launch get the same number of tiles (that of the largest), so a few
+    merged runs among single blocks must not set the size: the plan then keeps one descriptor per
+    block; a batch whose blocks are all contiguous is still merged into large pieces; and blocks
+    a little larger than unit_bytes are halved evenly, merged or not."""
+    bs, row = 64, 1024                                     # 64 KiB blocks, two fit the 128 KiB default
+    rng = np.random.Generator(np.random.PCG64(77))
+    R, per = 8, 40
+    perm = rng.permutation(4096)[:R * per].astype(np.int32)
+    tables = [np.sort(perm[r * per:(r + 1) * per])[::-1].copy() for r in range(R)]    # descending: never adjacent upwards
+    tables[3][10], tables[3][11] = 5000, 5001             # one adjacent pair
+    hit = np.full(R, per * bs, dtype=np.uint32)
+    app = np.zeros(R, dtype=np.uint32)
+    lay = K.make_layout(1, bs, (row,), 8192)
+    p = K.kvl_plan(lay, hit, app, tables, K.KVL_GATHER | K.KVL_HOST_ONLY)
+    u = p.units()
+    assert u[:, 2].max() == bs and p.n_units == R * per, "the merged pair must be split back into blocks"
+    # all contiguous: pieces of 128 rows (128 KiB), not of 64
+    cont = [np.arange(r * per, (r + 1) * per, dtype=np.int32) for r in range(R)]
+    p = K.kvl_plan(lay, hit, app, cont, K.KVL_GATHER | K.KVL_HOST_ONLY)
+    assert p.units()[:, 2].max() == 128 and p.n_units == R * per // 2
+    # 129 KiB blocks against the 128 KiB limit: halves of 32 rows everywhere, also in the merged pair
+    lay2 = K.make_layout(1, bs, (2064,), 8192)
+    p = K.kvl_plan(lay2, hit, app, tables, K.KVL_GATHER | K.KVL_HOST_ONLY)
+    u = p.units()
+    assert set(np.unique(u[:, 2]).tolist()) == {32} and p.n_units == 2 * R * per
