@@ -21,6 +21,7 @@ struct kvl_plan_s {
     uint64_t blocks_touched = 0;                 // Full Blocks a buffer of this plan's ranges holds
     bool vec16 = false;                          // every row size is a multiple of 16 bytes
     std::vector<kvl_unit_t> units;               // host copy of the descriptors
+    bool threads_chosen = false;                 // the caller named block_threads (else the launcher may halve the default)
     std::vector<uint32_t> block_first_unit;      // KVL_NO_MERGE plans, made on demand: first descriptor of each block
     std::vector<uint32_t> block_row_lo, block_row_hi;   // with it: rows [lo, hi) of each block that the plan moves
     kvl_unit_t *d_units = nullptr;               // device copy (absent for KVL_HOST_ONLY)

@@ -139,7 +139,7 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
     for (uint32_t p = plane_begin; p < plane_end; ++p)
         a.row_elems[p] = vec ? plan->layout.row_bytes[p] / 16 : plan->layout.row_bytes[p];
 
-    const uint32_t threads = plan->tuning.block_threads;
+    uint32_t threads = plan->tuning.block_threads;
     // default: tiled, one vector per lane; cache policies as measured (see the top of kvl_copy_kernels.h)
     uint32_t v;
     if (plan->tuning.variant) {
@@ -154,12 +154,22 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
         // form (kHostSideGroups) keep enough bytes in flight
         if (far_host) v |= 3u;
     }
-    dim3 block(threads);
     uint32_t widest = 0;        // vectors of the largest descriptor, over the planes of this launch
     for (uint32_t p = plane_begin; p < plane_end; ++p) widest = std::max(widest, a.row_elems[p]);
     const uint64_t unit_vecs = (uint64_t)plan->max_unit_rows * widest;
+    // Descriptors that fill their last tile badly: with the default workgroup size, halve it where that
+    // leaves clearly fewer lanes without work (32-token blocks of 656-byte rows are 5.1 tiles of 256 lanes:
+    // 5.1 TB/s; 10.3 tiles of 128 lanes: 5.8).
+    if (vec && !plan->threads_chosen && !plan->tuning.variant && threads == kDefaultBlockThreads) {
+        auto idle = [&](uint64_t t) { return 1.0 - (double)unit_vecs / (double)((unit_vecs + t - 1) / t * t); };
+        if (idle(threads) - idle(threads / 2) > 0.07) threads /= 2;
+    }
     // descriptors that fill less than half a workgroup: deal the lanes out without tiles
-    if (vec && !plan->tuning.variant && unit_vecs * 2 <= threads) v = pack ? kFlatPackCode : kFlatUnpackCode;
+    if (vec && !plan->tuning.variant && unit_vecs * 2 <= plan->tuning.block_threads) {
+        v = pack ? kFlatPackCode : kFlatUnpackCode;
+        threads = plan->tuning.block_threads;
+    }
+    dim3 block(threads);
     if (!vec) {
         dim3 grid(a.n_units, plane_end - plane_begin);
         if (pack) hipLaunchKernelGGL(kvl_bytes_kernel<true>, grid, block, 0, stream, a);

@@ -179,6 +179,7 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
     plan->vec16 = vec16;
     int rc = resolve_tuning(tuning, &plan->tuning);
     if (rc != KVL_OK) { delete plan; return rc; }
+    plan->threads_chosen = tuning && tuning->block_threads != 0;
 
     const uint64_t max_rows = std::max<uint64_t>(1, plan->tuning.unit_bytes / max_row);
     const bool scatter = (flags & KVL_SCATTER) != 0;
@@ -407,6 +408,7 @@ int kvl_plan_pair(const kvl_plan_t *g, const kvl_plan_t *s, kvl_plan_t **out) {
     plan->payload_bytes = g->payload_bytes;
     plan->vec16 = g->vec16;
     plan->tuning = g->tuning;
+    plan->threads_chosen = g->threads_chosen;
     try {
         // both descriptor lists tile the token rows [0, T) in order: walk them together
         size_t i = 0, j = 0;
@@ -451,6 +453,7 @@ int kvl_plan_set_tuning(kvl_plan_t *plan, const kvl_tuning_t *tuning) {
     if (tuning->block_threads) {
         if (!kvl::valid_block_threads(tuning->block_threads)) return KVL_EINVAL;
         t.block_threads = tuning->block_threads;
+        plan->threads_chosen = true;
     }
     if (tuning->variant > kvl::kNumVariants) return KVL_EINVAL;
     t.variant = tuning->variant;
