@@ -117,7 +117,9 @@ typedef struct {
 
 /* Optional tuning; a zero field means "library default". */
 typedef struct {
-    uint32_t unit_bytes;     /* target bytes of one descriptor (runs are split evenly to stay at or below it) */
+    uint32_t unit_bytes;     /* upper limit for the bytes of one descriptor: runs are split evenly into pieces at or
+                                below it; the plan picks one piece size for the whole batch (block_tokens * 2^j or
+                                this limit) so that its descriptors are alike */
     uint32_t block_threads;  /* threads per workgroup: 64, 128, 256, 512 or 1024 */
     uint32_t variant;        /* 0: default; 1..256: an explicit kernel variant, see kvl_variant_name */
     uint32_t max_groups;     /* tiled and Full-Block kernels: at most this many workgroups per launch and
