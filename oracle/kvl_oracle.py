@@ -2,6 +2,15 @@
 
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import
 this.  It never touches the HIP library and the HIP library never touches it.
+
+The C file holds the definitions; this file adds only the per-layer compositions
+(stream_layers, stream_layers_fullblocks) and the sharding of requests over host
+threads.  Pins (tests/test_oracle_pins.py): both compositions are checked against
+per-layer tags, with expected slot contents written out from the layout's defining
+sentence (Appendix A.5) by NumPy reshapes, for several numbers of resident slots and
+host buffers, and against each other on ragged ranges; mistakes planted in copies of
+this file (wrong slot, wrong layer, H and S swapped, a lost request in the sharding)
+must each trip a pin.
 """
 from __future__ import annotations
 

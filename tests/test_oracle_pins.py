@@ -381,7 +381,107 @@ def pin_full_blocks():
                     assert u.tobytes() == v.tobytes(), kw
 
 
-PINS = [pin_full_blocks, pin_ranges, pin_brute_force, pin_exhaustive_permutations, pin_round_trip, pin_byte_conservation,
+def pin_stream_layers():
+    """Layer-wise load from dense host buffers (Section 4.1): layer l comes from host buffer
+    l mod H and is what slot l mod S holds when layer l is computed, whatever S and H are.
+    Every payload byte carries its layer's tag; H, S and L are pairwise different where it matters."""
+    L = 5
+    w = W.tiny(seed=41, n_requests=4, block_tokens=8, row_bytes=(32,), pool_blocks=48, max_tokens=50, n_layers=L)
+    n = oracle.payload_bytes(w.hit, w.layout.row_bytes)
+    layers = [np.full(n, 0x10 + l, dtype=np.uint8) for l in range(L)]   # layer tag in every byte
+    mask = brute_hit_mask(8, 32, w.hit, w.dst.tables, w.dst.pool_blocks)
+    for S, H in ((1, 2), (2, 2), (5, 2), (2, 3), (3, 1)):
+        # host slot h is refilled with layer l's payload just before layer l is loaded
+        host = [np.zeros(n, np.uint8) for _ in range(H)]
+        slots = [W.sentinel_pool(w, "dst", 0xEE) for _ in range(S)]
+        seen = 0
+        gen = oracle.stream_layers(8, w.layout.row_bytes, w.hit, w.dst.tables, host, L, slots)
+        host[0][:] = layers[0]
+        for l in range(L):
+            ll, s, planes = next(gen)
+            assert (ll, s) == (l, l % S)
+            assert planes[0] is slots[l % S][0]
+            assert np.all(planes[0][mask] == 0x10 + l)       # the layer being computed is the one resident
+            assert np.all(planes[0][~mask] == 0xEE)
+            for k in range(S):                                # the other slots hold the layers loaded before
+                if k != l % S:
+                    older = [m for m in range(l) if m % S == k]
+                    want = 0x10 + older[-1] if older else 0xEE
+                    assert np.all(slots[k][0][mask] == want), (S, H, l, k)
+            if l + 1 < L:
+                host[(l + 1) % H][:] = layers[l + 1]
+            seen += 1
+        assert seen == L
+        assert next(gen, None) is None
+
+
+def pin_stream_fullblocks():
+    """Layer-wise load with the storage layout as its source (Appendix A.5: a Full Block is the
+    concatenation of a block's Layer Blocks; Section 4.1: layer l's cache is resident when layer l
+    is computed).  Expected slot contents are written out with NumPy reshapes of that sentence on
+    whole blocks whose bytes carry (block, layer) tags; ragged ranges are checked against the
+    dense path (store into Full Blocks, then stream the dense layers)."""
+    # (1) whole blocks, two planes, tags: byte (f, l, *) of the buffer is 1 + f * L + l
+    bs, rows, L, nblk = 4, (16, 32), 4, 10
+    lb = bs * sum(rows)
+    tabs = [np.array([7, 2, 9], np.int32), np.array([0, 5], np.int32)]
+    count = [3 * bs, 2 * bs]
+    flat = np.concatenate(tabs)
+    nfb = flat.size
+    f_idx, l_idx = np.meshgrid(np.arange(nfb), np.arange(L), indexing="ij")
+    tags = (1 + f_idx * L + l_idx).astype(np.uint8)
+    blocks = np.repeat(tags.reshape(nfb, L, 1), lb, axis=2)
+    # make the bytes inside a Layer Block distinct as well (plane span, row), keeping the tag in the high bits
+    inner = (np.arange(lb) % 5).astype(np.uint8)
+    blocks = (blocks * np.uint8(5) + inner[None, None, :]).astype(np.uint8)
+    buf = np.ascontiguousarray(blocks.reshape(-1))
+    for S in (1, 2, 3, L):
+        for run in (0, 3):
+            slots = [[np.full(nblk * bs * r, 0xEE, np.uint8) for r in rows] for _ in range(S)]
+            seen = []
+            for l, s, planes in oracle.stream_layers_fullblocks(bs, L, rows, None, count, tabs, buf, slots, run_layers=run):
+                assert s == l % S and all(a is b for a, b in zip(planes, slots[s]))
+                seen.append(l)
+                for k in range(S):
+                    older = [m for m in range(l + 1) if m % S == k]
+                    off = 0
+                    for p, row in enumerate(rows):
+                        want = np.full((nblk, bs * row), 0xEE, np.uint8)
+                        if older:
+                            # plane p's span of layer older[-1]'s Layer Block of every block, block by block
+                            want[flat] = blocks[:, older[-1], off:off + bs * row]
+                        assert slots[k][p].tobytes() == want.tobytes(), (S, run, l, k, p)
+                        off += bs * row
+            assert seen == list(range(run or L)), (S, run)
+    # (2) ragged ranges and every kind of table: the same observables as the dense path
+    for kw in TINY:
+        L = 3
+        w = W.tiny(**dict(kw, n_layers=L))
+        bs, rows = w.layout.block_tokens, w.layout.row_bytes
+        for first, count in ((np.zeros_like(w.hit), w.hit), (w.hit, w.app)):
+            nfb = oracle.fullblock_count(bs, first, count)
+            fb = oracle.fullblock_bytes(bs, L, rows)
+            pools = [W.fill_pool(w, l, "src") for l in range(L)]
+            buf = np.full(nfb * fb, 0x33, np.uint8)
+            dense = []
+            for l in range(L):
+                oracle.pool_to_fullblocks(bs, L, rows, first, count, w.src.tables, l, pools[l], buf)
+                dense.append(oracle.pack_range(bs, rows, first, count, w.src.tables, pools[l]))
+            for S in (1, 2, L):
+                a = [W.sentinel_pool(w, "dst") for _ in range(S)]
+                b = [W.sentinel_pool(w, "dst") for _ in range(S)]
+                n = 0
+                for l, s, planes in oracle.stream_layers_fullblocks(bs, L, rows, first, count, w.dst.tables, buf, a):
+                    oracle.unpack_range(bs, rows, first, count, w.dst.tables, dense[l], b[l % S])
+                    assert s == l % S
+                    for k in range(S):
+                        for u, v in zip(a[k], b[k]):
+                            assert u.tobytes() == v.tobytes(), (kw, S, l, k)
+                    n += 1
+                assert n == L
+
+
+PINS = [pin_stream_fullblocks, pin_stream_layers, pin_full_blocks, pin_ranges, pin_brute_force, pin_exhaustive_permutations, pin_round_trip, pin_byte_conservation,
         pin_memcpy_and_take, pin_permutation_algebra, pin_closed_form_fill, pin_threads_agree]
 
 
@@ -425,28 +525,21 @@ def test_empty_batch_and_zero_hits():
 # layer-wise streaming: same observables for any number of resident slots
 # --------------------------------------------------------------------------
 
-@pytest.mark.parametrize("S", [1, 2, 5])
-def test_stream_layers_observables(S):
-    L, H = 5, 2
-    w = W.tiny(seed=41, n_requests=4, block_tokens=8, row_bytes=(32,), pool_blocks=48, max_tokens=50, n_layers=L)
-    n = oracle.payload_bytes(w.hit, w.layout.row_bytes)
-    layers = [np.full(n, 0x10 + l, dtype=np.uint8) for l in range(L)]   # layer tag in every byte
-    mask = brute_hit_mask(8, 32, w.hit, w.dst.tables, w.dst.pool_blocks)
-    # host slot h is refilled with layer l's payload just before layer l is loaded
-    host = [np.zeros(n, np.uint8) for _ in range(H)]
-    slots = [W.sentinel_pool(w, "dst", 0xEE) for _ in range(S)]
-    seen = 0
-    gen = oracle.stream_layers(8, w.layout.row_bytes, w.hit, w.dst.tables, host, L, slots)
-    host[0][:] = layers[0]
-    for l in range(L):
-        ll, s, planes = next(gen)
-        assert (ll, s) == (l, l % S)
-        assert np.all(planes[0][mask] == 0x10 + l)       # the layer being computed is the one resident
-        assert np.all(planes[0][~mask] == 0xEE)
-        if l + 1 < L:
-            host[(l + 1) % H][:] = layers[l + 1]
-        seen += 1
-    assert seen == L
+def test_stream_layers_run_layers_beyond_buffer():
+    """run_layers only shortens the run: the layers it does load are those of the full run."""
+    w = W.tiny(seed=43, n_requests=2, block_tokens=4, row_bytes=(16,), pool_blocks=16, max_tokens=20, n_layers=4)
+    bs, rows, L = 4, (16,), 4
+    nfb = oracle.fullblock_count(bs, None, w.hit)
+    buf = W.random_payload(w, 3, nfb * oracle.fullblock_bytes(bs, L, rows))
+    full = [W.sentinel_pool(w, "dst")]          # S = 1
+    part = [W.sentinel_pool(w, "dst")]
+    got_full = [planes[0].copy() for _, _, planes in
+                oracle.stream_layers_fullblocks(bs, L, rows, None, w.hit, w.dst.tables, buf, full)]
+    got_part = [planes[0].copy() for _, _, planes in
+                oracle.stream_layers_fullblocks(bs, L, rows, None, w.hit, w.dst.tables, buf, part, run_layers=2)]
+    assert len(got_full) == 4 and len(got_part) == 2
+    for a, b in zip(got_full, got_part):
+        assert a.tobytes() == b.tobytes()
 
 
 # --------------------------------------------------------------------------
@@ -508,3 +601,71 @@ def test_planted_mistake_is_caught(name, pat, rep):
                 % (root, os.path.join(root, "tests"), so))
         rc = subprocess.run([sys.executable, "-c", code], capture_output=True).returncode
         assert rc != 0, f"no pin noticed: {name}"
+
+
+# The Python layer of the oracle (the per-layer compositions and the request sharding) gets the
+# same treatment: mistakes planted in a copy of kvl_oracle.py, the battery run against the copy.
+PY_MUTANTS = [
+    ("full blocks: slot not wrapped", "stream_layers_fullblocks", "s = l % S", "s = l"),
+    ("full blocks: slot one ahead", "stream_layers_fullblocks", "s = l % S", "s = (l + 1) % S"),
+    ("full blocks: always layer 0", "stream_layers_fullblocks", "tables, l, blocks", "tables, 0, blocks"),
+    ("full blocks: layer one ahead", "stream_layers_fullblocks", "tables, l, blocks", "tables, (l + 1) % n_layers, blocks"),
+    ("full blocks: run_layers ignored", "stream_layers_fullblocks", "range(run_layers or n_layers)", "range(n_layers)"),
+    ("full blocks: yields slot 0", "stream_layers_fullblocks", "yield l, s, dev_slots[s]", "yield l, s, dev_slots[0]"),
+    ("full blocks: loads into slot 0", "stream_layers_fullblocks", "l, blocks, dev_slots[s])", "l, blocks, dev_slots[0])"),
+    ("dense: H and S swapped", "stream_layers", "H, S = len(host_layers), len(dev_slots)", "S, H = len(host_layers), len(dev_slots)"),
+    ("dense: host slot by S", "stream_layers", "host_layers[l % H]", "host_layers[l % S]"),
+    ("dense: host slot fixed", "stream_layers", "host_layers[l % H]", "host_layers[0]"),
+    ("dense: slot by H", "stream_layers", "s = l % S", "s = l % H"),
+    ("dense: yields slot 0", "stream_layers", "yield l, s, dev_slots[s]", "yield l, s, dev_slots[0]"),
+    ("sharding: ranges lose a request", "_ranges", "int(cuts[i + 1]))", "int(cuts[i + 1]) - 1)"),
+    ("payload of the first plane only", "payload_bytes", "rb.size, rbp))", "1, rbp))"),
+    ("full blocks: count ignores the first token", "fullblock_count", "c.size, fp, cp))", "c.size, None, cp))"),
+]
+
+
+def _mutate_function(src, func, old, new):
+    """Replace `old` by `new` inside the top-level function `func` of the source text only."""
+    start = src.index("\ndef %s(" % func)
+    end = src.find("\ndef ", start + 1)
+    end = len(src) if end < 0 else end
+    body = src[start:end]
+    assert body.count(old) >= 1, "mutation pattern no longer matches the oracle source"
+    return src[:start] + body.replace(old, new) + src[end:]
+
+
+def _battery_against_python(py_path):
+    """Run every pin with the oracle's Python layer replaced by another version of its source."""
+    code = compile(open(py_path).read(), KO.__file__, "exec")
+    exec(code, KO.__dict__)                       # same module object, so paths and the C library stay the real ones
+    for name in list(vars(oracle)):
+        if name in KO.__dict__ and callable(KO.__dict__[name]):
+            setattr(oracle, name, KO.__dict__[name])
+    for pin in PINS:
+        try:
+            pin()
+        except (AssertionError, ValueError, RuntimeError, IndexError, TypeError, StopIteration):
+            return 1
+    return 0
+
+
+def _run_python_battery(source_text):
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    with tempfile.TemporaryDirectory() as d:
+        path = os.path.join(d, "mutant.py")
+        open(path, "w").write(source_text)
+        code = ("import sys; sys.path.insert(0, %r); sys.path.insert(0, %r); "
+                "import test_oracle_pins as t; sys.exit(t._battery_against_python(%r))"
+                % (root, os.path.join(root, "tests"), path))
+        return subprocess.run([sys.executable, "-c", code], capture_output=True).returncode
+
+
+def test_python_battery_passes_unmutated():
+    """The harness itself: the untouched source, swapped in the same way, passes every pin."""
+    assert _run_python_battery(open(KO.__file__).read()) == 0
+
+
+@pytest.mark.parametrize("name,func,old,new", PY_MUTANTS, ids=[m[0] for m in PY_MUTANTS])
+def test_planted_python_mistake_is_caught(name, func, old, new):
+    assert _run_python_battery(_mutate_function(open(KO.__file__).read(), func, old, new)) != 0, \
+        f"no pin noticed: {name}"
