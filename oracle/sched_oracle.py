@@ -8,17 +8,27 @@ threshold Z and the two categories of the second decode phase.
 Pins (tests/test_sched.py): the range is pinned by the worked example the paper
 prints (g = 8, s = 1, M ~ 500 GB/s, Bs ~ 50 GB/s gives 1/7 <= P/D <= 7/2) and by
 re-deriving each bound from the traffic sums of eqs. (1)-(8).  The scheduling
-rules are heuristics for which the paper prints no example: they are pinned by
-the invariants the text states (overloaded engines get nothing, short-queue
-engines are served before long-queue ones, every choice is an arg-min at the
-moment it is made, token counts are conserved, Z is the stated formula) and by
-an independent event-driven simulation on small cases -- parity with the paper's
-own implementation is unpinned.
+rules are heuristics for which the paper prints no example.  Algorithm 1 is pinned
+by cases worked by hand in which the limit beta is crossed in the middle of a fetch,
+by a closed form (equal engines and equal requests: every engine takes
+floor(beta / size) + 1 requests, in round-robin order), by the textbook special case
+it reduces to without limits (greedy list scheduling onto the least loaded machine),
+by a checker that replays a finished fetch against the sentences of the text, by a
+two-heap simulation of different structure, and by mistakes planted in copies of this
+file.  The decode rules are pinned by the invariants the text states and the stated
+formula for Z -- parity with the paper's own implementation is unpinned.
 
-Readings: Algorithm 1 classifies the engines once per fetch, before the loop (the
-algorithm states the classification ahead of the loop); ties go to the lowest index; tokens(r) is the request's total
-length; phase 1 adds a request's length to its group's sum at once; HBM need and
-free HBM are counted in tokens.
+Readings.  Algorithm 1: the three categories are defined by tok_e, and tok_e of the
+chosen engine is updated after every assignment, so an engine whose unfinished tokens
+have grown beyond beta is overloaded from then on and, like every overloaded engine,
+gets nothing more in this fetch; that is what lets the
+fetch end part-way and return the requests assigned so far, the case the text and the
+listing both provide for inside the loop.  (With categories frozen before the loop
+that case could only arise before the first request, and beta would bound nothing
+within a fetch.)  An engine at exactly beta is not overloaded and may take one more
+request.  Ties go to the lowest index; tokens(r) is the request's total length; phase
+1 adds a request's length to its group's sum at once; HBM need and free HBM are
+counted in tokens.
 """
 from __future__ import annotations
 
@@ -46,13 +56,17 @@ def pe_fetch(tok: List[int], read_q: Sequence[int], Q: Sequence[int], alpha: int
     assigned = [-1] * len(Q)
     for i, tokens_r in enumerate(Q):               # FIFO
         if C2:
-            pe = min(C2, key=lambda e: (tok[e], e))
+            C = C2
         elif C3:
-            pe = min(C3, key=lambda e: (tok[e], e))
+            C = C3
         else:
-            break                                  # terminate this fetch
+            break                                  # terminate this fetch; assigned so far is returned
+        pe = min(C, key=lambda e: (tok[e], e))
         assigned[i] = pe
         tok[pe] = tok[pe] + tokens_r
+        if tok[pe] > beta:                         # the categories are defined by tok_e: pe is overloaded now
+            C.remove(pe)
+            C1.append(pe)
     return assigned
 
 
