@@ -30,14 +30,18 @@ typedef struct {
 int kvl_pd_range(double g, double s, double mem_bw, double storage_bw, kvl_pd_range_t *out);
 
 /* Inter-engine prefill scheduling, Section 6.1, Algorithm 1.  One fetch of a
- * prefill-engine group: engines are classified once from the reported metrics
- * (overloaded: tok > beta; short queue: read_q <= alpha; long queue: the rest);
- * the waiting queue is served in FIFO order, each request going to the engine
- * with the smallest tok among the short-queue engines if there are any, else
- * among the long-queue engines; tok of the chosen engine grows by the request's
- * tokens.  If both classes are empty the fetch ends.
+ * prefill-engine group.  An engine is overloaded while tok > beta and then gets
+ * nothing; of the others, those on nodes with a short reading queue
+ * (read_q <= alpha) are served before those with a long one.  The waiting queue is
+ * taken in FIFO order: each request goes to the engine with the smallest tok among
+ * the short-queue engines if any is left, else among the long-queue engines, and
+ * tok of the chosen engine grows by the request's tokens -- which may make it
+ * overloaded for the rest of the fetch (the categories follow tok as it is updated).
+ * When no engine is left the fetch ends and the remaining requests stay in the
+ * queue.  An engine at exactly beta still takes one request.
  * tok[], read_q[]: n_engines entries, tok is updated in place.
- * assign[]: n_req entries, engine index or -1 for requests left in the queue. */
+ * assign[]: n_req entries, engine index or -1 for requests left in the queue
+ * (always a tail of the queue); *n_assigned (may be NULL): how many were placed. */
 int kvl_sched_pe_fetch(uint64_t *tok, const uint64_t *read_q, uint32_t n_engines,
                        const uint64_t *req_tokens, uint32_t n_req,
                        uint64_t alpha, uint64_t beta, int32_t *assign, uint32_t *n_assigned);

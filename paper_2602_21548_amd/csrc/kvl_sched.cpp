@@ -26,23 +26,22 @@ int kvl_sched_pe_fetch(uint64_t *tok, const uint64_t *read_q, uint32_t n_engines
                        const uint64_t *req_tokens, uint32_t n_req, uint64_t alpha, uint64_t beta,
                        int32_t *assign, uint32_t *n_assigned) {
     if ((n_engines && (!tok || !read_q)) || (n_req && (!req_tokens || !assign))) return KVL_EINVAL;
-    std::vector<uint32_t> shortq, longq;
-    for (uint32_t e = 0; e < n_engines; ++e) {
-        if (tok[e] > beta) continue;                       // overloaded: gets nothing in this fetch
-        (read_q[e] <= alpha ? shortq : longq).push_back(e);
-    }
-    const std::vector<uint32_t> &pick_from = !shortq.empty() ? shortq : longq;
-    uint32_t done = 0;
     for (uint32_t r = 0; r < n_req; ++r) assign[r] = -1;
-    if (!pick_from.empty()) {
-        for (uint32_t r = 0; r < n_req; ++r) {
-            uint32_t best = pick_from[0];
-            for (uint32_t e : pick_from)
-                if (tok[e] < tok[best]) best = e;
-            assign[r] = (int32_t)best;
-            tok[best] += req_tokens[r];
-            ++done;
+    uint32_t done = 0;
+    for (uint32_t r = 0; r < n_req; ++r) {
+        // one pass finds the emptiest engine of each class among those not over the limit;
+        // membership follows tok as it stands now, so an engine filled by this fetch drops out
+        int64_t best_short = -1, best_long = -1;
+        for (uint32_t e = 0; e < n_engines; ++e) {
+            if (tok[e] > beta) continue;                       // overloaded: gets nothing
+            int64_t &best = read_q[e] <= alpha ? best_short : best_long;
+            if (best < 0 || tok[e] < tok[best]) best = e;
         }
+        const int64_t pick = best_short >= 0 ? best_short : best_long;
+        if (pick < 0) break;                                   // no engine left: the fetch ends here
+        assign[r] = (int32_t)pick;
+        tok[pick] += req_tokens[r];
+        ++done;
     }
     if (n_assigned) *n_assigned = done;
     return KVL_OK;
