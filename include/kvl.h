@@ -209,6 +209,28 @@ int kvl_move_layer(const kvl_plan_t *paired, const void *const *src_pool_planes,
 int kvl_unpack_layer(const kvl_plan_t *plan, const void *xfer, uint64_t xfer_bytes,
                      void *const *pool_planes, void *stream);
 
+/* kvl_unpack_layer for callers that cannot allocate: code that must not call hipMalloc or
+ * hipFree where it runs (tight serving loops, harnesses that forbid device allocation,
+ * processes whose memory is fully handed out).  It takes the batch instead of a plan -- the
+ * arguments of kvl_plan (flags: any of KVL_NO_MERGE, KVL_TOKENS_APPEND, KVL_TOKENS_ALL,
+ * KVL_NO_POINTER_CHECKS; KVL_SCATTER is implied) followed by those of kvl_unpack_layer --
+ * builds the descriptors on the host as kvl_plan does (same validation and error codes),
+ * uploads them on `stream` into a fixed array in device memory that belongs to the library's
+ * code object (KVL_NOALLOC_MAX_UNITS descriptors of 16 bytes = 8 MiB on every GPU the library
+ * is loaded on, held until the process ends) and enqueues the same scatter kernels there.
+ * The result in the pool is that of kvl_plan + kvl_unpack_layer.  It allocates no device or
+ * pinned memory and creates no stream; its first call on a device creates two events.
+ * KVL_ESPACE if the batch needs more than KVL_NOALLOC_MAX_UNITS descriptors (one per block of
+ * a fragmented table) or xfer_bytes is below the payload.  Every call on a GPU uses that GPU's
+ * one array: a call orders itself after the previous call's kernels (by an event, whatever
+ * their streams) and calls are serialised by a lock inside the library, so calls from several
+ * threads or streams are safe but do not overlap.  The descriptors are uploaded from host
+ * memory, so the call cannot be captured into a HIP graph. */
+#define KVL_NOALLOC_MAX_UNITS 524288u
+int kvl_unpack_layer_noalloc(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t n_req,
+                             uint32_t flags, const void *xfer, uint64_t xfer_bytes,
+                             void *const *pool_planes, void *stream);
+
 /* Prefill-engine read path, host buffer -> HBM for one layer (Section 4.1,
  * steps 3-4 of that path): the transfer buffer lies in PINNED host memory; it is
  * copied in chunks of at most chunk_bytes with hipMemcpyAsync into

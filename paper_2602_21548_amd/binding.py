@@ -114,6 +114,8 @@ _SIGNATURES = {
                                       C.POINTER(C.c_uint64)]),
     "kvl_pack_layer": (C.c_int, [_PLAN_P, C.POINTER(C.c_void_p), C.c_void_p, C.c_uint64, C.c_void_p]),
     "kvl_unpack_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_void_p]),
+    "kvl_unpack_layer_noalloc": (C.c_int, [C.POINTER(kvl_layout_t), C.POINTER(kvl_request_t), C.c_uint32, C.c_uint32,
+                                           C.c_void_p, C.c_uint64, C.POINTER(C.c_void_p), C.c_void_p]),
     "kvl_h2d_unpack_layer": (C.c_int, [_PLAN_P, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                        C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p]),
     "kvl_plan_fullblock_geometry": (C.c_int, [_PLAN_P, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
@@ -291,9 +293,8 @@ def make_layout(n_layers: int, block_tokens: int, row_bytes: Sequence[int], pool
     return lay
 
 
-def kvl_plan(layout: kvl_layout_t, hit, app, tables: Sequence[np.ndarray], flags: int,
-             unit_bytes: int = 0, block_threads: int = 0, variant: int = 0, max_groups: int = 0) -> Plan:
-    """kvl_plan / kvl_plan_tuned: block tables -> copy descriptors (host; device upload unless HOST_ONLY)."""
+def _requests(hit, app, tables: Sequence[np.ndarray]):
+    """(kvl_request_t array, n, arrays to keep alive while it is in use)"""
     hit = np.asarray(hit, dtype=np.uint32)
     app = np.asarray(app, dtype=np.uint32)
     n = int(hit.shape[0])
@@ -306,6 +307,13 @@ def kvl_plan(layout: kvl_layout_t, hit, app, tables: Sequence[np.ndarray], flags
         reqs[r].append_tokens = int(app[r])
         reqs[r].n_blocks = int(keep[r].size)
         reqs[r].block_table = keep[r].ctypes.data_as(C.POINTER(C.c_int32)) if keep[r].size else None
+    return reqs, n, keep
+
+
+def kvl_plan(layout: kvl_layout_t, hit, app, tables: Sequence[np.ndarray], flags: int,
+             unit_bytes: int = 0, block_threads: int = 0, variant: int = 0, max_groups: int = 0) -> Plan:
+    """kvl_plan / kvl_plan_tuned: block tables -> copy descriptors (host; device upload unless HOST_ONLY)."""
+    reqs, n, _keep = _requests(hit, app, tables)
     out = C.c_void_p()
     if unit_bytes or block_threads or variant or max_groups:
         t = kvl_tuning_t(unit_bytes, block_threads, variant, max_groups)
@@ -371,6 +379,26 @@ def kvl_unpack_layer(plan: Plan, xfer: torch.Tensor, pool_planes: Sequence[torch
         ptr = _dev(xfer, "xfer")
     _check(_lib.kvl_unpack_layer(plan.handle, ptr, _nbytes(xfer), arr, _stream_handle(stream)),
            "kvl_unpack_layer")
+
+
+KVL_NOALLOC_MAX_UNITS = 524288
+
+
+def kvl_unpack_layer_noalloc(layout: kvl_layout_t, hit, app, tables: Sequence[np.ndarray], flags: int,
+                             xfer: torch.Tensor, pool_planes: Sequence[torch.Tensor], stream=None) -> None:
+    """The scatter of kvl_plan + kvl_unpack_layer in one call that allocates nothing on the device."""
+    reqs, n, _keep = _requests(hit, app, tables)
+    if len(pool_planes) != int(layout.n_planes):
+        raise ValueError(f"kvl_unpack_layer_noalloc: expected {int(layout.n_planes)} planes")
+    arr = (C.c_void_p * int(layout.n_planes))()
+    for p, t in enumerate(pool_planes):
+        need = int(layout.pool_blocks) * int(layout.block_tokens) * int(layout.row_bytes[p])
+        if _nbytes(t) < need:
+            raise ValueError(f"kvl_unpack_layer_noalloc: plane {p} holds {_nbytes(t)} bytes, pool needs {need}")
+        arr[p] = _dev(t, "kvl_unpack_layer_noalloc pool")
+    ptr = _pinned(xfer, "xfer", 0) if (isinstance(xfer, torch.Tensor) and not xfer.is_cuda) else _dev(xfer, "xfer")
+    _check(_lib.kvl_unpack_layer_noalloc(C.byref(layout), reqs, n, flags, ptr, _nbytes(xfer), arr,
+                                         _stream_handle(stream)), "kvl_unpack_layer_noalloc")
 
 
 def _pinned(t: torch.Tensor, what: str, need: int) -> int:

@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libkvl.so")
-SOURCES = ["kvl_plan.hip", "kvl_kernels.hip", "kvl_h2d.hip", "kvl_stream.hip", "kvl_sched.cpp"]
+SOURCES = ["kvl_plan.hip", "kvl_kernels.hip", "kvl_h2d.hip", "kvl_stream.hip", "kvl_noalloc.hip", "kvl_sched.cpp"]
 
 
 def hipcc() -> str:
