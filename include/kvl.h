@@ -121,12 +121,15 @@ typedef struct {
                                 below it; the plan picks one piece size for the whole batch (block_tokens * 2^j or
                                 this limit) so that its descriptors are alike */
     uint32_t block_threads;  /* threads per workgroup: 64, 128, 256, 512 or 1024 */
-    uint32_t variant;        /* 0: default; 1..256: an explicit kernel variant, see kvl_variant_name */
+    uint32_t variant;        /* 0: default; 1..512: an explicit kernel variant, see kvl_variant_name */
     uint32_t max_groups;     /* tiled and Full-Block kernels: at most this many workgroups per launch and
                                 plane, each walking over several tiles.  0: one workgroup per tile, except
                                 that a kernel whose far side is host memory is kept to 64 (enough to fill
                                 the host link; the rest of the machine stays free for other kernels);
-                                UINT32_MAX: never walk */
+                                UINT32_MAX: never walk.  (A launch always stays below 2^32 lanes: beyond
+                                that the workgroups walk, whatever this says.)  Flat kernels (token-granular
+                                pools): at most this many workgroups per launch, the descriptors being
+                                spread over as many launches as that takes; 0: as many as a launch holds */
 } kvl_tuning_t;
 
 /* Build a plan.  Validates the batch (KVL_ERANGE: a block id outside
@@ -141,11 +144,17 @@ int kvl_plan(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t
              uint32_t flags, kvl_plan_t **out);
 int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t n_req,
                    uint32_t flags, const kvl_tuning_t *tuning, kvl_plan_t **out);
-/* Frees the plan.  Work enqueued with the plan should have finished (synchronise
- * the streams first; the call waits for the device to go idle in any case, as a
- * device free would).  The device descriptor array goes back to a small cache
- * inside the library (at most 16 buffers / 256 MiB) from which later plans are
- * served without a device allocation; kvl_release_cached_memory empties it. */
+/* Frees the plan.  The call does not wait for the device: kernels enqueued with the
+ * plan may still be running or queued.  Its device descriptor array is retired with
+ * an event recorded on every stream the plan's kernels were enqueued on, and goes
+ * back to a small cache inside the library (at most 16 buffers / 256 MiB, from which
+ * later plans are served without a device allocation) only when those events have
+ * fired; the streams must still exist when the plan is destroyed (if one does not,
+ * the call falls back to waiting for the device).  Only the plan's own lanes, if a
+ * host-buffer call left work on them that is not finished, are waited for.  A HIP
+ * graph that captured calls made with the plan must not be replayed after this.
+ * kvl_release_cached_memory empties the cache and the library's pool of lanes; it
+ * waits for the kernels of destroyed plans, and for nothing else. */
 void kvl_plan_destroy(kvl_plan_t *plan);
 void kvl_release_cached_memory(void);
 
@@ -457,6 +466,35 @@ int kvl_measure_h2d_peak(const void *pinned_host, void *dev, uint64_t bytes, uin
  * gather with perfect locality could reach, and the known-size kernel used to
  * calibrate HBM byte counters. */
 int kvl_copy_linear(const void *src, void *dst, uint64_t bytes, void *stream);
+
+/* Reference streams for measuring what the memory can do, beside the kernels of the load path
+ * (the benchmark's ceilings): plain device memory, the load/store instructions and cache policies
+ * of the default gather and scatter, no descriptors.
+ *   block_bytes == 0: one linear stream of `bytes` bytes, src (+ skew_bytes) -> dst;
+ *   block_bytes != 0: the access shape of a paged copy without its block tables: one side
+ *     ("dense") is a linear stream, the other hops every block_bytes: block u of the dense
+ *     side lives in block (u * odd constant) mod 2^hop_blocks_log2 of the hopping side, or in
+ *     block block_table[u] if block_table (device, bytes / block_bytes entries, each below
+ *     2^hop_blocks_log2 -- the caller's responsibility) is given: one scalar load per workgroup
+ *     before the data can be addressed, as the descriptor fetch of the real kernels.
+ *     hopping_side 0: the source hops (a gather; src holds 2^hop_blocks_log2 blocks, dst
+ *     bytes + skew_bytes), 1: the destination hops (a scatter).  skew_bytes (multiple of 16, below
+ *     128) shifts the dense side, so that the two sides sit differently in their 128-byte lines.
+ * mode: copy, or only the reads, or only the writes of that copy.  Both pointers 128-byte
+ * aligned; sizes are checked against the buffers (KVL_ESPACE).  What lands in dst is of no
+ * use.  Enqueues on stream; the caller times it. */
+#define KVL_CEILING_COPY  0u
+#define KVL_CEILING_READ  1u
+#define KVL_CEILING_WRITE 2u
+typedef struct {
+    uint32_t mode;
+    uint32_t block_bytes;
+    uint32_t hopping_side;
+    uint32_t skew_bytes;
+    uint32_t hop_blocks_log2;
+} kvl_ceiling_t;
+int kvl_ceiling_kernel(const kvl_ceiling_t *c, const void *src, uint64_t src_bytes, void *dst, uint64_t dst_bytes,
+                       uint64_t bytes, const uint32_t *block_table, void *stream);
 
 /* What every entry point asks of a buffer before a kernel may touch it: is
  * [ptr, ptr + bytes) memory this device can address?  Host memory passes only if

@@ -14,6 +14,7 @@ _EXPORTS = (
     "KVL_GATHER", "KVL_SCATTER", "KVL_HOST_ONLY", "KVL_NO_MERGE", "KVL_MAX_PLANES",
     "KVL_TOKENS_APPEND", "KVL_TOKENS_ALL", "KVL_NO_POINTER_CHECKS", "kvl_check_buffer",
     "kvl_unpack_layer_noalloc", "KVL_NOALLOC_MAX_UNITS",
+    "kvl_ceiling_kernel", "KVL_CEILING_COPY", "KVL_CEILING_READ", "KVL_CEILING_WRITE",
 )
 __all__ = list(_EXPORTS)
 

@@ -55,6 +55,11 @@ class kvl_tuning_t(C.Structure):
                 ("max_groups", C.c_uint32)]
 
 
+class kvl_ceiling_t(C.Structure):
+    _fields_ = [("mode", C.c_uint32), ("block_bytes", C.c_uint32), ("hopping_side", C.c_uint32),
+                ("skew_bytes", C.c_uint32), ("hop_blocks_log2", C.c_uint32)]
+
+
 class kvl_chunk_t(C.Structure):
     _fields_ = [("plane", C.c_uint32), ("unit_begin", C.c_uint32), ("unit_end", C.c_uint32),
                 ("reserved", C.c_uint32), ("host_offset", C.c_uint64), ("bytes", C.c_uint64)]
@@ -139,6 +144,8 @@ _SIGNATURES = {
                                        C.POINTER(C.c_double)]),
     "kvl_copy_linear": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p]),
     "kvl_check_buffer": (C.c_int, [C.c_void_p, C.c_uint64, C.c_int]),
+    "kvl_ceiling_kernel": (C.c_int, [C.POINTER(kvl_ceiling_t), C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64,
+                                     C.c_uint64, C.c_void_p, C.c_void_p]),
     "kvl_strerror": (C.c_char_p, [C.c_int]),
     "kvl_last_hip_error": (C.c_int, []),
     "kvl_last_hip_error_string": (C.c_char_p, []),
@@ -399,6 +406,21 @@ def kvl_unpack_layer_noalloc(layout: kvl_layout_t, hit, app, tables: Sequence[np
     ptr = _pinned(xfer, "xfer", 0) if (isinstance(xfer, torch.Tensor) and not xfer.is_cuda) else _dev(xfer, "xfer")
     _check(_lib.kvl_unpack_layer_noalloc(C.byref(layout), reqs, n, flags, ptr, _nbytes(xfer), arr,
                                          _stream_handle(stream)), "kvl_unpack_layer_noalloc")
+
+
+KVL_CEILING_COPY, KVL_CEILING_READ, KVL_CEILING_WRITE = 0, 1, 2
+
+
+def kvl_ceiling_kernel(mode: int, src: torch.Tensor, dst: torch.Tensor, nbytes: int, block_bytes: int = 0,
+                       hopping_side: int = 0, skew_bytes: int = 0, hop_blocks_log2: int = 0,
+                       block_table: Optional[torch.Tensor] = None, stream=None) -> None:
+    """One launch of a reference stream (see kvl_ceiling_kernel in kvl.h); the caller times it."""
+    c = kvl_ceiling_t(mode, block_bytes, hopping_side, skew_bytes, hop_blocks_log2)
+    if block_table is not None and (block_table.dtype != torch.int32 or not block_table.is_cuda):
+        raise TypeError("block_table: need an int32 device tensor")
+    _check(_lib.kvl_ceiling_kernel(C.byref(c), _dev(src, "src"), _nbytes(src), _dev(dst, "dst"), _nbytes(dst), nbytes,
+                                   _dev(block_table, "block_table") if block_table is not None else None,
+                                   _stream_handle(stream)), "kvl_ceiling_kernel")
 
 
 def _pinned(t: torch.Tensor, what: str, need: int) -> int:

@@ -22,6 +22,9 @@
 //   deep    modes 0-1: 8 instead of 4 vectors in flight per lane
 //   noalign modes 2-3: do not line tiles up with the destination's 128-byte lines
 //           (they are lined up by default whenever the rows are not multiples of 128 bytes)
+//   pipe    (code bit 8, with ntl, sp and noalign only) the tiled form on a fixed grid of resident
+//           workgroups, each walking over its tiles with loads, stores and descriptor fetches
+//           software-pipelined (see kvl_tile_pipe_kernel)
 //   flat    (code bit 7, with ntl and sp only) no tiles: lane g of the launch takes vector
 //           g mod m of descriptor g div m, m = vectors of the largest descriptor; for
 //           descriptors far smaller than a workgroup (token-granular pools)
@@ -82,13 +85,16 @@ __device__ __forceinline__ v4u load16(gsrc_t p) {
 
 // Store with a cache policy.  The compiler only offers the non-temporal hint;
 // the system-scope write-through forms (sc1) are written out as instructions.
-// A store needs no wait: nothing here reads what it wrote.
+// A store needs no wait: nothing here reads what it wrote.  The s_nop after a written-out
+// store covers the one hazard the compiler cannot see through the asm: a vector-ALU write to the
+// store's data registers in the next two issue slots (it handles that itself for stores it
+// emits; in a loop the next instruction may well be such a write).
 template <int SP>
 __device__ __forceinline__ void store16(gdst_t p, v4u v) {
     if (SP == 0) *p = v;
     else if (SP == 1) __builtin_nontemporal_store(v, p);
-    else if (SP == 2) asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
-    else asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
+    else if (SP == 2) asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+    else asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
 
 // `lanes` threads copy n 16-byte vectors; this thread is `lane`.  U loads are
@@ -221,6 +227,123 @@ __global__ void __launch_bounds__(1024) kvl_tile_walk_kernel(const CopyArgs a, u
         tile_body<PACK, VPT, NTL, SP>(a, tiles_per_unit, align_dst, t);
 }
 
+// Pipelined form of the tiled kernels: a fixed grid that fills the machine once (every
+// workgroup resident), each workgroup walking over the tiles gridDim.x apart with its work
+// software-pipelined three deep -- while the vectors of tile i are on their way, the loads of
+// tile i+1 have been issued and the descriptor of tile i+2 is being fetched.  One-shot
+// workgroups (the tiled form above) start with a dependent chain, descriptor fetch then data
+// load, during which their wavefronts hold a slot but have nothing in flight; on workloads of
+// many small descriptors the memory system then runs below saturation (its request queues
+// hardly ever push back) although every wavefront slot is taken.  Here a wavefront always has
+// one or two loads outstanding and the descriptor latency is hidden behind them.  The tiles a
+// workgroup visits and their order over the machine are those of the tiled form, so the
+// access stream the memory sees is the same.  The trip count is fixed at launch.
+struct PipeStage {
+    kvl_unit_t u;       // descriptor of the stage's tile
+    uint32_t tile;      // index of the tile inside its descriptor
+    bool valid;         // false: the workgroup has run out of tiles
+};
+// The descriptors are not written while a kernel runs: read through the constant address
+// space they stay scalar loads inside the loop (a plain global pointer may alias the stores
+// there, and the compiler then reads it with vector loads it has to wait for at once).
+typedef const kvl_unit_t __attribute__((address_space(4))) *cunits_t;
+
+// Inside the loop nothing is conditional: a lane whose position falls outside its descriptor
+// (the idle lead of an aligned first tile, the ragged end of the last) moves the descriptor's
+// nearest vector instead, a duplicate of what the lane that owns that vector moves, and the
+// loop covers only the trips in which every workgroup has a tile.  With a branch around a
+// load or a store the compiler can no longer tell how many memory operations are in flight
+// and drains them all before every store; without one it waits for exactly the load it needs.
+// The last few tiles of each workgroup are done one by one after the loop.
+template <bool PACK, bool NTL, int SP>
+__global__ void __launch_bounds__(1024) kvl_tile_pipe_kernel(const CopyArgs a, uint32_t tiles_per_unit,
+                                                             uint32_t align_dst, uint32_t n_tiles) {
+    const uint32_t p = a.plane_begin + blockIdx.y;
+    const uint32_t row = a.row_elems[p];
+    const uintptr_t pool_base = a.pool[p], xfer_base = a.xfer[p];
+    cunits_t units = (cunits_t)(uintptr_t)(a.units + a.unit_begin);
+    const uint32_t last_unit = a.n_units - 1;               // the launcher passes at least one descriptor
+    const uint32_t G = gridDim.x;                           // <= n_tiles
+    // the tile `k` strides ahead of this workgroup's first is tile (k*G + blockIdx.x): kept as
+    // (descriptor, tile inside it) and advanced without a division
+    const uint32_t step_u = G / tiles_per_unit, step_t = G - step_u * tiles_per_unit;
+    uint32_t f_u = blockIdx.x / tiles_per_unit, f_t = blockIdx.x - f_u * tiles_per_unit;   // the fetch stage's tile
+    auto fetch = [&](PipeStage &s) {
+        s.tile = f_t;
+        s.valid = f_u <= last_unit;
+        cunits_t q = units + (f_u <= last_unit ? f_u : last_unit);     // always a load, never past the end
+        s.u.pool_row = q->pool_row;
+        s.u.xfer_row = q->xfer_row;
+        s.u.n_rows = q->n_rows;
+        f_u += step_u;
+        f_t += step_t;
+        if (f_t >= tiles_per_unit) {
+            f_t -= tiles_per_unit;
+            ++f_u;
+        }
+    };
+    // this lane's vector of a stage's tile (descriptors are never empty)
+    auto place = [&](const PipeStage &s, gsrc_t &src, gdst_t &dst) {
+        const uint32_t n = s.u.n_rows * row;
+        const uintptr_t pool = pool_base + (uint64_t)s.u.pool_row * row * 16u;
+        const uintptr_t xfer = xfer_base + (uint64_t)s.u.xfer_row * row * 16u;
+        const uint32_t lead = align_dst ? ((uint32_t)((PACK ? xfer : pool) >> 4) & 7u) : 0u;
+        const uint32_t pos = s.tile * blockDim.x + threadIdx.x;
+        uint32_t j = pos >= lead ? pos - lead : 0u;
+        j = j < n ? j : n - 1;
+        src = (gsrc_t)(PACK ? pool : xfer) + j;
+        dst = (gdst_t)(PACK ? xfer : pool) + j;
+    };
+    // trips in which every workgroup has a tile; the loop takes them two at a time and stops
+    // two short, so that its three stages never run past them
+    const uint32_t full = n_tiles / G;
+    const uint32_t looped = full >= 2 ? (full - 2) & ~1u : 0u;
+    // Two sets of registers, A for the even tiles and B for the odd ones, so that nothing is
+    // moved from one to the other (a move of loaded data would have to wait for it).
+    PipeStage s_a, s_b;
+    gsrc_t src_a, src_b;
+    gdst_t dst_a, dst_b;
+    v4u v_a, v_b;
+    fetch(s_a);                                   // tile 0 of this workgroup (there always is one)
+    fetch(s_b);                                   // tile 1
+    place(s_a, src_a, dst_a);
+    v_a = load16<NTL>(src_a);
+    fetch(s_a);                                   // tile 2
+    for (uint32_t i = 0; i < looped; i += 2) {
+        // (a scalar load can only be waited for together with every other one in flight, so a
+        // descriptor is fetched after the step's use of the one fetched before it)
+        place(s_b, src_b, dst_b);
+        v_b = load16<NTL>(src_b);                 // tile i + 1 on its way
+        fetch(s_b);                               // descriptor of tile i + 3, first needed two steps on
+        store16<SP>(dst_a, v_a);                  // tile i: waits for its own load only
+        place(s_a, src_a, dst_a);
+        v_a = load16<NTL>(src_a);                 // tile i + 2
+        fetch(s_a);                               // tile i + 4
+        store16<SP>(dst_b, v_b);                  // tile i + 1
+    }
+    // in flight: tile `looped` in v_a; s_b holds tile looped + 1, s_a tile looped + 2
+    store16<SP>(dst_a, v_a);
+    // the remaining tiles of this workgroup (at most three: looped + 1, + 2, + 3), one at a
+    // time; they may not exist, and their idle lanes are switched off rather than duplicated
+    PipeStage s_c;
+    fetch(s_c);                                   // tile looped + 3
+    auto copy_tile = [&](const PipeStage &s) {
+        const uint32_t n = s.valid ? s.u.n_rows * row : 0u;
+        const uintptr_t pool = pool_base + (uint64_t)s.u.pool_row * row * 16u;
+        const uintptr_t xfer = xfer_base + (uint64_t)s.u.xfer_row * row * 16u;
+        const uint32_t lead = align_dst ? ((uint32_t)((PACK ? xfer : pool) >> 4) & 7u) : 0u;
+        const uint32_t pos = s.tile * blockDim.x + threadIdx.x;
+        if (pos >= lead && pos - lead < n) {
+            gsrc_t sp = (gsrc_t)(PACK ? pool : xfer) + (pos - lead);
+            gdst_t dp = (gdst_t)(PACK ? xfer : pool) + (pos - lead);
+            store16<SP>(dp, load16<NTL>(sp));
+        }
+    };
+    copy_tile(s_b);
+    copy_tile(s_a);
+    copy_tile(s_c);
+}
+
 // Flat form for descriptors much smaller than a workgroup: the lanes of the launch are
 // dealt to the descriptors m at a time (m = max_unit_rows * row, the vectors of the
 // largest descriptor), so lane g moves vector g mod m of descriptor g div m; a shorter
@@ -324,6 +447,60 @@ __global__ void __launch_bounds__(256) kvl_fullblock_kernel(const FullBlockArgs 
                                                             uint32_t n_tiles) {
     for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x)
         fullblock_tile<TO_POOL, VEC, VPT>(a, tiles_per_unit, t);
+}
+
+// Reference streams for measuring what the memory can do (kvl_ceiling_kernel): the tiled form
+// with its addresses computed instead of read from descriptors.  Block u of the dense side
+// lives in block (u * mul) mod 2^k of the hopping side (mul odd: a bijection), or in block
+// table[u] if a table is given (one scalar load, as the descriptor fetch of the real kernels).
+struct CeilingArgs {
+    uintptr_t dense, hopping;       // base addresses
+    const uint32_t *table;          // optional
+    uint64_t tile_magic;            // ceil(2^40 / tiles_per_block): block of a workgroup by multiplication
+    uint32_t n_blocks, hop_mask, mul;
+    uint32_t block_vecs, tiles_per_block, skew_vecs, n_vecs;
+};
+
+// MODE 0: copy, 1: read only, 2: write only.  GATHER: the source hops, else the destination.
+template <int MODE, bool GATHER, bool NTL, int SP>
+__global__ void __launch_bounds__(256) kvl_ceiling_pattern_kernel(const CeilingArgs a) {
+    const uint32_t w = blockIdx.x;
+    const uint32_t u = (uint32_t)(((uint64_t)w * a.tile_magic) >> 40);
+    const uint32_t tile = w - u * a.tiles_per_block;
+    const uint32_t hb = a.table ? a.table[u] : ((u * a.mul) & a.hop_mask);
+    const uintptr_t hop = a.hopping + (uint64_t)hb * a.block_vecs * 16u;
+    const uintptr_t den = a.dense + ((uint64_t)u * a.block_vecs + a.skew_vecs) * 16u;
+    gsrc_t src = (gsrc_t)(GATHER ? hop : den);
+    gdst_t dst = (gdst_t)(GATHER ? den : hop);
+    const uint32_t lead = (uint32_t)((GATHER ? den : hop) >> 4) & 7u;     // tiles start on a destination line
+    const uint32_t pos = tile * blockDim.x + threadIdx.x;
+    if (pos < lead || pos - lead >= a.block_vecs) return;
+    if (MODE == 0) {
+        store16<SP>(dst + (pos - lead), load16<NTL>(src + (pos - lead)));
+    } else if (MODE == 1) {
+        const v4u v = load16<NTL>(src + (pos - lead));
+        if (v.x == 0x9e3779b9u && v.y == 0x7f4a7c15u && v.z == 0xf39cc060u && v.w == 0x5cedc834u)
+            store16<SP>(dst + (pos - lead), v);     // keeps the load alive; the pattern does not occur in the buffers
+    } else {
+        const v4u v = {pos, u, tile, hb};
+        store16<SP>(dst + (pos - lead), v);
+    }
+}
+
+template <int MODE, bool NTL, int SP>
+__global__ void __launch_bounds__(256) kvl_ceiling_linear_kernel(const v4u *src, v4u *dst, uint64_t n) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    if (MODE == 0) {
+        store16<SP>((gdst_t)dst + i, load16<NTL>((gsrc_t)src + i));
+    } else if (MODE == 1) {
+        const v4u v = load16<NTL>((gsrc_t)src + i);
+        if (v.x == 0x9e3779b9u && v.y == 0x7f4a7c15u && v.z == 0xf39cc060u && v.w == 0x5cedc834u)
+            store16<SP>((gdst_t)dst + i, v);
+    } else {
+        const v4u v = {(uint32_t)i, 1u, 2u, 3u};
+        store16<SP>((gdst_t)dst + i, v);
+    }
 }
 
 // Straight copy, one vector per lane: the tiled kernel without descriptors.

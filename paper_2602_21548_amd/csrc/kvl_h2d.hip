@@ -31,9 +31,10 @@ namespace kvl {
 int ensure_lanes(kvl_plan_t *plan, size_t lanes) {
     while (plan->lanes.size() < lanes) {
         hipStream_t s = nullptr;
-        if (plan->lane_cu_mask.empty())
-            KVL_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
-        else
+        if (plan->lane_cu_mask.empty()) {
+            s = take_pooled_lane(plan->device);
+            if (!s) KVL_HIP(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        } else
             KVL_HIP(hipExtStreamCreateWithCUMask(&s, (uint32_t)plan->lane_cu_mask.size(),
                                                  plan->lane_cu_mask.data()));
         plan->lanes.push_back(s);
@@ -441,11 +442,23 @@ int kvl_plan_set_lane_cu_mask(kvl_plan_t *plan, const uint32_t *mask, uint32_t n
     if (!any) return KVL_EINVAL;                       // a mask with no compute unit at all
     // the lanes are made anew, under the new mask, by the next call that needs them
     hipError_t first = hipSuccess;
+    const bool poolable = plan->lane_cu_mask.empty();       // lanes made without a mask serve any plan
     for (hipStream_t s : plan->lanes) {
         hipError_t e = hipStreamSynchronize(s);
         if (first == hipSuccess) first = e;
-        e = hipStreamDestroy(s);
-        if (first == hipSuccess) first = e;
+        // nothing of this plan runs on the lane any more: it need not be followed when the plan goes
+        for (size_t i = 0; i < plan->used_streams.size(); ++i) {
+            if (plan->used_streams[i] == s) {
+                plan->used_streams.erase(plan->used_streams.begin() + (long)i);
+                break;
+            }
+        }
+        if (poolable) {
+            kvl::return_lane(s, plan->device);
+        } else {
+            e = hipStreamDestroy(s);
+            if (first == hipSuccess) first = e;
+        }
     }
     plan->lanes.clear();
     try {

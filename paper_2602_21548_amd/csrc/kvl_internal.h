@@ -27,6 +27,10 @@ struct kvl_plan_s {
     kvl_unit_t *d_units = nullptr;               // device copy (absent for KVL_HOST_ONLY)
     size_t d_units_capacity = 0;                 // bytes of the cached buffer d_units lives in
     int device = -1;
+    // streams on which kernels that read d_units were enqueued (the caller's and the lanes):
+    // the buffer may be handed to another plan once each of them has got past that work
+    mutable std::vector<hipStream_t> used_streams;
+    mutable bool used_streams_overflow = false;  // more distinct streams than are tracked: wait for the device instead
     kvl_tuning_t tuning{};                       // resolved (no zero fields)
     // h2d path: one lane (a stream of the library's own) and one "lane done" event per staging slot
     std::vector<hipStream_t> lanes;
@@ -51,8 +55,19 @@ void set_hip_error(hipError_t e);
 constexpr uint32_t kDefaultUnitBytes = 128u << 10;
 constexpr uint32_t kDefaultBlockThreads = 256;
 constexpr uint32_t kHostSideGroups = 64;    // workgroups of a kernel whose far side is host memory (see kvl_tile_walk_kernel)
-constexpr uint32_t kNumVariants = 256;       // explicit variants are 1 .. kNumVariants
+constexpr uint32_t kNumVariants = 512;       // explicit variants are 1 .. kNumVariants
 bool valid_block_threads(uint32_t t);
+
+// A launch may not have 2^32 or more lanes along x.  How many workgroups of `threads` lanes a
+// launch over `work` workgroups' worth of tiles gets: all of them if that fits (and no cap is
+// asked for), else as many as fit, each walking over several tiles.  *walk says which.
+constexpr uint64_t kMaxLanesPerLaunch = (1ull << 32) - 1;
+inline uint32_t launch_groups(uint64_t work, uint32_t threads, uint32_t cap, bool *walk) {
+    uint64_t most = kMaxLanesPerLaunch / threads;
+    if (cap && cap < most) most = cap;
+    *walk = work > most;
+    return (uint32_t)(*walk ? most : work);
+}
 
 // Cut [0, n_units) of one plane into chunks of at most chunk_bytes.
 int make_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, std::vector<kvl_chunk_t> &out);
@@ -70,6 +85,11 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
 bool is_host_memory(const kvl_plan_t *plan, const void *ptr);
 
 int upload_units(kvl_plan_t *plan);
+// remember that a kernel reading the plan's descriptors was enqueued on `stream`
+void note_stream(const kvl_plan_t *plan, hipStream_t stream);
+// lanes come from, and go back to, a small pool shared by all plans
+hipStream_t take_pooled_lane(int device);
+void return_lane(hipStream_t lane, int device);
 // kvl_check_buffer unless the plan opted out
 int check_buffer(const kvl_plan_t *plan, const void *ptr, uint64_t bytes, bool allow_host);
 int check_pool(const kvl_plan_t *plan, const void *const *planes, uint64_t pool_blocks);

@@ -87,6 +87,39 @@ static void launch_tile_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const
 }
 
 template <bool PACK, bool NTL>
+static void launch_pipe_sp(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu, uint32_t al,
+                           uint32_t n_tiles) {
+    switch ((v >> 3) & 3u) {
+        case 0: hipLaunchKernelGGL((kvl_tile_pipe_kernel<PACK, NTL, 0>), g, b, 0, s, a, tpu, al, n_tiles); break;
+        case 1: hipLaunchKernelGGL((kvl_tile_pipe_kernel<PACK, NTL, 1>), g, b, 0, s, a, tpu, al, n_tiles); break;
+        case 2: hipLaunchKernelGGL((kvl_tile_pipe_kernel<PACK, NTL, 2>), g, b, 0, s, a, tpu, al, n_tiles); break;
+        default: hipLaunchKernelGGL((kvl_tile_pipe_kernel<PACK, NTL, 3>), g, b, 0, s, a, tpu, al, n_tiles); break;
+    }
+}
+
+template <bool PACK>
+static void launch_pipe_variant(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t tpu,
+                                uint32_t al, uint32_t n_tiles) {
+    if (v & 4u) launch_pipe_sp<PACK, true>(v, g, b, s, a, tpu, al, n_tiles);
+    else launch_pipe_sp<PACK, false>(v, g, b, s, a, tpu, al, n_tiles);
+}
+
+// Compute units of a device (asked once per device).
+static int compute_units(int device) {
+    static int cached[64] = {};
+    if (device < 0 || device >= 64) return 256;
+    if (cached[device] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n <= 0) {
+            (void)hipGetLastError();
+            n = 256;
+        }
+        cached[device] = n;
+    }
+    return cached[device];
+}
+
+template <bool PACK, bool NTL>
 static void launch_flat_sp(uint32_t v, dim3 g, dim3 b, hipStream_t s, const CopyArgs &a, uint32_t mur) {
     switch ((v >> 3) & 3u) {
         case 0: hipLaunchKernelGGL((kvl_flat_kernel<PACK, NTL, 0>), g, b, 0, s, a, mur); break;
@@ -124,6 +157,7 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
     }
     int rc_dev = check_device(plan);
     if (rc_dev != KVL_OK) return rc_dev;
+    note_stream(plan, stream);
     CopyArgs a{};
     a.units = plan->d_units;
     a.unit_begin = unit_begin;
@@ -154,6 +188,7 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
         // form (kHostSideGroups) keep enough bytes in flight
         if (far_host) v |= 3u;
     }
+    if (v & 256u) v = (v & ~(3u | 32u | 128u)) | 2u;      // the pipelined form is a tiled one, one vector per lane
     uint32_t widest = 0;        // vectors of the largest descriptor, over the planes of this launch
     for (uint32_t p = plane_begin; p < plane_end; ++p) widest = std::max(widest, a.row_elems[p]);
     const uint64_t unit_vecs = (uint64_t)plan->max_unit_rows * widest;
@@ -171,12 +206,23 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
     }
     dim3 block(threads);
     if (!vec) {
-        dim3 grid(a.n_units, plane_end - plane_begin);
-        if (pack) hipLaunchKernelGGL(kvl_bytes_kernel<true>, grid, block, 0, stream, a);
-        else hipLaunchKernelGGL(kvl_bytes_kernel<false>, grid, block, 0, stream, a);
+        // one workgroup per descriptor; a launch holds fewer than 2^32 lanes
+        const uint64_t per_launch = kMaxLanesPerLaunch / threads;
+        for (uint64_t first = 0; first < a.n_units; first += per_launch) {
+            CopyArgs part = a;
+            part.unit_begin = a.unit_begin + (uint32_t)first;
+            part.n_units = (uint32_t)std::min<uint64_t>(per_launch, a.n_units - first);
+            dim3 grid(part.n_units, plane_end - plane_begin);
+            if (pack) hipLaunchKernelGGL(kvl_bytes_kernel<true>, grid, block, 0, stream, part);
+            else hipLaunchKernelGGL(kvl_bytes_kernel<false>, grid, block, 0, stream, part);
+        }
     } else if (v & 128u) {
         // lane indices are 32 bits: split the descriptors over launches where they would not fit
-        const uint64_t per_launch = std::max<uint64_t>(1, ((1ull << 32) - threads) / std::max<uint64_t>(1, unit_vecs));
+        // (tuning.max_groups, if given, lowers the workgroups per launch further)
+        uint64_t lanes_per_launch = (1ull << 32) - threads;
+        if (plan->tuning.max_groups)
+            lanes_per_launch = std::min<uint64_t>(lanes_per_launch, (uint64_t)plan->tuning.max_groups * threads);
+        const uint64_t per_launch = std::max<uint64_t>(1, lanes_per_launch / std::max<uint64_t>(1, unit_vecs));
         for (uint64_t first = 0; first < a.n_units; first += per_launch) {
             CopyArgs part = a;
             part.unit_begin = a.unit_begin + (uint32_t)first;
@@ -203,8 +249,23 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
         // fewer workgroups than tiles, each walking over several: on request, or because the
         // far side is host memory
         const uint32_t cap = plan->tuning.max_groups ? plan->tuning.max_groups : (far_host ? kHostSideGroups : 0u);
-        const uint32_t n_tiles = (cap && blocks > cap) ? (uint32_t)blocks : 0u;
-        dim3 grid(n_tiles ? cap : (uint32_t)blocks, plane_end - plane_begin);
+        if (v & 256u) {
+            // pipelined walk: as many workgroups as the machine holds at once (32 wavefronts per compute
+            // unit), shared among the planes of the launch
+            const uint64_t resident = (uint64_t)compute_units(plan->device) * (2048u / threads);
+            uint64_t groups = cap ? cap : std::max<uint64_t>(1, resident / (plane_end - plane_begin));
+            groups = std::min<uint64_t>(groups, blocks);
+            dim3 grid((uint32_t)groups, plane_end - plane_begin);
+            if (pack) launch_pipe_variant<true>(v, grid, block, stream, a, (uint32_t)tpu, al, (uint32_t)blocks);
+            else launch_pipe_variant<false>(v, grid, block, stream, a, (uint32_t)tpu, al, (uint32_t)blocks);
+            KVL_HIP(hipGetLastError());
+            return KVL_OK;
+        }
+        // one workgroup per tile, unless a cap was asked for or the launch would not fit
+        bool walk = false;
+        const uint32_t groups = launch_groups(blocks, threads, cap, &walk);
+        const uint32_t n_tiles = walk ? (uint32_t)blocks : 0u;
+        dim3 grid(groups, plane_end - plane_begin);
         if (pack) {
             if (vpt == 2) launch_tile_variant<true, 2>(v, grid, block, stream, a, (uint32_t)tpu, al, n_tiles);
             else launch_tile_variant<true, 1>(v, grid, block, stream, a, (uint32_t)tpu, al, n_tiles);
@@ -214,6 +275,7 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
         }
     } else {
         const uint32_t per_wg = (v & 3u) == 1u ? threads / 64 : 1;
+        if ((uint64_t)((a.n_units + per_wg - 1) / per_wg) * threads > kMaxLanesPerLaunch) return KVL_ERANGE;
         dim3 grid((a.n_units + per_wg - 1) / per_wg, plane_end - plane_begin);
         if (pack) launch_span_variant<true>(v, grid, block, stream, a);
         else launch_span_variant<false>(v, grid, block, stream, a);
@@ -241,6 +303,7 @@ int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint6
         vec = vec && reinterpret_cast<uintptr_t>(pool_planes[p]) % 16 == 0;
     }
     const uint64_t e = vec ? 16 : 1;          // element size
+    note_stream(plan, stream);
     FullBlockArgs a{};
     a.units = plan->d_units + unit_begin;
     a.n_units = unit_end - unit_begin;
@@ -265,7 +328,8 @@ int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint6
     if (tpu == 0 || wgs > (uint64_t)INT32_MAX) return KVL_ERANGE;
     const uint32_t cap = plan->tuning.max_groups ? plan->tuning.max_groups : (far_host ? kHostSideGroups : 0u);
     const uint32_t n_tiles = (uint32_t)wgs;
-    dim3 grid((cap && wgs > cap) ? cap : (uint32_t)wgs, P), block(threads);
+    bool walk = false;
+    dim3 grid(launch_groups(wgs, threads, cap, &walk), P), block(threads);
 #define KVL_FB_LAUNCH(TP, VE, VP) \
     hipLaunchKernelGGL((kvl_fullblock_kernel<TP, VE, VP>), grid, block, 0, stream, a, (uint32_t)tpu, n_tiles)
     if (to_pool) {
@@ -394,11 +458,83 @@ int kvl_copy_linear(const void *src, void *dst, uint64_t bytes, void *stream) {
     int rc = kvl_check_buffer(src, bytes, 1);
     if (rc == KVL_OK) rc = kvl_check_buffer(dst, bytes, 1);
     if (rc != KVL_OK) return rc;
-    const uint64_t n = bytes / 16;
-    const uint64_t blocks = (n + 255) / 256;
-    if (blocks > (uint64_t)INT32_MAX) return KVL_ERANGE;
-    hipLaunchKernelGGL(kvl::kvl_linear_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream,
-                       static_cast<const kvl::v4u *>(src), static_cast<kvl::v4u *>(dst), n);
+    // a launch holds fewer than 2^32 lanes: larger copies go in several
+    const uint64_t n = bytes / 16, per_launch = (kvl::kMaxLanesPerLaunch / 256) * 256;
+    for (uint64_t first = 0; first < n; first += per_launch) {
+        const uint64_t m = std::min<uint64_t>(per_launch, n - first);
+        hipLaunchKernelGGL(kvl::kvl_linear_kernel, dim3((uint32_t)((m + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                           static_cast<const kvl::v4u *>(src) + first, static_cast<kvl::v4u *>(dst) + first, m);
+        KVL_HIP(hipGetLastError());
+    }
+    return KVL_OK;
+}
+
+int kvl_ceiling_kernel(const kvl_ceiling_t *c, const void *src, uint64_t src_bytes, void *dst, uint64_t dst_bytes,
+                       uint64_t bytes, const uint32_t *block_table, void *stream) {
+    using namespace kvl;
+    if (!c || !src || !dst || bytes == 0) return KVL_EINVAL;
+    if (c->mode > KVL_CEILING_WRITE || c->skew_bytes % 16 || c->skew_bytes >= 128 || c->block_bytes % 16) return KVL_EINVAL;
+    if (bytes % 16 || reinterpret_cast<uintptr_t>(src) % 128 || reinterpret_cast<uintptr_t>(dst) % 128) return KVL_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    if (c->block_bytes == 0) {
+        // one linear stream; the skew shifts the source
+        if (src_bytes < bytes + c->skew_bytes || dst_bytes < bytes) return KVL_ESPACE;
+        int rc = kvl_check_buffer(src, bytes + c->skew_bytes, 0);
+        if (rc == KVL_OK) rc = kvl_check_buffer(dst, bytes, 0);
+        if (rc != KVL_OK) return rc;
+        const uint64_t n = bytes / 16, per_launch = (kMaxLanesPerLaunch / 256) * 256;
+        const v4u *from = reinterpret_cast<const v4u *>(static_cast<const char *>(src) + c->skew_bytes);
+        for (uint64_t first = 0; first < n; first += per_launch) {
+            const uint64_t m = std::min<uint64_t>(per_launch, n - first);
+            const dim3 grid((uint32_t)((m + 255) / 256)), block(256);
+            v4u *to = static_cast<v4u *>(dst) + first;
+            if (c->mode == KVL_CEILING_COPY)
+                hipLaunchKernelGGL((kvl_ceiling_linear_kernel<0, kLinearNtLoad, kLinearStorePolicy>), grid, block, 0, s, from + first, to, m);
+            else if (c->mode == KVL_CEILING_READ)
+                hipLaunchKernelGGL((kvl_ceiling_linear_kernel<1, kLinearNtLoad, kLinearStorePolicy>), grid, block, 0, s, from + first, to, m);
+            else
+                hipLaunchKernelGGL((kvl_ceiling_linear_kernel<2, kLinearNtLoad, kLinearStorePolicy>), grid, block, 0, s, from + first, to, m);
+            KVL_HIP(hipGetLastError());
+        }
+        return KVL_OK;
+    }
+    if (bytes % c->block_bytes || c->hop_blocks_log2 > 31) return KVL_EINVAL;
+    const uint64_t n_blocks = bytes / c->block_bytes, hop_blocks = 1ull << c->hop_blocks_log2;
+    if (n_blocks > hop_blocks || n_blocks > UINT32_MAX) return KVL_EINVAL;
+    const uint64_t hop_bytes = hop_blocks * c->block_bytes, dense_bytes = bytes + c->skew_bytes;
+    const bool gather = c->hopping_side == 0;
+    if ((gather ? src_bytes : dst_bytes) < hop_bytes || (gather ? dst_bytes : src_bytes) < dense_bytes) return KVL_ESPACE;
+    int rc = kvl_check_buffer(src, gather ? hop_bytes : dense_bytes, 0);
+    if (rc == KVL_OK) rc = kvl_check_buffer(dst, gather ? dense_bytes : hop_bytes, 0);
+    if (rc == KVL_OK && block_table) rc = kvl_check_buffer(block_table, n_blocks * 4, 0);
+    if (rc != KVL_OK) return rc;
+    CeilingArgs a{};
+    a.dense = reinterpret_cast<uintptr_t>(gather ? dst : src);
+    a.hopping = reinterpret_cast<uintptr_t>(gather ? const_cast<void *>(src) : dst);
+    a.table = block_table;
+    a.n_blocks = (uint32_t)n_blocks;
+    a.hop_mask = (uint32_t)(hop_blocks - 1);
+    a.mul = 0x9e3779b1u;                    // odd
+    a.block_vecs = c->block_bytes / 16;
+    a.tiles_per_block = (a.block_vecs + 7 + 255) / 256;
+    a.skew_vecs = c->skew_bytes / 16;
+    a.tile_magic = ((1ull << 40) + a.tiles_per_block - 1) / a.tiles_per_block;
+    const uint64_t groups = n_blocks * a.tiles_per_block;
+    // the multiplication finds the block of every workgroup index below 2^24 * tiles_per_block exactly
+    if (groups > (1ull << 24) || groups * 256 > kMaxLanesPerLaunch) return KVL_ERANGE;
+    const dim3 grid((uint32_t)groups), block(256);
+#define KVL_CEIL(M, G, N, S) hipLaunchKernelGGL((kvl_ceiling_pattern_kernel<M, G, N, S>), grid, block, 0, s, a)
+    // the cache policies of the default gather and scatter
+    if (gather) {
+        if (c->mode == KVL_CEILING_COPY) KVL_CEIL(0, true, true, 2);
+        else if (c->mode == KVL_CEILING_READ) KVL_CEIL(1, true, true, 2);
+        else KVL_CEIL(2, true, true, 2);
+    } else {
+        if (c->mode == KVL_CEILING_COPY) KVL_CEIL(0, false, false, 3);
+        else if (c->mode == KVL_CEILING_READ) KVL_CEIL(1, false, false, 3);
+        else KVL_CEIL(2, false, false, 3);
+    }
+#undef KVL_CEIL
     KVL_HIP(hipGetLastError());
     return KVL_OK;
 }
@@ -410,7 +546,10 @@ const char *kvl_variant_name(uint32_t v) {
     v -= 1;
     static const char *modes[4] = {"wg/unit", "wave/unit", "tile x1", "tile x2"};
     static const char *sp[4] = {"", " st:nt", " st:sc1", " st:sc1+nt"};
-    if (v & 128u)
+    if (v & 256u)
+        std::snprintf(name, sizeof name, "pipe%s%s%s", (v & 4u) ? " ld:nt" : "", sp[(v >> 3) & 3u],
+                      (v & 64u) ? " noalign" : "");
+    else if (v & 128u)
         std::snprintf(name, sizeof name, "flat%s%s", (v & 4u) ? " ld:nt" : "", sp[(v >> 3) & 3u]);
     else
         std::snprintf(name, sizeof name, "%s%s%s%s%s", modes[v & 3u], (v & 4u) ? " ld:nt" : "",

@@ -43,32 +43,157 @@ int make_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, std::vector<kvl_ch
     return KVL_OK;
 }
 
-// Descriptor arrays come from a small per-process cache, so that a caller who
-// builds a plan per batch does not pay a device allocation and a device free
-// (both synchronise the device, and a free can stall the next launch for tens
-// of milliseconds) on every batch.
+// Descriptor arrays come from a small per-process cache, so that a caller who builds a plan
+// per batch pays neither a device allocation nor a device free (both synchronise the device,
+// and a free can stall the next launch for tens of milliseconds).  A destroyed plan's array is
+// retired, not freed: an event is recorded on every stream that ran kernels reading it, and the
+// array goes back to the cache only when those events have fired.  Nothing here waits for the
+// device; only kvl_release_cached_memory blocks (on the retired arrays' own events).
 namespace {
 struct CachedBuffer {
     void *ptr;
     size_t capacity;
     int device;
 };
-std::mutex g_cache_mutex;
+struct RetiredBuffer {
+    CachedBuffer buf;
+    std::vector<hipEvent_t> events;     // all fired: no kernel reads the buffer any more
+};
+struct PooledLane {
+    hipStream_t stream;
+    int device;
+};
+std::mutex g_cache_mutex;               // guards everything below
 std::vector<CachedBuffer> g_cache;
+std::vector<RetiredBuffer> g_retired;
+std::vector<std::pair<hipEvent_t, int>> g_events;       // spare events, with their device
+std::vector<PooledLane> g_lanes;
 constexpr size_t kCacheEntries = 16;
 constexpr size_t kCacheBytes = 256u << 20;      // never keep more than this much idle
+constexpr size_t kSpareEvents = 64;
+constexpr size_t kPooledLanes = 16;
+constexpr size_t kTrackedStreams = 24;
 
 size_t round_capacity(size_t bytes) {
     size_t cap = 64u << 10;
     while (cap < bytes) cap <<= 1;
     return cap;
 }
+
+// with g_cache_mutex held and `device` current
+hipEvent_t take_event(int device) {
+    for (size_t i = 0; i < g_events.size(); ++i) {
+        if (g_events[i].second == device) {
+            hipEvent_t e = g_events[i].first;
+            g_events.erase(g_events.begin() + (long)i);
+            return e;
+        }
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    return e;
+}
+
+void give_event(hipEvent_t e, int device) {
+    if (g_events.size() < kSpareEvents) {
+        try {
+            g_events.emplace_back(e, device);
+            return;
+        } catch (const std::bad_alloc &) {
+        }
+    }
+    (void)hipEventDestroy(e);
+}
+
+// a buffer nobody reads any more: keep it for the next plan, or free it if the cache is full
+void keep_or_free(const CachedBuffer &b) {
+    size_t held = 0;
+    for (const CachedBuffer &c : g_cache) held += c.capacity;
+    if (g_cache.size() < kCacheEntries && held + b.capacity <= kCacheBytes) {
+        try {
+            g_cache.push_back(b);
+            return;
+        } catch (const std::bad_alloc &) {
+        }
+    }
+    (void)hipFree(b.ptr);
+}
+
+// move the retired buffers whose events have all fired to the cache; `wait`: block for them
+void reap_retired(bool wait) {
+    for (size_t i = 0; i < g_retired.size();) {
+        RetiredBuffer &r = g_retired[i];
+        bool done = true;
+        for (hipEvent_t e : r.events) {
+            const hipError_t q = wait ? hipEventSynchronize(e) : hipEventQuery(e);
+            if (q == hipErrorNotReady) {
+                done = false;
+                break;
+            }
+            if (q != hipSuccess) (void)hipGetLastError();       // a broken event cannot hold the buffer for ever
+        }
+        if (!done) {
+            ++i;
+            continue;
+        }
+        for (hipEvent_t e : r.events) give_event(e, r.buf.device);
+        keep_or_free(r.buf);
+        g_retired.erase(g_retired.begin() + (long)i);
+    }
+}
 }  // namespace
+
+void note_stream(const kvl_plan_t *plan, hipStream_t stream) {
+    for (hipStream_t s : plan->used_streams)
+        if (s == stream) return;
+    if (plan->used_streams.size() >= kTrackedStreams) {
+        plan->used_streams_overflow = true;
+        return;
+    }
+    try {
+        plan->used_streams.push_back(stream);
+    } catch (const std::bad_alloc &) {
+        plan->used_streams_overflow = true;
+    }
+}
+
+hipStream_t take_pooled_lane(int device) {
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    for (size_t i = 0; i < g_lanes.size(); ++i) {
+        if (g_lanes[i].device == device) {
+            hipStream_t s = g_lanes[i].stream;
+            g_lanes.erase(g_lanes.begin() + (long)i);
+            return s;
+        }
+    }
+    return nullptr;
+}
+
+// A lane that is not needed any more; work may still be queued on it (it runs to its end there:
+// a lane is an in-order stream, and whoever takes it from the pool queues behind that work).
+void return_lane(hipStream_t lane, int device) {
+    {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        if (g_lanes.size() < kPooledLanes) {
+            try {
+                g_lanes.push_back(PooledLane{lane, device});
+                return;
+            } catch (const std::bad_alloc &) {
+            }
+        }
+    }
+    (void)hipStreamSynchronize(lane);
+    (void)hipStreamDestroy(lane);
+}
 
 static hipError_t descriptor_alloc(void **out, size_t bytes, size_t *capacity, int device) {
     const size_t want = round_capacity(bytes);
     {
         std::lock_guard<std::mutex> lock(g_cache_mutex);
+        reap_retired(false);
         for (size_t i = 0; i < g_cache.size(); ++i) {
             if (g_cache[i].device == device && g_cache[i].capacity == want) {
                 *out = g_cache[i].ptr;
@@ -82,28 +207,47 @@ static hipError_t descriptor_alloc(void **out, size_t bytes, size_t *capacity, i
     return hipMalloc(out, want);
 }
 
-static void descriptor_release(void *ptr, size_t capacity, int device) {
-    // A kernel that still reads these descriptors must not see the next plan's: wait for the
-    // device as the device free this replaces would have (it is idle if the caller has
-    // synchronised its streams, as it should).
-    int current = device;
+// The plan is going away: its descriptor array may be reused once every stream that ran its
+// kernels has got past them.
+static void descriptor_release(const kvl_plan_t *plan) {
+    int current = plan->device;
     (void)hipGetDevice(&current);
-    if (current != device) (void)hipSetDevice(device);
-    (void)hipDeviceSynchronize();
-    if (current != device) (void)hipSetDevice(current);
+    if (current != plan->device) (void)hipSetDevice(plan->device);
+    RetiredBuffer r{CachedBuffer{plan->d_units, plan->d_units_capacity, plan->device}, {}};
+    bool tracked = !plan->used_streams_overflow;
     {
         std::lock_guard<std::mutex> lock(g_cache_mutex);
-        size_t held = 0;
-        for (const CachedBuffer &b : g_cache) held += b.capacity;
-        if (g_cache.size() < kCacheEntries && held + capacity <= kCacheBytes) {
-            try {
-                g_cache.push_back(CachedBuffer{ptr, capacity, device});
-                return;
-            } catch (const std::bad_alloc &) {
+        try {
+            for (size_t i = 0; tracked && i < plan->used_streams.size(); ++i) {
+                hipEvent_t e = take_event(plan->device);
+                if (!e) {
+                    tracked = false;
+                    break;
+                }
+                r.events.push_back(e);
+                if (hipEventRecord(e, plan->used_streams[i]) != hipSuccess) {
+                    (void)hipGetLastError();        // e.g. a stream the caller has destroyed since
+                    tracked = false;
+                }
             }
+            if (tracked) {
+                g_retired.push_back(std::move(r));
+                r.events.clear();
+                r.buf.ptr = nullptr;
+            }
+        } catch (const std::bad_alloc &) {
+            tracked = false;
         }
+        if (!tracked)
+            for (hipEvent_t e : r.events) give_event(e, plan->device);
     }
-    (void)hipFree(ptr);
+    if (r.buf.ptr) {
+        // the streams could not be followed: fall back to what a device free would have done
+        (void)hipDeviceSynchronize();
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        keep_or_free(r.buf);
+    }
+    if (current != plan->device) (void)hipSetDevice(current);
 }
 
 int check_buffer(const kvl_plan_t *plan, const void *ptr, uint64_t bytes, bool allow_host) {
@@ -121,13 +265,50 @@ bool is_host_memory(const kvl_plan_t *plan, const void *ptr) {
     return a.type == hipMemoryTypeHost;
 }
 
+// Descriptors go up on a stream of the library's own, out of pinned memory, and the call waits
+// for that copy alone: a plain hipMemcpy would also wait for whatever the caller has running on
+// the default stream.
+namespace {
+struct Uploader {
+    hipStream_t stream = nullptr;
+    void *bounce = nullptr;         // pinned
+    size_t capacity = 0;
+};
+std::mutex g_upload_mutex;
+Uploader g_uploaders[64];
+constexpr size_t kBounceLimit = 64u << 20;      // larger descriptor arrays are copied from pageable memory
+}  // namespace
+
 int upload_units(kvl_plan_t *plan) {
     hipError_t e = hipGetDevice(&plan->device);
     if (e == hipSuccess && !plan->units.empty()) {
         const size_t bytes = plan->units.size() * sizeof(kvl_unit_t);
         e = descriptor_alloc((void **)&plan->d_units, bytes, &plan->d_units_capacity, plan->device);
-        if (e == hipSuccess)
+        if (e == hipSuccess && plan->device >= 0 && plan->device < 64) {
+            std::lock_guard<std::mutex> lock(g_upload_mutex);
+            Uploader &u = g_uploaders[plan->device];
+            if (!u.stream) e = hipStreamCreateWithFlags(&u.stream, hipStreamNonBlocking);
+            if (e == hipSuccess && bytes <= kBounceLimit && u.capacity < bytes) {
+                if (u.bounce) (void)hipHostFree(u.bounce);
+                u.bounce = nullptr;
+                u.capacity = 0;
+                size_t cap = 1u << 20;
+                while (cap < bytes) cap <<= 1;
+                if (hipHostMalloc(&u.bounce, cap, hipHostMallocDefault) == hipSuccess) u.capacity = cap;
+                else (void)hipGetLastError();       // no pinned memory to be had: copy from where the descriptors are
+            }
+            if (e == hipSuccess) {
+                const void *from = plan->units.data();
+                if (u.capacity >= bytes) {
+                    std::memcpy(u.bounce, plan->units.data(), bytes);
+                    from = u.bounce;
+                }
+                e = hipMemcpyAsync(plan->d_units, from, bytes, hipMemcpyHostToDevice, u.stream);
+                if (e == hipSuccess) e = hipStreamSynchronize(u.stream);
+            }
+        } else if (e == hipSuccess) {
             e = hipMemcpy(plan->d_units, plan->units.data(), bytes, hipMemcpyHostToDevice);
+        }
     }
     if (e != hipSuccess) {
         set_hip_error(e);
@@ -186,8 +367,18 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
     const bool merge = !(flags & KVL_NO_MERGE);
 
     try {
-        std::vector<uint8_t> taken;
-        if (scatter) taken.assign(layout->pool_blocks ? layout->pool_blocks : 1, 0);
+        // which destination blocks a scatter plan has named already: one array per thread, kept
+        // from plan to plan; an entry counts only if it carries this plan's stamp, so nothing is
+        // cleared between plans
+        static thread_local std::vector<uint32_t> taken;
+        static thread_local uint32_t stamp = 0;
+        if (scatter) {
+            if (taken.size() < layout->pool_blocks) taken.resize((size_t)layout->pool_blocks, 0);
+            if (++stamp == 0) {                     // the stamps have wrapped: start over
+                std::fill(taken.begin(), taken.end(), 0u);
+                stamp = 1;
+            }
+        }
 
         // token range of request q that this plan moves
         auto range = [flags](const kvl_request_t &q, uint64_t *t0, uint64_t *t1) {
@@ -235,9 +426,9 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
             const uint64_t b_first = t0 / bs, b_end = (t1 + bs - 1) / bs;   // blocks [b_first, b_end) are touched
             if (scatter) {
                 for (uint64_t b = b_first; b < b_end; ++b) {
-                    uint8_t &t = taken[(size_t)q.block_table[b]];
-                    if (t) { delete plan; return KVL_EALIAS; }
-                    t = 1;
+                    uint32_t &t = taken[(size_t)q.block_table[b]];
+                    if (t == stamp) { delete plan; return KVL_EALIAS; }
+                    t = stamp;
                 }
             }
             // rows of block b that lie in the range: [lo, hi) in request tokens
@@ -377,10 +568,16 @@ int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, ui
 
 void kvl_plan_destroy(kvl_plan_t *plan) {
     if (!plan) return;
-    if (plan->d_units) kvl::descriptor_release(plan->d_units, plan->d_units_capacity, plan->device);
+    if (plan->d_units) kvl::descriptor_release(plan);
     for (hipStream_t s : plan->lanes) {
-        (void)hipStreamSynchronize(s);
-        (void)hipStreamDestroy(s);
+        // the lanes' work on this plan has normally ended (the stream the caller waits on follows
+        // them); one that is still busy is waited for, it alone, since the plan's events go below
+        if (hipStreamQuery(s) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipStreamSynchronize(s);
+        }
+        if (plan->lane_cu_mask.empty()) kvl::return_lane(s, plan->device);
+        else (void)hipStreamDestroy(s);
     }
     for (hipEvent_t e : plan->ev_lane_done) (void)hipEventDestroy(e);
     if (plan->ev_entry) (void)hipEventDestroy(plan->ev_entry);
@@ -539,11 +736,21 @@ int kvl_check_buffer(const void *ptr, uint64_t bytes, int allow_host) {
 
 void kvl_release_cached_memory(void) {
     std::vector<kvl::CachedBuffer> drop;
+    std::vector<kvl::PooledLane> lanes;
+    std::vector<std::pair<hipEvent_t, int>> events;
     {
         std::lock_guard<std::mutex> lock(kvl::g_cache_mutex);
+        kvl::reap_retired(true);                    // waits for the kernels of destroyed plans, nothing else
         drop.swap(kvl::g_cache);
+        lanes.swap(kvl::g_lanes);
+        events.swap(kvl::g_events);
     }
     for (const kvl::CachedBuffer &b : drop) (void)hipFree(b.ptr);
+    for (const kvl::PooledLane &l : lanes) {
+        (void)hipStreamSynchronize(l.stream);
+        (void)hipStreamDestroy(l.stream);
+    }
+    for (const auto &e : events) (void)hipEventDestroy(e.first);
 }
 
 const char *kvl_strerror(int code) {
