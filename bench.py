@@ -1,7 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the layer-wise KV-cache load path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4]
+
+The default workload is the largest one that runs device-resident on one GPU (cfg4: 12.2 GB of
+cache per layer, 61 layers, 289,870 fully fragmented blocks); it is also the one whose kernels
+run furthest below the memory's peak.  Every other workload gets a short run with a roofline
+object of its own (`other_configs`).
 
 A step is one batch through the whole device-resident path: kvl_plan for the
 decode side and the prefill side, then for every layer kvl_pack_layer (paged
@@ -69,9 +74,18 @@ def measured_traffic(workload_index: int, kernel: str):
 
 def cpu_baseline(index: int, sample_requests: int) -> dict:
     """The oracle, as it stands, on a sample of the workload: one layer of the
-    first `sample_requests` requests, pack then unpack, on the host cores."""
+    first `sample_requests` requests, pack then unpack, on the host cores.
+    sample_requests == 0: as many of the first requests as keep the payload near 6 GB
+    (about 10-30 s of single-threaded work for two layers)."""
     import kvl_workloads as W
     import oracle
+    if not sample_requests:
+        full = W.config(index)
+        per_token = sum(full.layout.row_bytes)
+        csum = np.cumsum(full.hit.astype(np.int64)) * per_token
+        sample_requests = max(1, int(np.searchsorted(csum, 6.5e9)))
+        sample_requests = min(sample_requests, full.n_requests)
+        del full
     w = W.config(index, n_requests=sample_requests or None)
     sample_requests = w.n_requests
     bs, rows = w.layout.block_tokens, w.layout.row_bytes
@@ -104,12 +118,16 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOADS))
+    ap.add_argument("--config", type=int, default=4, choices=sorted(WORKLOADS))
     ap.add_argument("--skip-host-link", action="store_true", help="leave out the pinned-host legs")
     ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU-oracle baseline")
     ap.add_argument("--skip-other-configs", action="store_true", help="leave out the short runs of the other workloads")
     ap.add_argument("--stream-layers", type=int, default=0, help="layers of the streamed leg (0: all 61)")
-    ap.add_argument("--cpu-sample-requests", type=int, default=0, help="requests in the CPU sample (0: the whole batch)")
+    ap.add_argument("--cpu-sample-requests", type=int, default=0,
+                    help="requests in the CPU sample (0: the first requests up to about 6 GB of payload)")
+    ap.add_argument("--only-h2d-study", action="store_true",
+                    help="run the submission-cost study of the host-buffer path and print its table (Section 5.2)")
+    ap.add_argument("--skip-studies", action="store_true", help="leave out the ceilings and kernel-shape legs")
     ap.add_argument("--only-steps", action="store_true",
                     help="time the steps only: no tail-return, other-config, host-link or CPU legs (for profiler runs)")
     ap.add_argument("--only-host-link", action="store_true",
@@ -118,7 +136,7 @@ def main() -> int:
                     help="also launch one plain copy kernel of this size (a known-traffic reference for counter runs)")
     args = ap.parse_args()
     if args.only_steps:
-        args.skip_host_link = args.skip_cpu = args.skip_other_configs = True
+        args.skip_host_link = args.skip_cpu = args.skip_other_configs = args.skip_studies = True
     if args.gpus != 1:
         print("bench.py: the library runs on one GPU; --gpus must be 1 "
               "(the load path shards by request across GPUs without any collective)", file=sys.stderr)
@@ -135,6 +153,9 @@ def main() -> int:
     dev = torch.device("cuda:0")
     if args.only_host_link:
         print(json.dumps({"host_link": host_link_legs(args)}), flush=True)
+        return 0
+    if args.only_h2d_study:
+        h2d_study()
         return 0
 
     w = W.config(args.config)
@@ -225,15 +246,7 @@ def main() -> int:
     ceiling, runtime_copy = copy_ceiling(stream, args.calibration_copy_gib or 4.0)
 
     def roof(name, ms):
-        avg = float(ms.mean())
-        achieved = 2.0 * payload / (avg * 1e-3) / 1e9          # algorithmic bytes: row read + row written
-        return {"kernel": name, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": measured_traffic(args.config, name),
-                "frac_of_measured_linear_copy": round(achieved / ceiling, 4),
-                "algorithmic_bytes_per_launch": 2 * payload, "avg_launch_ms": round(avg, 4),
-                "median_launch_ms": round(float(np.median(ms)), 4),
-                "min_launch_ms": round(float(ms.min()), 4), "launches": int(ms.size)}
+        return roofline_object(args.config, name, ms, payload, ceiling)
 
     tail = None if args.only_steps else tail_return_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN)
     fused = None if args.only_steps else fused_move_leg(w, lay_src, lay_dst, src, dst, stream, L, WIN, payload)
@@ -264,8 +277,11 @@ def main() -> int:
     torch.cuda.empty_cache()
 
     if not args.skip_other_configs:
-        out["other_configs"] = {f"cfg{i}": short_hop(i, check=not args.skip_cpu)
+        out["other_configs"] = {f"cfg{i}": short_hop(i, check=not args.skip_cpu, linear_ceiling=ceiling)
                                 for i in sorted(WORKLOADS) if i != args.config}
+    if not args.skip_studies:
+        out["ceilings"] = ceilings_leg(stream, roof_pack, roof_unpack, args.config)
+        out["kernel_shapes"] = kernel_shapes_leg()
     if not args.skip_host_link:
         out["host_link"] = host_link_legs(args)
     if not args.only_steps:
@@ -275,6 +291,22 @@ def main() -> int:
         out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_sample_requests)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def roofline_object(config_index: int, kernel: str, ms, payload: int, linear_ceiling: float) -> dict:
+    """The roofline entry of one kernel on one workload: algorithmic bytes per launch (every
+    payload byte read once and written once) over the average launch time measured with HIP
+    events on the stream the kernel ran on."""
+    ms = np.asarray(ms, dtype=np.float64)
+    avg = float(ms.mean())
+    achieved = 2.0 * payload / (avg * 1e-3) / 1e9
+    return {"kernel": kernel, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": measured_traffic(config_index, kernel),
+            "frac_of_measured_linear_copy": round(achieved / linear_ceiling, 4) if linear_ceiling else None,
+            "algorithmic_bytes_per_launch": 2 * payload, "avg_launch_ms": round(avg, 4),
+            "median_launch_ms": round(float(np.median(ms)), 4),
+            "min_launch_ms": round(float(ms.min()), 4), "launches": int(ms.size)}
 
 
 def row_heads(host_planes, rows):
@@ -435,7 +467,7 @@ def copy_ceiling(stream, gib: float = 4.0):
     return best, runtime
 
 
-def short_hop(index: int, reps: int = 8, check: bool = True) -> dict:
+def short_hop(index: int, reps: int = 8, check: bool = True, linear_ceiling: float = 0.0) -> dict:
     """pack + unpack of one resident layer of another workload, timed per launch."""
     import torch
     import kvl_workloads as W
@@ -475,7 +507,9 @@ def short_hop(index: int, reps: int = 8, check: bool = True) -> dict:
            "pack_frac_of_hbm_peak": round(2 * payload / pm / 1e6 / HBM_PEAK_GBPS, 4),
            "unpack_frac_of_hbm_peak": round(2 * payload / um / 1e6 / HBM_PEAK_GBPS, 4),
            "tokens_layers_per_s": round(T / ((pm + um) * 1e-3), 1), "verified_rows_vs_oracle": verified,
-           "plan_ms": round(plan_ms, 3), "descriptors": g.n_units}
+           "plan_ms": round(plan_ms, 3), "descriptors": g.n_units,
+           "roofline": {"pack": roofline_object(index, "kvl_pack_tile_kernel", pk, payload, linear_ceiling),
+                        "unpack": roofline_object(index, "kvl_unpack_tile_kernel", up, payload, linear_ceiling)}}
     # pool to pool in one kernel (paired plan), after the hop above has been checked
     m = K.kvl_plan_pair(g, s)
     mv = []
@@ -825,6 +859,173 @@ def full_block_leg(pinned: "torch.Tensor", h2d_peak: float) -> dict:
     del a, b
     s.destroy()
     return out
+
+
+def _time_launches(fn, stream, reps: int = 8, warm: int = 2) -> float:
+    """Average duration in ms of `reps` launches of fn() on `stream` (HIP events on that stream)."""
+    import torch
+    ms = []
+    for i in range(reps + warm):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fn()
+        e1.record(stream)
+        e1.synchronize()
+        if i >= warm:
+            ms.append(e0.elapsed_time(e1))
+    return float(np.mean(ms))
+
+
+def ceilings_leg(stream, roof_pack: dict, roof_unpack: dict, config_index: int) -> dict:
+    """What the memory of this machine does on reference streams that use the load and store
+    instructions and cache policies of the default kernels but no descriptors: a linear copy and
+    its read and write halves alone (4 GiB), and a copy with the access shape of cfg4 -- one
+    side dense, the other hopping every 41,984 bytes to a pseudo-random block, the two sides 16
+    bytes apart in their 128-byte lines -- with the block's address computed, or read from a
+    4-byte table entry through the scalar cache as a descriptor is."""
+    import torch
+    import paper_2602_21548_amd as K
+    dev = torch.device("cuda:0")
+    out = {"unit": "GB/s of memory traffic (bytes read + bytes written)", "peak": HBM_PEAK_GBPS}
+    n = 4 << 30
+    a = torch.full((n + 128,), 1, dtype=torch.uint8, device=dev)
+    b = torch.empty(n, dtype=torch.uint8, device=dev)
+    lin = {}
+    for name, mode, factor in (("copy", K.KVL_CEILING_COPY, 2.0), ("read_only", K.KVL_CEILING_READ, 1.0),
+                               ("write_only", K.KVL_CEILING_WRITE, 1.0)):
+        ms = _time_launches(lambda: K.kvl_ceiling_kernel(mode, a, b, n, stream=stream), stream)
+        lin[name] = round(factor * n / ms / 1e6, 1)
+    ms = _time_launches(lambda: K.kvl_ceiling_kernel(K.KVL_CEILING_COPY, a, b, n, skew_bytes=16, stream=stream), stream)
+    lin["copy_source_16_bytes_off_its_lines"] = round(2.0 * n / ms / 1e6, 1)
+    r, w = lin["read_only"], lin["write_only"]
+    lin["harmonic_mean_of_read_and_write"] = round(2.0 / (1.0 / r + 1.0 / w), 1)
+    out["linear_4GiB"] = lin
+    del a, b
+    torch.cuda.empty_cache()
+    # the shape of cfg4: 2^18 blocks of 64 x 656 bytes, the hopping side holds 2^19
+    block, k_dense, k_hop, skew = 64 * 656, 18, 19, 16
+    payload = (1 << k_dense) * block
+    hop = torch.full(((1 << k_hop) * block,), 1, dtype=torch.uint8, device=dev)
+    dense = torch.full((payload + 128,), 2, dtype=torch.uint8, device=dev)
+    # the table holds the blocks the computed form would visit (u * odd constant mod 2^19)
+    table = ((torch.arange(1 << k_dense, dtype=torch.int64, device=dev) * 0x9e3779b1) & ((1 << k_hop) - 1)).to(torch.int32)
+    shape = {"block_bytes": block, "blocks": 1 << k_dense, "payload_bytes": payload, "skew_bytes": skew}
+    for side, name, src, dst in ((0, "gather", hop, dense), (1, "scatter", dense, hop)):
+        for tname, tab in (("computed_address", None), ("table_entry_per_block", table)):
+            ms = _time_launches(lambda: K.kvl_ceiling_kernel(K.KVL_CEILING_COPY, src, dst, payload, block_bytes=block,
+                                                             hopping_side=side, skew_bytes=skew, hop_blocks_log2=k_hop,
+                                                             block_table=tab, stream=stream), stream)
+            shape[f"{name}_{tname}"] = round(2.0 * payload / ms / 1e6, 1)
+    out["shape_of_cfg4"] = shape
+    if config_index == 4:
+        best_g = max(shape["gather_computed_address"], shape["gather_table_entry_per_block"])
+        best_s = max(shape["scatter_computed_address"], shape["scatter_table_entry_per_block"])
+        out["library_over_shape_ceiling"] = {"pack": round(roof_pack["achieved"] / best_g, 4),
+                                             "unpack": round(roof_unpack["achieved"] / best_s, 4)}
+    del hop, dense, table
+    torch.cuda.empty_cache()
+    return out
+
+
+def kernel_shapes_leg(index: int = 3) -> dict:
+    """The kernel forms the library holds, on one layer of cfg3: the default (tiled, one vector
+    per lane, one-shot workgroups) against one wavefront per descriptor looping over it, one
+    workgroup per descriptor, two vectors per lane, and the pipelined walk on a fixed grid."""
+    import torch
+    import kvl_workloads as W
+    import paper_2602_21548_amd as K
+    dev = torch.device("cuda:0")
+    w = W.config(index)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    src = [torch.full((w.src.pool_blocks * bs * r,), 3, dtype=torch.uint8, device=dev) for r in rows]
+    dst = [torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device=dev) for r in rows]
+    g = K.kvl_plan(K.make_layout(1, bs, rows, w.src.pool_blocks), w.hit, w.app, w.src.tables, K.KVL_GATHER)
+    s = K.kvl_plan(K.make_layout(1, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables, K.KVL_SCATTER)
+    n = g.payload_bytes
+    x = torch.empty(n, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.Stream()
+    # (name, pack variant, unpack variant): the cache policies are those of the default throughout
+    forms = [("default: tiled, one vector per lane", 0, 0),
+             ("one wavefront per descriptor, 4 vectors in flight per lane", 22, 30),
+             ("one wavefront per descriptor, 8 vectors in flight per lane", 54, 62),
+             ("one workgroup per descriptor, 4 vectors in flight per lane", 21, 29),
+             ("tiled, two vectors per lane", 24, 32),
+             ("pipelined walk on a fixed grid of resident workgroups", 279, 287)]
+    out = {"workload": WORKLOADS[index], "unit": "GB/s of memory traffic", "forms": []}
+    for name, vp, vu in forms:
+        g.set_tuning(variant=vp)
+        s.set_tuning(variant=vu)
+        pk = _time_launches(lambda: K.kvl_pack_layer(g, src, x, stream=stream), stream, reps=6)
+        up = _time_launches(lambda: K.kvl_unpack_layer(s, x, dst, stream=stream), stream, reps=6)
+        out["forms"].append({"form": name, "pack_variant": K.kvl_variant_name(vp), "unpack_variant": K.kvl_variant_name(vu),
+                             "pack": round(2.0 * n / pk / 1e6, 1), "unpack": round(2.0 * n / up / 1e6, 1)})
+    g.destroy()
+    s.destroy()
+    del src, dst, x
+    torch.cuda.empty_cache()
+    return out
+
+
+def h2d_study(requests: int = 0) -> None:
+    """Submission-cost study of the host-buffer load path (Section 5.2 of the paper observes that a
+    copy engine fed many small copies is bound by the per-copy submission cost: 5-7 us per copy on
+    its hardware).  Prints what the same question looks like here for one layer of the streamed MLA
+    workload: one copy per Layer Block, chunked copies through a staging ring at several chunk
+    sizes, and the scatter kernel reading the pinned buffer itself."""
+    import torch
+    import kvl_workloads as W
+    import paper_2602_21548_amd as K
+    dev = torch.device("cuda:0")
+    w = W.config(5, n_requests=requests or None)
+    L, bs, rows = w.layout.n_layers, w.layout.block_tokens, w.layout.row_bytes
+    lay = K.make_layout(L, bs, rows, w.dst.pool_blocks)
+    plan = K.kvl_plan(lay, w.hit, w.app, w.dst.tables, K.KVL_SCATTER)
+    n = plan.payload_bytes
+    host = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+    host.numpy()[:] = 7
+    pool = [torch.full((w.dst.pool_blocks * bs * r,), 0xA5, dtype=torch.uint8, device=dev) for r in rows]
+    cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+    big = torch.empty(min(n, 1 << 30), dtype=torch.uint8, device=dev)
+    peak = K.kvl_measure_h2d_peak(host[:big.numel()], big, reps=5, stream=cs)
+    del big
+    print(f"workload: one layer of {w.name}, {w.n_requests} requests, {n / 1e9:.3f} GB payload, "
+          f"{plan.n_units} Layer-Block descriptors of up to {bs * rows[0]} bytes")
+    print(f"host link peak (1 GiB pinned hipMemcpyAsync): {peak:.2f} GB/s\n")
+    print(f"{'method':44s} {'copies':>8s} {'GB/s':>8s} {'of peak':>8s} {'enqueue us/copy':>16s}")
+
+    def timed(fn, streams):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        copies = fn()
+        t1 = time.perf_counter()
+        for st in streams:
+            st.synchronize()
+        t2 = time.perf_counter()
+        return copies, n / (t2 - t0) / 1e9, (t1 - t0) * 1e6 / max(1, copies)
+
+    best = None
+    for _ in range(2):
+        best = timed(lambda: K.kvl_h2d_blockwise_layer(plan, host, pool, stream=cs), [cs])
+    c, gb, us = best
+    print(f"{'one hipMemcpyAsync per Layer Block':44s} {c:8d} {gb:8.2f} {gb / peak:8.1%} {us:16.2f}")
+    for mb in (1, 2, 4, 8, 16, 32, 64, 128, 256):
+        chunk = mb << 20
+        if chunk < bs * max(rows):
+            continue
+        staging = torch.empty(4 * chunk, dtype=torch.uint8, device=dev)
+        copies = len(plan.chunks(chunk))
+        res = None
+        for _ in range(2):
+            res = timed(lambda: (K.kvl_h2d_unpack_layer(plan, host, staging, chunk, pool, cs, ks), copies)[1], [ks, cs])
+        c, gb, us = res
+        print(f"{'staging ring, chunk ' + str(mb) + ' MiB x 4 slots':44s} {c:8d} {gb:8.2f} {gb / peak:8.1%} {us:16.2f}")
+        del staging
+    res = None
+    for _ in range(2):
+        res = timed(lambda: (K.kvl_unpack_layer(plan, host, pool, stream=ks), 1)[1], [ks])
+    c, gb, us = res
+    print(f"{'scatter kernel reads pinned memory (0 copies)':44s} {0:8d} {gb:8.2f} {gb / peak:8.1%} {us:16.2f}")
+    plan.destroy()
 
 
 if __name__ == "__main__":
