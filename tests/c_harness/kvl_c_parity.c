@@ -7,7 +7,10 @@
  * its own size, the entry points' buffer checks are exercised at their edges: a
  * pool one block short and a transfer buffer shorter than its stated capacity
  * must come back as KVL_ESPACE, pageable host memory as KVL_EINVAL, and none
- * of them may launch anything.
+ * of them may launch anything.  Then the other calls of the boundary: the
+ * host-buffer load, the appended tail's way back, a layer out of Full Blocks in
+ * pinned memory, and three layers streamed into two resident slots (staged and
+ * zero-copy), each against the oracle.
  *
  * Prints one line per check and "c parity ok" at the end; exit status 0 only
  * if every check passed.
@@ -39,6 +42,17 @@ int kvo_unpack(uint32_t bs, uint32_t n_planes, const uint32_t *row_bytes, uint32
                const int32_t *const *tables, const uint8_t *xfer, uint8_t *const *pool_planes,
                uint32_t r_begin, uint32_t r_end);
 uint64_t kvo_payload_bytes(uint32_t n_req, const uint32_t *hit, uint32_t n_planes, const uint32_t *row_bytes);
+int kvo_pack_range(uint32_t bs, uint32_t n_planes, const uint32_t *row_bytes, uint32_t n_req, const uint32_t *first,
+                   const uint32_t *count, const int32_t *const *tables, const uint8_t *const *pool_planes,
+                   uint8_t *xfer, uint32_t r_begin, uint32_t r_end);
+int kvo_unpack_range(uint32_t bs, uint32_t n_planes, const uint32_t *row_bytes, uint32_t n_req, const uint32_t *first,
+                     const uint32_t *count, const int32_t *const *tables, const uint8_t *xfer,
+                     uint8_t *const *pool_planes, uint32_t r_begin, uint32_t r_end);
+uint64_t kvo_fullblock_bytes(uint32_t bs, uint32_t n_layers, uint32_t n_planes, const uint32_t *row_bytes);
+uint64_t kvo_fullblock_count(uint32_t bs, uint32_t n_req, const uint32_t *first, const uint32_t *count);
+int kvo_fullblocks_to_pool(uint32_t bs, uint32_t n_layers, uint32_t n_planes, const uint32_t *row_bytes, uint32_t n_req,
+                           const uint32_t *first, const uint32_t *count, const int32_t *const *tables, uint32_t layer,
+                           const uint8_t *blocks, uint8_t *const *pool_planes);
 
 #define HIP_OK(call)                                                                      \
     do {                                                                                  \
@@ -67,6 +81,18 @@ static uint64_t rnd(void) {
 }
 
 enum { R = 5, BS = 16, P = 2, POOL_BLOCKS = 96 };
+
+/* kvl_stream_layers' host_fill: the storage read of layer `layer` delivers its bytes here */
+struct fill_ctx {
+    uint8_t *const *layer_payload;
+    int calls;
+};
+static int fill_layer(void *user, uint32_t layer, void *host_slot, uint64_t bytes) {
+    struct fill_ctx *c = (struct fill_ctx *)user;
+    memcpy(host_slot, c->layer_payload[layer], bytes);
+    c->calls++;
+    return 0;
+}
 
 static double now_ms(void) {
     struct timespec t;
@@ -334,6 +360,154 @@ int main(int argc, char **argv) {
     if (refused != KVL_OK)
         expect(kvl_h2d_unpack_layer(s, pinned, d_stage, 4 * chunk, chunk, d_dst, cs, ks), KVL_ESPACE,
                "host-buffer load with a staging area stated larger than its allocation");
+
+    /* --- the appended tail goes back (Section 4.1: only the miss tokens' cache returns to the decode
+     * engine, where it is merged with the hit tokens' cache): gather rows [hit, hit + app) from the
+     * pool just loaded, scatter them into a copy of the source pool --- */
+    {
+        kvl_plan_t *ga = NULL, *sa = NULL;
+        expect(kvl_plan(&lay, dst_req, R, KVL_GATHER | KVL_TOKENS_APPEND, &ga), KVL_OK, "kvl_plan (gather, appended tail)");
+        expect(kvl_plan(&lay, src_req, R, KVL_SCATTER | KVL_TOKENS_APPEND, &sa), KVL_OK, "kvl_plan (scatter, appended tail)");
+        const uint64_t tail_bytes = kvo_payload_bytes(R, app, P, rows);
+        uint64_t lib_tail = 0;
+        kvl_plan_payload_bytes(ga, &lib_tail);
+        expect(lib_tail == tail_bytes, 1, "tail payload bytes equal the oracle's");
+        uint8_t *want_tail = malloc(tail_bytes), *got_tail = malloc(tail_bytes);
+        uint8_t *h_back_want[P], *h_back[P];
+        void *d_back[P], *d_tail = NULL;
+        HIP_OK(hipMalloc(&d_tail, tail_bytes));
+        for (int p = 0; p < P; ++p) {
+            h_back_want[p] = malloc(plane_bytes[p]);
+            h_back[p] = malloc(plane_bytes[p]);
+            memcpy(h_back_want[p], h_src[p], plane_bytes[p]);
+            HIP_OK(hipMalloc(&d_back[p], plane_bytes[p]));
+            HIP_OK(hipMemcpy(d_back[p], h_src[p], plane_bytes[p], hipMemcpyHostToDevice));
+        }
+        if (kvo_pack_range(BS, P, rows, R, hit, app, dst_tabs, (const uint8_t *const *)h_dst_want, want_tail, 0, R) != 0) return 2;
+        if (kvo_unpack_range(BS, P, rows, R, hit, app, src_tabs, want_tail, h_back_want, 0, R) != 0) return 2;
+        expect(kvl_pack_layer(ga, (const void *const *)d_dst, d_tail, tail_bytes, ks), KVL_OK, "kvl_pack_layer (appended tail)");
+        expect(kvl_unpack_layer(sa, d_tail, tail_bytes, d_back, ks), KVL_OK, "kvl_unpack_layer (appended tail)");
+        HIP_OK(hipStreamSynchronize(ks));
+        HIP_OK(hipMemcpy(got_tail, d_tail, tail_bytes, hipMemcpyDeviceToHost));
+        expect(memcmp(got_tail, want_tail, tail_bytes) == 0, 1, "tail transfer buffer equals the oracle's");
+        for (int p = 0; p < P; ++p) {
+            HIP_OK(hipMemcpy(h_back[p], d_back[p], plane_bytes[p], hipMemcpyDeviceToHost));
+            expect(memcmp(h_back[p], h_back_want[p], plane_bytes[p]) == 0, 1, "pool plane after the tail was merged in");
+            HIP_OK(hipFree(d_back[p]));
+            free(h_back[p]); free(h_back_want[p]);
+        }
+        HIP_OK(hipFree(d_tail));
+        free(want_tail); free(got_tail);
+        kvl_plan_destroy(ga);
+        kvl_plan_destroy(sa);
+    }
+
+    /* --- storage layout (Appendix A.5): layer 1 of 3-layer Full Blocks in pinned host memory -> pool --- */
+    {
+        enum { LFB = 3 };
+        kvl_layout_t lay3 = lay;
+        lay3.n_layers = LFB;
+        kvl_plan_t *sf = NULL;
+        expect(kvl_plan(&lay3, dst_req, R, KVL_SCATTER | KVL_NO_MERGE, &sf), KVL_OK, "kvl_plan (scatter, one descriptor per block)");
+        uint64_t fb = 0, nfb = 0;
+        expect(kvl_plan_fullblock_geometry(sf, &fb, &nfb), KVL_OK, "kvl_plan_fullblock_geometry");
+        expect(fb == kvo_fullblock_bytes(BS, LFB, P, rows) && nfb == kvo_fullblock_count(BS, R, NULL, hit), 1,
+               "Full-Block size and count equal the oracle's");
+        void *blocks = NULL;
+        HIP_OK(hipHostMalloc(&blocks, fb * nfb, hipHostMallocDefault));
+        for (uint64_t i = 0; i < fb * nfb; ++i) ((uint8_t *)blocks)[i] = (uint8_t)rnd();
+        uint8_t *h_fb_want[P];
+        for (int p = 0; p < P; ++p) {
+            h_fb_want[p] = malloc(plane_bytes[p]);
+            memset(h_fb_want[p], 0xA5, plane_bytes[p]);
+            HIP_OK(hipMemset(d_dst[p], 0xA5, plane_bytes[p]));
+        }
+        if (kvo_fullblocks_to_pool(BS, LFB, P, rows, R, NULL, hit, dst_tabs, 1, blocks, h_fb_want) != 0) return 2;
+        expect(kvl_fullblocks_to_pool_layer(sf, blocks, fb * nfb, 1, d_dst, ks), KVL_OK, "kvl_fullblocks_to_pool_layer (pinned buffer)");
+        HIP_OK(hipStreamSynchronize(ks));
+        for (int p = 0; p < P; ++p) {
+            HIP_OK(hipMemcpy(h_dst[p], d_dst[p], plane_bytes[p], hipMemcpyDeviceToHost));
+            expect(memcmp(h_dst[p], h_fb_want[p], plane_bytes[p]) == 0, 1, "pool plane after the Full-Block load");
+            free(h_fb_want[p]);
+        }
+        expect(kvl_fullblocks_to_pool_layer(sf, blocks, fb * nfb - 1, 1, d_dst, ks), KVL_ESPACE, "Full-Block buffer stated one byte short");
+        expect(kvl_fullblocks_to_pool_layer(sf, blocks, fb * nfb, LFB, d_dst, ks), KVL_EINVAL, "Full-Block load of a layer that does not exist");
+        kvl_plan_destroy(sf);
+        HIP_OK(hipHostFree(blocks));
+    }
+
+    /* --- kvl_stream_layers: 3 layers through 2 host buffers into 2 resident slots, under 50 us of
+     * compute each; what every layer's compute saw is kept and compared with the oracle's slot --- */
+    {
+        enum { LS = 3, S = 2, H = 2 };
+        uint8_t *layer_payload[LS];
+        for (int l = 0; l < LS; ++l) {
+            layer_payload[l] = malloc(payload);
+            for (uint64_t i = 0; i < payload; ++i) layer_payload[l][i] = (uint8_t)rnd();
+        }
+        void *host_slots[H], *slot_planes[S * P], *snap[LS * P];
+        uint8_t *h_slot[S][P], *h_seen[LS][P];
+        hipStream_t ms;
+        HIP_OK(hipStreamCreateWithFlags(&ms, hipStreamNonBlocking));
+        for (int h = 0; h < H; ++h) HIP_OK(hipHostMalloc(&host_slots[h], payload, hipHostMallocDefault));
+        for (int sl = 0; sl < S; ++sl)
+            for (int p = 0; p < P; ++p) HIP_OK(hipMalloc(&slot_planes[sl * P + p], plane_bytes[p]));
+        for (int l = 0; l < LS; ++l)
+            for (int p = 0; p < P; ++p) {
+                HIP_OK(hipMalloc(&snap[l * P + p], plane_bytes[p]));
+                h_seen[l][p] = malloc(plane_bytes[p]);
+            }
+        for (int form = 0; form < 2; ++form) {            /* staged, then zero-copy */
+            for (int sl = 0; sl < S; ++sl)
+                for (int p = 0; p < P; ++p) {
+                    HIP_OK(hipMemset(slot_planes[sl * P + p], 0xA5, plane_bytes[p]));
+                    if (form == 0) h_slot[sl][p] = malloc(plane_bytes[p]);
+                    memset(h_slot[sl][p], 0xA5, plane_bytes[p]);
+                }
+            /* the oracle: layer l is unpacked into slot l mod S; that slot is what its compute sees */
+            for (int l = 0; l < LS; ++l) {
+                if (kvo_unpack(BS, P, rows, R, hit, dst_tabs, layer_payload[l], h_slot[l % S], 0, R) != 0) return 2;
+                for (int p = 0; p < P; ++p) memcpy(h_seen[l][p], h_slot[l % S][p], plane_bytes[p]);
+            }
+            struct fill_ctx ctx = {layer_payload, 0};
+            kvl_stream_cfg_t cfg;
+            memset(&cfg, 0, sizeof cfg);
+            cfg.n_layers = LS;
+            cfg.n_host_slots = H;
+            cfg.host_layers = host_slots;
+            cfg.n_dev_slots = S;
+            cfg.dev_slot_planes = slot_planes;
+            cfg.dev_staging = form == 0 ? d_stage : NULL;
+            cfg.staging_bytes = form == 0 ? stage_bytes : 0;
+            cfg.chunk_bytes = form == 0 ? chunk : 0;
+            cfg.compute_us = 50;
+            cfg.snapshot_planes = snap;
+            cfg.host_fill = fill_layer;
+            cfg.host_fill_user = &ctx;
+            cfg.copy_stream = cs;
+            cfg.kernel_stream = ks;
+            cfg.compute_stream = ms;
+            kvl_stream_stats_t st;
+            memset(&st, 0, sizeof st);
+            expect(kvl_stream_layers(s, &cfg, &st), KVL_OK,
+                   form == 0 ? "kvl_stream_layers (staged, 2 slots)" : "kvl_stream_layers (zero-copy, 2 slots)");
+            expect(ctx.calls == LS, 1, "host_fill called once per layer");
+            expect(st.total_ms >= LS * 0.05 && st.h2d_bytes == (double)payload * LS, 1, "stream statistics");
+            for (int l = 0; l < LS; ++l)
+                for (int p = 0; p < P; ++p) {
+                    HIP_OK(hipMemcpy(h_dst[p], snap[l * P + p], plane_bytes[p], hipMemcpyDeviceToHost));
+                    expect(memcmp(h_dst[p], h_seen[l][p], plane_bytes[p]) == 0, 1, "slot as the layer's compute saw it equals the oracle's");
+                }
+        }
+        for (int l = 0; l < LS; ++l) {
+            free(layer_payload[l]);
+            for (int p = 0; p < P; ++p) { HIP_OK(hipFree(snap[l * P + p])); free(h_seen[l][p]); }
+        }
+        for (int sl = 0; sl < S; ++sl)
+            for (int p = 0; p < P; ++p) { HIP_OK(hipFree(slot_planes[sl * P + p])); free(h_slot[sl][p]); }
+        for (int h = 0; h < H; ++h) HIP_OK(hipHostFree(host_slots[h]));
+        HIP_OK(hipStreamDestroy(ms));
+    }
 
     kvl_plan_destroy(g);
     kvl_plan_destroy(s);

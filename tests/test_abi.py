@@ -41,7 +41,8 @@ def test_strerror_and_versions():
         assert K.kvl_strerror(code) not in ("ok", "unknown kvl error")
     assert K.kvl_strerror(-99) == "unknown kvl error"
     assert "gfx950" in K.kvl_version()
-    assert K.kvl_variant_name(0) == "default" and K.kvl_variant_name(128) and K.kvl_variant_name(256).startswith("flat") and K.kvl_variant_name(257) is None
+    assert K.kvl_variant_name(0) == "default" and K.kvl_variant_name(128) and K.kvl_variant_name(256).startswith("flat")
+    assert K.kvl_variant_name(257).startswith("pipe") and K.kvl_variant_name(512) and K.kvl_variant_name(513) is None
 
 
 def test_struct_sizes_match_the_header():

@@ -234,10 +234,15 @@ def test_full_size_streamed_layers():
     chunk = 128 << 20
     staging = torch.empty(4 * chunk, dtype=torch.uint8, device="cuda")
     probe_out = torch.zeros(L * len(probes) * 16, dtype=torch.uint8, device="cuda")
+    # two layers from the middle of the run are kept whole, every byte of the slot as their compute saw it
+    whole_layers = [L // 3, (2 * L) // 3 + 1]
+    snaps = [[torch.empty(pool_rows * row, dtype=torch.uint8, device="cuda")] if l in whole_layers else None
+             for l in range(L)]
     cs, ks, ms = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
     st = K.kvl_stream_layers(s, host, slots, staging, chunk, w.notes["compute_us"], cs, ks, ms,
-                             probes=probes, probe_out=probe_out, host_fill=fill, per_layer_times=True)
+                             probes=probes, probe_out=probe_out, host_fill=fill, per_layer_times=True,
+                             snapshots=snaps)
     print(f"[cfg5] streamed {L} layers in {st['total_ms']:.0f} ms ({st['link_gbps']:.1f} GB/s) "
           f"after {time.perf_counter() - t0:.1f} s", flush=True)
     got = to_host(probe_out).reshape(L, len(probes), 16)
@@ -263,6 +268,31 @@ def test_full_size_streamed_layers():
     assert np.all(tb >= tl - 1e-3) and np.all(te - tb >= 0.18) and np.all(np.diff(tb) > 0)
     # load of layer l + S does not finish before compute of layer l has ended
     assert np.all(tl[S:] >= te[:-S] - 1e-3)
+    # The whole slot of two middle layers.  The oracle, run once more on 16-byte rows, says which
+    # host row (layer, g) every pool row must hold; the bytes after a row's head are the host
+    # buffer's, which is the repeated tile whatever the layer.  Rows are compared in slices.
+    gen = oracle.stream_layers(bs, (16,), w.hit, w.dst.tables, o_host, max(whole_layers) + 1,
+                               [[np.full(pool_rows * 16, 0xA5, dtype=np.uint8)] for _ in range(S)])
+    for l in range(max(whole_layers) + 1):
+        o_host[l % H][:] = tags_of(l).view(np.uint8).reshape(-1)
+        _, _, planes = next(gen)
+        if l not in whole_layers:
+            continue
+        heads = planes[0].reshape(pool_rows, 16)
+        got = to_host(snaps[l][0]).reshape(pool_rows, row)
+        assert same_bytes(np.ascontiguousarray(got[:, :16]).reshape(-1), planes[0]), f"layer {l}: row heads"
+        empty = np.all(heads == 0xA5, axis=1)
+        assert np.all(heads[~empty].view(np.uint64).reshape(-1, 2)[:, 0] == l)
+        gi = heads.view(np.uint64).reshape(pool_rows, 2)[:, 1]
+        step = 1 << 18
+        for lo in range(0, pool_rows, step):
+            hi = min(pool_rows, lo + step)
+            e = empty[lo:hi]
+            blk = got[lo:hi]
+            assert np.all(blk[e] == 0xA5), f"layer {l}: a row without a hit token was written"
+            pos = gi[lo:hi][~e].astype(np.int64)[:, None] * row + np.arange(16, row, dtype=np.int64)[None, :]
+            assert np.array_equal(blk[~e][:, 16:], tile[pos % tile.size]), f"layer {l}: rows {lo}..{hi}"
+    print(f"[cfg5] layers {whole_layers} compared whole after {time.perf_counter() - t0:.1f} s", flush=True)
     s.destroy()
 
 

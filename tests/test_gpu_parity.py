@@ -109,7 +109,11 @@ def test_token_ranges(name, make, flag):
     run_range_hop(w, flag, unit_bytes=2048, variant=2)
 
 
-@pytest.mark.parametrize("variant", list(range(129)) + [1 + (128 | n << 2 | sp << 3) for n in (0, 1) for sp in range(4)])
+PIPE_VARIANTS = [1 + (256 | 2 | n << 2 | sp << 3 | na << 6) for n in (0, 1) for sp in range(4) for na in (0, 1)]
+
+
+@pytest.mark.parametrize("variant", list(range(129)) + [1 + (128 | n << 2 | sp << 3) for n in (0, 1) for sp in range(4)]
+                         + PIPE_VARIANTS)
 @pytest.mark.parametrize("threads", [64, 256, 1024])
 def test_every_variant(variant, threads):
     # units of 5 KiB against 64..1024 threads x 4..8 vectors: full steps, ragged tails and idle lanes
@@ -759,6 +763,161 @@ def test_fused_move_equals_pack_then_unpack(name, make):
     with pytest.raises(K.KvlError) as e:
         K.kvl_pack_layer(m, d_src, x)             # a paired plan only moves
     assert e.value.code == K.KVL_EINVAL
+
+
+@pytest.mark.parametrize("name,make", [c for c in CASES if c[0] in ("tiny-random", "tiny-3planes", "cfg1", "cfg2-small",
+                                                                     "cfg4-small", "trace32k-6req")],
+                         ids=lambda v: v if isinstance(v, str) else "")
+def test_pipelined_walk_on_every_kind_of_batch(name, make):
+    """The pipelined form has a main loop over the trips every workgroup shares and a tail of up
+    to three tiles: batches of a few tiles (no loop at all), of a few trips, ragged descriptors,
+    several planes, 656-byte rows (aligned first tiles)."""
+    w = make()
+    for threads in (64, 256):
+        run_hop(w, variant=PIPE_VARIANTS[5], block_threads=threads)
+        run_hop(w, variant=PIPE_VARIANTS[-1], block_threads=threads, max_groups=3)    # three workgroups walk it all
+        run_hop(w, variant=PIPE_VARIANTS[2], block_threads=threads, unit_bytes=4096, max_groups=7)
+
+
+def test_flat_kernel_split_over_several_launches():
+    """Token-granular pools: the flat kernel numbers its lanes with 32 bits and spreads the
+    descriptors over several launches when they would not fit.  max_groups lowers the
+    workgroups per launch, so that a small batch takes the same path: 3 and more launches,
+    the last one ragged."""
+    for make in (lambda: W.tiny(215, 9, 1, (1152,), 3000, 300),
+                 lambda: W.tiny(216, 7, 2, (256, 64), 2000, 250, kind="fragmented")):
+        w = make()
+        g = dev_plan(w, "src", K.KVL_GATHER)
+        n_units = g.n_units
+        g.destroy()
+        vecs = max(w.layout.row_bytes) // 16 * w.layout.block_tokens          # lanes per descriptor
+        for launches in (3, 7):
+            per_launch = -(-n_units // launches)                               # descriptors per launch
+            groups = max(1, per_launch * vecs // 256)
+            assert -(-n_units // max(1, groups * 256 // vecs)) >= launches
+            run_hop(w, max_groups=groups)                                      # default (flat) kernels, capped
+            run_hop(w, variant=1 + (128 | 4 | 8), max_groups=groups)           # an explicit flat variant
+
+
+def test_destroying_a_plan_does_not_wait_for_the_device():
+    """kvl_plan_destroy retires the descriptor array behind events instead of synchronising: it
+    returns at once while another stream is busy for a long time, and the array is not handed to
+    the next plan while a kernel of the destroyed one has yet to run."""
+    import time
+    w = W.config(3, n_requests=12, token_scale=1 / 16)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    src = W.fill_pool(w, 0, "src")
+    want_x = oracle.pack(bs, rows, w.hit, w.src.tables, src, threads=8)
+    d_src = planes_to_dev(src)
+    busy, side = torch.cuda.Stream(), torch.cuda.Stream()
+    # a kernel that spins for about 0.2 s: the counter torch's _sleep reads ticks at a rate found by trying
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda._sleep(1000)
+    torch.cuda.synchronize()
+    e0.record()
+    torch.cuda._sleep(1_000_000)
+    e1.record()
+    e1.synchronize()
+    spin_cycles = int(1_000_000 * 200.0 / max(e0.elapsed_time(e1), 1e-3))
+    K.kvl_release_cached_memory()
+    # (1) a long kernel on another stream: destroy returns while it is still running
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    x = torch.zeros(g.payload_bytes, dtype=torch.uint8, device="cuda")
+    K.kvl_pack_layer(g, d_src, x, stream=side)
+    side.synchronize()
+    done = torch.cuda.Event()
+    with torch.cuda.stream(busy):
+        torch.cuda._sleep(spin_cycles)
+        done.record(busy)
+    t0 = time.perf_counter()
+    g.destroy()
+    dt = time.perf_counter() - t0
+    still_running = not done.query()
+    assert still_running, "the spinning kernel ended before the check: make it longer"
+    assert dt < 5e-3, f"kvl_plan_destroy took {dt * 1e3:.1f} ms beside a busy stream"
+    assert same_bytes(to_host(x), want_x)
+    # (2) the plan's own kernel is still queued behind a long one when the plan goes; plans made
+    # right after must not get its descriptor array (their descriptors differ)
+    g = dev_plan(w, "src", K.KVL_GATHER)
+    x.zero_()
+    with torch.cuda.stream(side):
+        torch.cuda._sleep(spin_cycles)
+    K.kvl_pack_layer(g, d_src, x, stream=side)
+    g.destroy()
+    other = W.config(3, n_requests=12, token_scale=1 / 16)
+    other.src.tables = [t[::-1].copy() for t in other.src.tables]       # same sizes, other descriptors
+    plans = [dev_plan(other, "src", K.KVL_GATHER) for _ in range(4)]
+    y = torch.zeros_like(x)
+    K.kvl_pack_layer(plans[0], d_src, y, stream=busy)
+    torch.cuda.synchronize()
+    assert same_bytes(to_host(x), want_x), "a retired descriptor array was reused before its kernel had run"
+    want_y = oracle.pack(bs, rows, other.hit, other.src.tables, src, threads=8)
+    assert same_bytes(to_host(y), want_y)
+    for p in plans:
+        p.destroy()
+    # (3) once the work is done the array does come back: no device memory is lost over many plans
+    torch.cuda.synchronize()
+    K.kvl_release_cached_memory()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(200):
+        p = dev_plan(w, "src", K.KVL_GATHER)
+        K.kvl_pack_layer(p, d_src, x, stream=side)
+        p.destroy()                                                 # no synchronisation in between
+    torch.cuda.synchronize()
+    K.kvl_release_cached_memory()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < (8 << 20), f"{(free0 - free1) >> 20} MiB of device memory gone"
+
+
+def test_ceiling_kernels_stay_inside_their_buffers():
+    """The reference streams of the benchmark: the copy modes move what they say, and nothing is
+    written outside the bytes they were given."""
+    block, k_dense, k_hop, skew = 64 * 656, 6, 7, 16
+    payload = (1 << k_dense) * block
+    guard = 4096
+    hop = torch.randint(0, 255, ((1 << k_hop) * block + guard,), dtype=torch.uint8, device="cuda")
+    dense = torch.full((payload + 128 + guard,), 0x3C, dtype=torch.uint8, device="cuda")
+    hop0 = hop.clone()
+    table = ((torch.arange(1 << k_dense, dtype=torch.int64, device="cuda") * 0x9e3779b1) & ((1 << k_hop) - 1)).to(torch.int32)
+    for tab in (None, table):
+        dense.fill_(0x3C)
+        K.kvl_ceiling_kernel(K.KVL_CEILING_COPY, hop[:(1 << k_hop) * block], dense[:payload + 128], payload,
+                             block_bytes=block, hopping_side=0, skew_bytes=skew, hop_blocks_log2=k_hop, block_table=tab)
+        torch.cuda.synchronize()
+        got = to_host(dense)
+        h = to_host(hop0)
+        assert np.all(got[:skew] == 0x3C) and np.all(got[skew + payload:] == 0x3C)
+        for u in (0, 1, 17, (1 << k_dense) - 1):
+            b = (u * 0x9e3779b1) & ((1 << k_hop) - 1)
+            assert got[skew + u * block: skew + (u + 1) * block].tobytes() == h[b * block:(b + 1) * block].tobytes()
+    # the scatter direction writes only inside the hopping side's blocks; read-only writes nothing
+    K.kvl_ceiling_kernel(K.KVL_CEILING_READ, dense[:payload + 128], hop[:(1 << k_hop) * block], payload,
+                         block_bytes=block, hopping_side=1, skew_bytes=skew, hop_blocks_log2=k_hop)
+    torch.cuda.synchronize()
+    assert torch.equal(hop, hop0)
+    K.kvl_ceiling_kernel(K.KVL_CEILING_COPY, dense[:payload + 128], hop[:(1 << k_hop) * block], payload,
+                         block_bytes=block, hopping_side=1, skew_bytes=skew, hop_blocks_log2=k_hop, block_table=table)
+    torch.cuda.synchronize()
+    assert torch.equal(hop[(1 << k_hop) * block:], hop0[(1 << k_hop) * block:])
+    d = to_host(dense)
+    hh = to_host(hop)
+    for u in (0, 5, (1 << k_dense) - 1):
+        b = (u * 0x9e3779b1) & ((1 << k_hop) - 1)
+        assert hh[b * block:(b + 1) * block].tobytes() == d[skew + u * block: skew + (u + 1) * block].tobytes()
+    # linear modes
+    n = 1 << 20
+    a = torch.randint(0, 255, (n + 128,), dtype=torch.uint8, device="cuda")
+    b = torch.full((n + guard,), 0x3C, dtype=torch.uint8, device="cuda")
+    K.kvl_ceiling_kernel(K.KVL_CEILING_COPY, a, b[:n], n, skew_bytes=16)
+    torch.cuda.synchronize()
+    assert torch.equal(b[:n], a[16:16 + n]) and bool(torch.all(b[n:] == 0x3C))
+    K.kvl_ceiling_kernel(K.KVL_CEILING_WRITE, a, b[:n], n)
+    K.kvl_ceiling_kernel(K.KVL_CEILING_READ, a, b[:n], n)
+    torch.cuda.synchronize()
+    assert bool(torch.all(b[n:] == 0x3C))
+    with pytest.raises(K.KvlError) as e:
+        K.kvl_ceiling_kernel(K.KVL_CEILING_COPY, a, b[:n], 2 * n)
+    assert e.value.code == K.KVL_ESPACE
 
 
 def test_plans_do_not_leak_device_memory():
