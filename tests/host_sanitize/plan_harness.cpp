@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "kvl.h"
+#include "kvl_internal.h"      // launch_groups: how a launch is kept below 2^32 lanes
 
 static uint64_t rng_state = 0x9E3779B97F4A7C15ull;
 static uint32_t rnd(uint32_t n) {
@@ -102,6 +103,23 @@ int main() {
                 req[1] = save;
             }
         }
+    }
+    // launch geometry: one workgroup per tile while that fits, else (or on request) a capped grid that walks
+    {
+        bool walk = true;
+        REQUIRE(kvl::launch_groups(1000, 256, 0, &walk) == 1000 && !walk);
+        REQUIRE(kvl::launch_groups(1000, 256, 64, &walk) == 64 && walk);
+        REQUIRE(kvl::launch_groups(64, 256, 64, &walk) == 64 && !walk);
+        REQUIRE(kvl::launch_groups(10, 256, UINT32_MAX, &walk) == 10 && !walk);
+        const uint64_t most256 = ((1ull << 32) - 1) / 256, most1024 = ((1ull << 32) - 1) / 1024;
+        REQUIRE(kvl::launch_groups(most256, 256, 0, &walk) == most256 && !walk);            // 2^32 - 256 lanes: fits
+        REQUIRE(kvl::launch_groups(most256 + 1, 256, 0, &walk) == most256 && walk);         // 2^32 lanes: must walk
+        REQUIRE(kvl::launch_groups(1ull << 31, 1024, UINT32_MAX, &walk) == most1024 && walk);
+        for (uint32_t threads : {64u, 128u, 256u, 512u, 1024u})
+            for (uint64_t work : {1ull, 4194303ull, 16777216ull, 1ull << 26, (1ull << 31) - 1}) {
+                const uint32_t g = kvl::launch_groups(work, threads, 0, &walk);
+                REQUIRE((uint64_t)g * threads < (1ull << 32) && g >= 1 && (walk || g == work));
+            }
     }
     std::printf("plan harness ok\n");
     return 0;
