@@ -553,6 +553,27 @@ def short_hop(index: int, reps: int = 8, check: bool = True, linear_ceiling: flo
         out["hop_us_eager"], out["hop_us_hip_graph"] = round(res["eager"], 2), round(res["graph"], 2)
         out["hops_per_graph"] = HOPS
         del graph
+        # the same eager hops with plans whose launches are not followed by an event each
+        # (KVL_CALLER_SYNCS: the caller synchronises before it destroys them)
+        g2 = K.kvl_plan(K.make_layout(L, bs, rows, w.src.pool_blocks), w.hit, w.app, w.src.tables,
+                        K.KVL_GATHER | K.KVL_CALLER_SYNCS)
+        s2 = K.kvl_plan(K.make_layout(L, bs, rows, w.dst.pool_blocks), w.hit, w.app, w.dst.tables,
+                        K.KVL_SCATTER | K.KVL_CALLER_SYNCS)
+
+        def hops2():
+            for _ in range(HOPS):
+                K.kvl_pack_layer(g2, src, xfer, stream=stream)
+                K.kvl_unpack_layer(s2, xfer, dst, stream=stream)
+        for _ in range(5):
+            hops2()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(50):
+            hops2()
+        stream.synchronize()
+        out["hop_us_eager_caller_syncs"] = round((time.perf_counter() - t0) / (50 * HOPS) * 1e6, 2)
+        g2.destroy()
+        s2.destroy()
         out["host_buffer_load"] = small_host_buffer_load(s, dst, payload, stream)
     g.destroy()
     s.destroy()

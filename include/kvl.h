@@ -77,6 +77,10 @@ extern "C" {
                               such a plan can be inspected but not executed */
 #define KVL_NO_MERGE   8u  /* do not merge physically adjacent blocks into one run */
 #define KVL_NO_POINTER_CHECKS 64u  /* skip kvl_check_buffer on every call made with this plan */
+#define KVL_CALLER_SYNCS 128u      /* the caller promises that everything enqueued with the plan has finished
+                                      by the time it destroys the plan: launches are then not followed by an
+                                      event each (about 3 us per launch, which only shows on layers of a few
+                                      MB), and kvl_plan_destroy hands the descriptor array on at once */
 /* Which token rows of each request the plan moves.  Default: the hit prefix
  * [0, hit).  The other two serve the step after a layer's computation
  * (Section 4.1): the decode-engine read path sends on only the miss tokens'
@@ -145,16 +149,17 @@ int kvl_plan(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t
 int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, uint32_t n_req,
                    uint32_t flags, const kvl_tuning_t *tuning, kvl_plan_t **out);
 /* Frees the plan.  The call does not wait for the device: kernels enqueued with the
- * plan may still be running or queued.  Its device descriptor array is retired with
- * an event recorded on every stream the plan's kernels were enqueued on, and goes
- * back to a small cache inside the library (at most 16 buffers / 256 MiB, from which
- * later plans are served without a device allocation) only when those events have
- * fired; the streams must still exist when the plan is destroyed (if one does not,
- * the call falls back to waiting for the device).  Only the plan's own lanes, if a
- * host-buffer call left work on them that is not finished, are waited for.  A HIP
- * graph that captured calls made with the plan must not be replayed after this.
- * kvl_release_cached_memory empties the cache and the library's pool of lanes; it
- * waits for the kernels of destroyed plans, and for nothing else. */
+ * plan may still be running or queued.  Every launch made with a plan is followed by
+ * an event on its stream (one event per stream, recorded again after each launch);
+ * the plan's device descriptor array is retired with those events and goes back to a
+ * small cache inside the library (at most 16 buffers / 256 MiB, from which later
+ * plans are served without a device allocation) only when they have fired.  The
+ * streams themselves are not touched here and may be gone already.  Only the plan's
+ * own lanes, if a host-buffer call left work on them that is not finished, are
+ * waited for.  A plan whose launches were captured into a HIP graph cannot be followed
+ * that way: destroying it waits for the device, and the graph must not be replayed
+ * afterwards.  A plan made with KVL_CALLER_SYNCS is not followed at all (see there).  kvl_release_cached_memory empties the cache and the library's pool of
+ * lanes; it waits for the kernels of destroyed plans, and for nothing else. */
 void kvl_plan_destroy(kvl_plan_t *plan);
 void kvl_release_cached_memory(void);
 

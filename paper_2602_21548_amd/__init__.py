@@ -12,7 +12,7 @@ _EXPORTS = (
     "kvl_strerror", "kvl_release_cached_memory", "kvl_variant_name", "kvl_version", "LIB_PATH",
     "KVL_OK", "KVL_EINVAL", "KVL_ERANGE", "KVL_EALIAS", "KVL_ESPACE", "KVL_EHIP", "KVL_ENOMEM", "KVL_ENOSYS", "kvl_h2d_blockwise_batched_layer",
     "KVL_GATHER", "KVL_SCATTER", "KVL_HOST_ONLY", "KVL_NO_MERGE", "KVL_MAX_PLANES",
-    "KVL_TOKENS_APPEND", "KVL_TOKENS_ALL", "KVL_NO_POINTER_CHECKS", "kvl_check_buffer",
+    "KVL_TOKENS_APPEND", "KVL_TOKENS_ALL", "KVL_NO_POINTER_CHECKS", "KVL_CALLER_SYNCS", "kvl_check_buffer",
     "kvl_unpack_layer_noalloc", "KVL_NOALLOC_MAX_UNITS",
     "kvl_ceiling_kernel", "KVL_CEILING_COPY", "KVL_CEILING_READ", "KVL_CEILING_WRITE",
 )

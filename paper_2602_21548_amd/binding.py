@@ -24,6 +24,7 @@ KVL_ENOSYS = -7
 KVL_GATHER, KVL_SCATTER, KVL_HOST_ONLY, KVL_NO_MERGE = 1, 2, 4, 8
 KVL_TOKENS_APPEND, KVL_TOKENS_ALL = 16, 32
 KVL_NO_POINTER_CHECKS = 64
+KVL_CALLER_SYNCS = 128
 
 
 class KvlError(RuntimeError):

@@ -446,13 +446,7 @@ int kvl_plan_set_lane_cu_mask(kvl_plan_t *plan, const uint32_t *mask, uint32_t n
     for (hipStream_t s : plan->lanes) {
         hipError_t e = hipStreamSynchronize(s);
         if (first == hipSuccess) first = e;
-        // nothing of this plan runs on the lane any more: it need not be followed when the plan goes
-        for (size_t i = 0; i < plan->used_streams.size(); ++i) {
-            if (plan->used_streams[i] == s) {
-                plan->used_streams.erase(plan->used_streams.begin() + (long)i);
-                break;
-            }
-        }
+        // (the event recorded after the lane's last launch has fired by now and stays with the plan)
         if (poolable) {
             kvl::return_lane(s, plan->device);
         } else {

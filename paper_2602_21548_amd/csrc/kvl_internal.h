@@ -27,10 +27,13 @@ struct kvl_plan_s {
     kvl_unit_t *d_units = nullptr;               // device copy (absent for KVL_HOST_ONLY)
     size_t d_units_capacity = 0;                 // bytes of the cached buffer d_units lives in
     int device = -1;
-    // streams on which kernels that read d_units were enqueued (the caller's and the lanes):
-    // the buffer may be handed to another plan once each of them has got past that work
-    mutable std::vector<hipStream_t> used_streams;
-    mutable bool used_streams_overflow = false;  // more distinct streams than are tracked: wait for the device instead
+    // One event per stream on which kernels that read d_units were enqueued (the caller's streams and
+    // the lanes), re-recorded after every such launch: once all of them have fired no kernel reads the
+    // buffer any more and it may be handed to another plan.  Recorded at launch time because a stream
+    // of the caller's may be gone by the time the plan is destroyed.
+    mutable std::vector<std::pair<hipStream_t, hipEvent_t>> stream_events;
+    mutable bool untracked_use = false;          // a launch could not be followed (too many streams, a stream
+                                                 // under capture, a failed record): wait for the device instead
     kvl_tuning_t tuning{};                       // resolved (no zero fields)
     // h2d path: one lane (a stream of the library's own) and one "lane done" event per staging slot
     std::vector<hipStream_t> lanes;
@@ -85,8 +88,9 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
 bool is_host_memory(const kvl_plan_t *plan, const void *ptr);
 
 int upload_units(kvl_plan_t *plan);
-// remember that a kernel reading the plan's descriptors was enqueued on `stream`
-void note_stream(const kvl_plan_t *plan, hipStream_t stream);
+// a kernel reading the plan's descriptors has just been enqueued on `stream`
+void mark_launch(const kvl_plan_t *plan, hipStream_t stream);
+void drop_stream_events(const kvl_plan_t *plan);
 // lanes come from, and go back to, a small pool shared by all plans
 hipStream_t take_pooled_lane(int device);
 void return_lane(hipStream_t lane, int device);

@@ -157,7 +157,6 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
     }
     int rc_dev = check_device(plan);
     if (rc_dev != KVL_OK) return rc_dev;
-    note_stream(plan, stream);
     CopyArgs a{};
     a.units = plan->d_units;
     a.unit_begin = unit_begin;
@@ -259,6 +258,7 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
             if (pack) launch_pipe_variant<true>(v, grid, block, stream, a, (uint32_t)tpu, al, (uint32_t)blocks);
             else launch_pipe_variant<false>(v, grid, block, stream, a, (uint32_t)tpu, al, (uint32_t)blocks);
             KVL_HIP(hipGetLastError());
+            mark_launch(plan, stream);
             return KVL_OK;
         }
         // one workgroup per tile, unless a cap was asked for or the launch would not fit
@@ -281,6 +281,7 @@ int launch_units(const kvl_plan_t *plan, bool pack, uint32_t unit_begin, uint32_
         else launch_span_variant<false>(v, grid, block, stream, a);
     }
     KVL_HIP(hipGetLastError());
+    mark_launch(plan, stream);
     return KVL_OK;
 }
 
@@ -303,7 +304,6 @@ int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint6
         vec = vec && reinterpret_cast<uintptr_t>(pool_planes[p]) % 16 == 0;
     }
     const uint64_t e = vec ? 16 : 1;          // element size
-    note_stream(plan, stream);
     FullBlockArgs a{};
     a.units = plan->d_units + unit_begin;
     a.n_units = unit_end - unit_begin;
@@ -341,6 +341,7 @@ int fullblock_launch(const kvl_plan_t *plan, bool to_pool, uintptr_t base, uint6
     }
 #undef KVL_FB_LAUNCH
     KVL_HIP(hipGetLastError());
+    mark_launch(plan, stream);
     return KVL_OK;
 }
 

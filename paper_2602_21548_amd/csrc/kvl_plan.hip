@@ -70,7 +70,7 @@ std::vector<std::pair<hipEvent_t, int>> g_events;       // spare events, with th
 std::vector<PooledLane> g_lanes;
 constexpr size_t kCacheEntries = 16;
 constexpr size_t kCacheBytes = 256u << 20;      // never keep more than this much idle
-constexpr size_t kSpareEvents = 64;
+constexpr size_t kSpareEvents = 256;
 constexpr size_t kPooledLanes = 16;
 constexpr size_t kTrackedStreams = 24;
 
@@ -89,8 +89,10 @@ hipEvent_t take_event(int device) {
             return e;
         }
     }
+    // The events only say "the kernels before this point have finished": no timing, and no
+    // system-scope cache flush when they fire (nothing is read back through them).
     hipEvent_t e = nullptr;
-    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) {
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventDisableSystemFence) != hipSuccess) {
         (void)hipGetLastError();
         return nullptr;
     }
@@ -146,18 +148,55 @@ void reap_retired(bool wait) {
 }
 }  // namespace
 
-void note_stream(const kvl_plan_t *plan, hipStream_t stream) {
-    for (hipStream_t s : plan->used_streams)
-        if (s == stream) return;
-    if (plan->used_streams.size() >= kTrackedStreams) {
-        plan->used_streams_overflow = true;
+void mark_launch(const kvl_plan_t *plan, hipStream_t stream) {
+    if (plan->flags & KVL_CALLER_SYNCS) return;            // the caller answers for the plan's lifetime
+    // a launch that is being captured into a graph runs whenever the graph is replayed: not ours to follow
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capture) != hipSuccess) {
+        (void)hipGetLastError();
+        plan->untracked_use = true;
         return;
     }
-    try {
-        plan->used_streams.push_back(stream);
-    } catch (const std::bad_alloc &) {
-        plan->used_streams_overflow = true;
+    if (capture != hipStreamCaptureStatusNone) {
+        plan->untracked_use = true;
+        return;
     }
+    hipEvent_t ev = nullptr;
+    for (const auto &se : plan->stream_events)
+        if (se.first == stream) ev = se.second;
+    if (!ev) {
+        if (plan->stream_events.size() >= kTrackedStreams) {
+            plan->untracked_use = true;
+            return;
+        }
+        {
+            std::lock_guard<std::mutex> lock(g_cache_mutex);
+            ev = take_event(plan->device);
+        }
+        if (!ev) {
+            plan->untracked_use = true;
+            return;
+        }
+        try {
+            plan->stream_events.emplace_back(stream, ev);
+        } catch (const std::bad_alloc &) {
+            std::lock_guard<std::mutex> lock(g_cache_mutex);
+            give_event(ev, plan->device);
+            plan->untracked_use = true;
+            return;
+        }
+    }
+    if (hipEventRecord(ev, stream) != hipSuccess) {
+        (void)hipGetLastError();
+        plan->untracked_use = true;
+    }
+}
+
+void drop_stream_events(const kvl_plan_t *plan) {
+    if (plan->stream_events.empty()) return;
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    for (const auto &se : plan->stream_events) give_event(se.second, plan->device);
+    plan->stream_events.clear();
 }
 
 hipStream_t take_pooled_lane(int device) {
@@ -207,47 +246,41 @@ static hipError_t descriptor_alloc(void **out, size_t bytes, size_t *capacity, i
     return hipMalloc(out, want);
 }
 
-// The plan is going away: its descriptor array may be reused once every stream that ran its
-// kernels has got past them.
+// The plan is going away: its descriptor array may be reused once the events recorded after its
+// launches have fired.  No stream is touched here.
 static void descriptor_release(const kvl_plan_t *plan) {
-    int current = plan->device;
-    (void)hipGetDevice(&current);
-    if (current != plan->device) (void)hipSetDevice(plan->device);
     RetiredBuffer r{CachedBuffer{plan->d_units, plan->d_units_capacity, plan->device}, {}};
-    bool tracked = !plan->used_streams_overflow;
+    if (plan->flags & KVL_CALLER_SYNCS) {
+        std::lock_guard<std::mutex> lock(g_cache_mutex);
+        keep_or_free(r.buf);
+        return;
+    }
+    bool tracked = !plan->untracked_use;
     {
         std::lock_guard<std::mutex> lock(g_cache_mutex);
-        try {
-            for (size_t i = 0; tracked && i < plan->used_streams.size(); ++i) {
-                hipEvent_t e = take_event(plan->device);
-                if (!e) {
-                    tracked = false;
-                    break;
-                }
-                r.events.push_back(e);
-                if (hipEventRecord(e, plan->used_streams[i]) != hipSuccess) {
-                    (void)hipGetLastError();        // e.g. a stream the caller has destroyed since
-                    tracked = false;
-                }
-            }
-            if (tracked) {
+        if (tracked) {
+            try {
+                for (const auto &se : plan->stream_events) r.events.push_back(se.second);
                 g_retired.push_back(std::move(r));
-                r.events.clear();
                 r.buf.ptr = nullptr;
+            } catch (const std::bad_alloc &) {
+                tracked = false;
             }
-        } catch (const std::bad_alloc &) {
-            tracked = false;
         }
-        if (!tracked)
-            for (hipEvent_t e : r.events) give_event(e, plan->device);
+        if (r.buf.ptr)
+            for (const auto &se : plan->stream_events) give_event(se.second, plan->device);
     }
+    plan->stream_events.clear();
     if (r.buf.ptr) {
-        // the streams could not be followed: fall back to what a device free would have done
+        // some launch could not be followed: fall back to what a device free would have done
+        int current = plan->device;
+        (void)hipGetDevice(&current);
+        if (current != plan->device) (void)hipSetDevice(plan->device);
         (void)hipDeviceSynchronize();
+        if (current != plan->device) (void)hipSetDevice(current);
         std::lock_guard<std::mutex> lock(g_cache_mutex);
         keep_or_free(r.buf);
     }
-    if (current != plan->device) (void)hipSetDevice(current);
 }
 
 int check_buffer(const kvl_plan_t *plan, const void *ptr, uint64_t bytes, bool allow_host) {
@@ -335,7 +368,7 @@ static int build(const kvl_layout_t *layout, const kvl_request_t *req, uint32_t 
     *out = nullptr;
     if (!(flags & (KVL_GATHER | KVL_SCATTER))) return KVL_EINVAL;
     if (flags & ~(KVL_GATHER | KVL_SCATTER | KVL_HOST_ONLY | KVL_NO_MERGE | KVL_TOKENS_APPEND | KVL_TOKENS_ALL |
-                  KVL_NO_POINTER_CHECKS))
+                  KVL_NO_POINTER_CHECKS | KVL_CALLER_SYNCS))
         return KVL_EINVAL;
     if ((flags & KVL_TOKENS_APPEND) && (flags & KVL_TOKENS_ALL)) return KVL_EINVAL;
     if (layout->block_tokens == 0 || layout->n_planes == 0 || layout->n_planes > KVL_MAX_PLANES)
@@ -569,6 +602,7 @@ int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, ui
 void kvl_plan_destroy(kvl_plan_t *plan) {
     if (!plan) return;
     if (plan->d_units) kvl::descriptor_release(plan);
+    kvl::drop_stream_events(plan);          // of a plan that never owned a descriptor array
     for (hipStream_t s : plan->lanes) {
         // the lanes' work on this plan has normally ended (the stream the caller waits on follows
         // them); one that is still busy is waited for, it alone, since the plan's events go below
@@ -598,7 +632,7 @@ int kvl_plan_pair(const kvl_plan_t *g, const kvl_plan_t *s, kvl_plan_t **out) {
     if (!plan) return KVL_ENOMEM;
     plan->layout = a;
     plan->dst_pool_blocks = b.pool_blocks;
-    plan->flags = KVL_GATHER | ((g->flags | s->flags) & KVL_HOST_ONLY);
+    plan->flags = KVL_GATHER | ((g->flags | s->flags) & KVL_HOST_ONLY) | (g->flags & s->flags & KVL_CALLER_SYNCS);
     plan->paired = true;
     plan->n_req = g->n_req;
     plan->hit_tokens = g->hit_tokens;

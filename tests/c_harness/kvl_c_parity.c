@@ -509,6 +509,28 @@ int main(int argc, char **argv) {
         HIP_OK(hipStreamDestroy(ms));
     }
 
+    /* --- a plan outlives a stream it was used on: kvl_plan_destroy follows the streams its kernels ran
+     * on, and one that no longer exists must not trip it (it then waits for the device instead) --- */
+    {
+        kvl_plan_t *g2 = NULL;
+        hipStream_t gone;
+        expect(kvl_plan(&lay, src_req, R, KVL_GATHER, &g2), KVL_OK, "kvl_plan (for a stream that will be destroyed)");
+        HIP_OK(hipStreamCreateWithFlags(&gone, hipStreamNonBlocking));
+        HIP_OK(hipMemset(d_xfer, 0, payload));
+        expect(kvl_pack_layer(g2, (const void *const *)d_src, d_xfer, payload, gone), KVL_OK, "kvl_pack_layer on that stream");
+        HIP_OK(hipStreamSynchronize(gone));
+        HIP_OK(hipStreamDestroy(gone));
+        kvl_plan_destroy(g2);
+        (void)hipGetLastError();
+        HIP_OK(hipMemcpy(got_xfer, d_xfer, payload, hipMemcpyDeviceToHost));
+        expect(memcmp(got_xfer, want_xfer, payload) == 0, 1, "plan destroyed after its stream: result intact, no error left behind");
+        kvl_plan_t *g3 = NULL;                       /* and the library still works */
+        expect(kvl_plan(&lay, src_req, R, KVL_GATHER, &g3), KVL_OK, "kvl_plan after that");
+        expect(kvl_pack_layer(g3, (const void *const *)d_src, d_xfer, payload, ks), KVL_OK, "kvl_pack_layer after that");
+        HIP_OK(hipStreamSynchronize(ks));
+        kvl_plan_destroy(g3);
+    }
+
     kvl_plan_destroy(g);
     kvl_plan_destroy(s);
     kvl_release_cached_memory();

@@ -840,6 +840,8 @@ def test_destroying_a_plan_does_not_wait_for_the_device():
     # right after must not get its descriptor array (their descriptors differ)
     g = dev_plan(w, "src", K.KVL_GATHER)
     x.zero_()
+    y = torch.zeros_like(x)
+    torch.cuda.synchronize()                      # the fills above ran on the default stream
     with torch.cuda.stream(side):
         torch.cuda._sleep(spin_cycles)
     K.kvl_pack_layer(g, d_src, x, stream=side)
@@ -847,7 +849,6 @@ def test_destroying_a_plan_does_not_wait_for_the_device():
     other = W.config(3, n_requests=12, token_scale=1 / 16)
     other.src.tables = [t[::-1].copy() for t in other.src.tables]       # same sizes, other descriptors
     plans = [dev_plan(other, "src", K.KVL_GATHER) for _ in range(4)]
-    y = torch.zeros_like(x)
     K.kvl_pack_layer(plans[0], d_src, y, stream=busy)
     torch.cuda.synchronize()
     assert same_bytes(to_host(x), want_x), "a retired descriptor array was reused before its kernel had run"
@@ -867,6 +868,33 @@ def test_destroying_a_plan_does_not_wait_for_the_device():
     K.kvl_release_cached_memory()
     free1, _ = torch.cuda.mem_get_info()
     assert free0 - free1 < (8 << 20), f"{(free0 - free1) >> 20} MiB of device memory gone"
+
+
+def test_plans_whose_caller_answers_for_their_lifetime():
+    """KVL_CALLER_SYNCS: no event after each launch, the descriptor array goes back at once."""
+    w = W.config(3, n_requests=12, token_scale=1 / 16)
+    bs, rows = w.layout.block_tokens, w.layout.row_bytes
+    src = W.fill_pool(w, 1, "src")
+    want_x = oracle.pack(bs, rows, w.hit, w.src.tables, src, threads=8)
+    want_dst = W.sentinel_pool(w, "dst")
+    oracle.unpack(bs, rows, w.hit, w.dst.tables, want_x, want_dst, threads=8)
+    d_src = planes_to_dev(src)
+    for _ in range(3):
+        g = dev_plan(w, "src", K.KVL_GATHER | K.KVL_CALLER_SYNCS)
+        s = dev_plan(w, "dst", K.KVL_SCATTER | K.KVL_CALLER_SYNCS)
+        m = K.kvl_plan_pair(g, s)
+        x = torch.zeros(g.payload_bytes, dtype=torch.uint8, device="cuda")
+        d_dst = planes_to_dev(W.sentinel_pool(w, "dst"))
+        d_dst2 = planes_to_dev(W.sentinel_pool(w, "dst"))
+        K.kvl_pack_layer(g, d_src, x)
+        K.kvl_unpack_layer(s, x, d_dst)
+        K.kvl_move_layer(m, d_src, d_dst2)
+        torch.cuda.synchronize()                       # the promise the flag makes
+        for p in (g, s, m):
+            p.destroy()
+        assert same_bytes(to_host(x), want_x)
+        for a, b, c in zip(d_dst, d_dst2, want_dst):
+            assert same_bytes(to_host(a), c) and same_bytes(to_host(b), c)
 
 
 def test_ceiling_kernels_stay_inside_their_buffers():
