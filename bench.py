@@ -200,7 +200,9 @@ def main() -> int:
             K.kvl_unpack_layer(s, xfer, dst[l % WIN], stream=stream)
             if events is not None:
                 events[l][2].record(stream)
-        stream.synchronize()
+        # no synchronisation here: destroying a plan does not wait for the device, so the host
+        # goes on to plan the next batch while this one's kernels run (the timed region as a
+        # whole is bracketed by device-wide synchronisations)
         g.destroy()
         s.destroy()
 
@@ -262,7 +264,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": WORKLOADS[args.config], "layers": L, "requests": w.n_requests,
                    "hit_tokens": T, "payload_bytes_per_layer": payload, "descriptors": n_units,
-                   "step": f"kvl_plan x2 + {L} x (kvl_pack_layer + kvl_unpack_layer), inputs resident in HBM",
+                   "step": f"kvl_plan x2 + {L} x (kvl_pack_layer + kvl_unpack_layer), inputs resident in HBM; "
+                           "the host plans batch k+1 while the kernels of batch k run",
                    "resident_layer_window": WIN},
         "roofline": dominant, "roofline_other": other,
         "pack_payload_gbps": round(payload / (pack_ms.mean() * 1e-3) / 1e9, 1),

@@ -71,7 +71,8 @@ int kvl_unpack_layer_noalloc(const kvl_layout_t *layout, const kvl_request_t *re
     if (flags & ~(KVL_NO_MERGE | KVL_TOKENS_APPEND | KVL_TOKENS_ALL | KVL_NO_POINTER_CHECKS)) return KVL_EINVAL;
     // descriptors on the host: validation, layout and run merging are those of kvl_plan
     kvl_plan_t *plan = nullptr;
-    int rc = kvl_plan(layout, requests, n_req, flags | KVL_SCATTER | KVL_HOST_ONLY, &plan);
+    // (KVL_CALLER_SYNCS: the kernels are followed by this file's own event, not by the plan's)
+    int rc = kvl_plan(layout, requests, n_req, flags | KVL_SCATTER | KVL_HOST_ONLY | KVL_CALLER_SYNCS, &plan);
     if (rc != KVL_OK) return rc;
     const size_t n_units = plan->units.size();
     if (n_units > kMaxUnits) rc = KVL_ESPACE;                    // the fixed array cannot hold this batch
