@@ -785,6 +785,13 @@ void kvl_release_cached_memory(void) {
         (void)hipStreamDestroy(l.stream);
     }
     for (const auto &e : events) (void)hipEventDestroy(e.first);
+    // the upload streams and their pinned staging buffers come back on the next plan
+    std::lock_guard<std::mutex> lock(kvl::g_upload_mutex);
+    for (kvl::Uploader &u : kvl::g_uploaders) {
+        if (u.bounce) (void)hipHostFree(u.bounce);
+        if (u.stream) (void)hipStreamDestroy(u.stream);
+        u = kvl::Uploader{};
+    }
 }
 
 const char *kvl_strerror(int code) {

@@ -334,6 +334,83 @@ def test_de_fetch_invariants_and_library(seed):
     assert (lt.tolist(), ls.tolist(), lf.tolist()) == (tok, seq, free)
 
 
+# Cases worked by hand from Section 6.1 ("DE Scheduling Phase 2"): R is the head of the queue that fits the group's
+# free HBM taken as one piece; Z = 1.05 (sum of R's lengths + sum of tok) / |E|; among the engines with room for the
+# request those with tok + len <= Z come first and the one with the fewest requests is taken, otherwise the one with
+# the smallest tok; the fetch ends at the first request no engine has room for.
+# (tok, seq, free_hbm, Q, expected assignment, expected Z)
+DE_HAND_CASES = [
+    # engine 0 would go over Z = 78.75, so the request goes to engine 1 although that one holds more requests
+    ([100, 0], [1, 5], [1000, 1000], [50], [1], 78.75),
+    # both over Z = 126: the smaller tok wins
+    ([100, 90], [1, 5], [1000, 1000], [50], [1], 126.0),
+    # the group's free HBM as one piece would hold the request (so it is in R), but no engine does: the fetch ends
+    ([0, 0], [0, 0], [40, 45], [50], [-1], 26.25),
+    # a lone request on idle engines is over Z = 3.5 everywhere: smallest tok, lowest index
+    ([0, 0, 0], [3, 1, 2], [100, 100, 100], [10], [0], 3.5),
+    # six equal requests, Z = 21: fewest requests first, an engine drops to the other class once it holds two
+    ([0, 0, 0], [3, 1, 2], [100, 100, 100], [10] * 6, [1, 1, 2, 0, 2, 0], 21.0),
+    # R holds three requests (60 tokens free in all) but fragmentation lets only two in
+    ([0, 0], [0, 0], [30, 30], [20, 20, 20, 20], [0, 1, -1, -1], 31.5),
+    # Z = 89.25: under-threshold first (engine 1, then 0), then both over and the smaller tok
+    ([50, 0], [0, 9], [100, 100], [60, 30, 30], [1, 0, 1], 89.25),
+    # only engine 1 has room for the first request; it is over Z but the only choice
+    ([10, 10], [2, 2], [15, 100], [20, 5], [1, 0], 23.625),
+    # engine 1 lands exactly on Z = 35: that is not over it, and it has fewer requests than engine 0
+    ([5, 15, 60], [9, 1, 0], [100, 100, 100], [20], [1], 35.0),
+]
+
+
+@pytest.mark.parametrize("case", DE_HAND_CASES, ids=[str(i) for i in range(len(DE_HAND_CASES))])
+def test_de_fetch_hand_cases(case):
+    tok0, seq0, free0, Q, want, want_z = case
+    tok, seq, free = list(tok0), list(seq0), list(free0)
+    got, Z = O.de_fetch(tok, seq, free, Q)
+    assert got == want and Z == pytest.approx(want_z, rel=1e-12)
+    placed = [(e, n) for e, n in zip(got, Q) if e >= 0]
+    assert sum(tok) == sum(tok0) + sum(n for _, n in placed) and sum(free) == sum(free0) - sum(n for _, n in placed)
+    lib, lib_z, lt, ls, lf = S.kvl_sched_de_fetch(tok0, seq0, free0, Q)
+    assert lib == want and lib_z == pytest.approx(want_z, rel=1e-12)
+    assert (lt.tolist(), ls.tolist(), lf.tolist()) == (tok, seq, free)
+
+
+DE_MUTANTS = [
+    ("threshold factor 1.5", "Z = 1.05 * (sum(R) + sum(tok)) / len(tok)", "Z = 1.5 * (sum(R) + sum(tok)) / len(tok)"),
+    ("Z ignores the queued requests", "Z = 1.05 * (sum(R) + sum(tok)) / len(tok)", "Z = 1.05 * sum(tok) / len(tok)"),
+    ("R is the whole queue", "        if used + len_r > total_free:\n            break", "        if False:\n            break"),
+    ("at Z counts as over", "high = [e for e in fits if tok[e] + len_r > Z]\n        rest = [e for e in fits if not tok[e] + len_r > Z]",
+     "high = [e for e in fits if tok[e] + len_r >= Z]\n        rest = [e for e in fits if not tok[e] + len_r >= Z]"),
+    ("under-threshold class by tok", "de = min(rest, key=lambda e: (seq[e], e))", "de = min(rest, key=lambda e: (tok[e], e))"),
+    ("over-threshold class by seq", "de = min(high, key=lambda e: (tok[e], e))", "de = min(high, key=lambda e: (seq[e], e))"),
+    ("over-threshold engines first", "        if rest:\n            de = min(rest", "        if not high:\n            de = min(rest"),
+    ("room is not checked", "fits = [e for e in E if free_hbm[e] >= len_r]", "fits = [e for e in E]"),
+    ("free HBM not reduced", "        free_hbm[de] -= len_r", "        free_hbm[de] -= 0"),
+    ("request count not updated", "        seq[de] += 1", "        seq[de] += 0"),
+]
+
+
+def _de_battery(fetch):
+    for tok0, seq0, free0, Q, want, want_z in DE_HAND_CASES:
+        got, Z = fetch(list(tok0), list(seq0), list(free0), Q)
+        if got != want or abs(Z - want_z) > 1e-9:
+            return 1
+    return 0
+
+
+@pytest.mark.parametrize("name,old,new", DE_MUTANTS, ids=[m[0] for m in DE_MUTANTS])
+def test_planted_mistake_in_decode_phase_2_is_caught(name, old, new):
+    src = open(O.__file__).read()
+    assert src.count(old) >= 1, "mutation pattern no longer matches the oracle source"
+    scope = {"__name__": "sched_oracle_mutant"}
+    exec(compile(src.replace(old, new), "sched_oracle_mutant.py", "exec"), scope)
+    assert _de_battery(O.de_fetch) == 0
+    try:
+        rc = _de_battery(scope["de_fetch"])
+    except (ValueError, IndexError, AssertionError, ZeroDivisionError):
+        rc = 1
+    assert rc != 0, f"no hand case noticed: {name}"
+
+
 def test_read_side():
     for a, b in ((0, 0), (5, 9), (9, 5), (7, 7)):
         want = O.read_side(a, b)
