@@ -15,8 +15,10 @@ floor(beta / size) + 1 requests, in round-robin order), by the textbook special 
 it reduces to without limits (greedy list scheduling onto the least loaded machine),
 by a checker that replays a finished fetch against the sentences of the text, by a
 two-heap simulation of different structure, and by mistakes planted in copies of this
-file.  The decode rules are pinned by the invariants the text states and the stated
-formula for Z -- parity with the paper's own implementation is unpinned.
+file.  The second decode phase is pinned by hand-worked cases (the threshold Z, its two
+categories, fragmentation against the set R, an engine exactly at Z), by the invariants the
+text states, and by planted mistakes; the first phase by its arg-min invariant -- parity with
+the paper's own implementation is unpinned (it prints no example).
 
 Readings.  Algorithm 1: the three categories are defined by tok_e, and tok_e of the
 chosen engine is updated after every assignment, so an engine whose unfinished tokens

@@ -46,9 +46,10 @@ int make_chunks(const kvl_plan_t *plan, uint64_t chunk_bytes, std::vector<kvl_ch
 // Descriptor arrays come from a small per-process cache, so that a caller who builds a plan
 // per batch pays neither a device allocation nor a device free (both synchronise the device,
 // and a free can stall the next launch for tens of milliseconds).  A destroyed plan's array is
-// retired, not freed: an event is recorded on every stream that ran kernels reading it, and the
-// array goes back to the cache only when those events have fired.  Nothing here waits for the
-// device; only kvl_release_cached_memory blocks (on the retired arrays' own events).
+// retired, not freed: every launch that reads it is followed by an event on its stream (one event
+// per stream, recorded again after each launch), and the array goes back to the cache only when
+// those events have fired.  Nothing here waits for the device; only kvl_release_cached_memory
+// blocks (on the retired arrays' own events).
 namespace {
 struct CachedBuffer {
     void *ptr;
