@@ -906,7 +906,8 @@ def ceilings_leg(stream, roof_pack: dict, roof_unpack: dict, config_index: int) 
     its read and write halves alone (4 GiB), and a copy with the access shape of cfg4 -- one
     side dense, the other hopping every 41,984 bytes to a pseudo-random block, the two sides 16
     bytes apart in their 128-byte lines -- with the block's address computed, or read from a
-    4-byte table entry through the scalar cache as a descriptor is."""
+    4-byte table entry through the scalar cache as a descriptor is; and that last form once more with
+    every hop kept within 16 neighbouring blocks, which shows what the distance of the hops costs."""
     import torch
     import paper_2602_21548_amd as K
     dev = torch.device("cuda:0")
@@ -940,6 +941,16 @@ def ceilings_leg(stream, roof_pack: dict, roof_unpack: dict, config_index: int) 
                                                              hopping_side=side, skew_bytes=skew, hop_blocks_log2=k_hop,
                                                              block_table=tab, stream=stream), stream)
             shape[f"{name}_{tname}"] = round(2.0 * payload / ms / 1e6, 1)
+    # the same copy with the hops kept local: the blocks of every 16 consecutive ones (0.7 MB) are
+    # permuted among themselves, so only how far a hop goes differs from the table above
+    u = torch.arange(1 << k_dense, dtype=torch.int64, device=dev)
+    near = ((u // 16) * 16 + (u % 16) * 5 % 16).to(torch.int32)
+    for side, name, src, dst in ((0, "gather", hop, dense), (1, "scatter", dense, hop)):
+        ms = _time_launches(lambda: K.kvl_ceiling_kernel(K.KVL_CEILING_COPY, src, dst, payload, block_bytes=block,
+                                                         hopping_side=side, skew_bytes=skew, hop_blocks_log2=k_hop,
+                                                         block_table=near, stream=stream), stream)
+        shape[f"{name}_table_entry_hops_within_16_blocks"] = round(2.0 * payload / ms / 1e6, 1)
+    del u, near
     out["shape_of_cfg4"] = shape
     if config_index == 4:
         best_g = max(shape["gather_computed_address"], shape["gather_table_entry_per_block"])

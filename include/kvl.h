@@ -158,8 +158,9 @@ int kvl_plan_tuned(const kvl_layout_t *layout, const kvl_request_t *requests, ui
  * own lanes, if a host-buffer call left work on them that is not finished, are
  * waited for.  A plan whose launches were captured into a HIP graph cannot be followed
  * that way: destroying it waits for the device, and the graph must not be replayed
- * afterwards.  A plan made with KVL_CALLER_SYNCS is not followed at all (see there).  kvl_release_cached_memory empties the cache and the library's pool of
- * lanes; it waits for the kernels of destroyed plans, and for nothing else. */
+ * afterwards.  A plan made with KVL_CALLER_SYNCS is not followed at all (see there).
+ * kvl_release_cached_memory empties the cache and the library's pool of lanes; it
+ * waits for the kernels of destroyed plans, and for nothing else. */
 void kvl_plan_destroy(kvl_plan_t *plan);
 void kvl_release_cached_memory(void);
 

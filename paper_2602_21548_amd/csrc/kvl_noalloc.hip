@@ -23,9 +23,11 @@ constexpr int kMaxDevices = 64;
 // returned, never the name.
 static __device__ __align__(256) kvl_unit_t scratch[kMaxUnits];
 
-// Host-side staging for the upload.  Reused by every call, so a call first waits for the
-// previous upload out of it to finish.
+// Host-side staging for the upload.  Reused by every call on every device, so a call first waits
+// for the previous upload out of it (g_bounce_busy: the event that follows that upload, on whichever
+// device it ran) to finish.
 static kvl_unit_t g_bounce[kMaxUnits];
+static hipEvent_t g_bounce_busy = nullptr;
 
 struct DeviceState {
     kvl_unit_t *units = nullptr;       // device address of `scratch` on this GPU
@@ -109,12 +111,16 @@ int kvl_unpack_layer_noalloc(const kvl_layout_t *layout, const kvl_request_t *re
             // the staging array is free once the previous upload has left it, the device array once
             // the previous call's kernels (on whatever stream they ran) have finished
             // (an event that was never recorded counts as finished)
-            bool ok = hip(hipEventSynchronize(d->uploaded));
+            bool ok = !g_bounce_busy || hip(hipEventSynchronize(g_bounce_busy));
             if (ok) {
                 std::memcpy(g_bounce, plan->units.data(), bytes);
                 ok = hip(hipStreamWaitEvent(s, d->kernels_done, 0)) &&
-                     hip(hipMemcpyAsync(d->units, g_bounce, bytes, hipMemcpyHostToDevice, s)) &&
-                     hip(hipEventRecord(d->uploaded, s));
+                     hip(hipMemcpyAsync(d->units, g_bounce, bytes, hipMemcpyHostToDevice, s));
+                if (ok) {
+                    g_bounce_busy = d->uploaded;
+                    ok = hip(hipEventRecord(d->uploaded, s));
+                    if (!ok) (void)hipStreamSynchronize(s);      // nothing follows the upload: wait for it here
+                }
             }
             if (ok) {
                 plan->d_units = d->units;            // borrowed: taken back before the plan is destroyed
