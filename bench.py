@@ -986,7 +986,11 @@ def kernel_shapes_leg(index: int = 3) -> dict:
              ("one workgroup per descriptor, 4 vectors in flight per lane", 21, 29),
              ("tiled, two vectors per lane", 24, 32),
              ("pipelined walk on a fixed grid of resident workgroups", 279, 287)]
-    out = {"workload": WORKLOADS[index], "unit": "GB/s of memory traffic", "forms": []}
+    out = {"workload": WORKLOADS[index], "unit": "GB/s of memory traffic",
+           "note": "every launch is timed alone, the device idle before it and the same kernel run again and again on the same "
+                   "buffers: rates for comparing the forms with each other; the rates of the load path itself, with pack and "
+                   "unpack alternating and no idle time, are those under other_configs (a few per cent higher)",
+           "forms": []}
     for name, vp, vu in forms:
         g.set_tuning(variant=vp)
         s.set_tuning(variant=vu)
